@@ -1,0 +1,181 @@
+/*
+ * dab.h - C ABI of the MI355X (gfx950) hot path of distribution-aware
+ * binarization, after "Distribution-Aware Binarization of Neural Networks for
+ * Sketch Recognition" (arXiv 1804.02941).
+ *
+ * The path: a layer's real-valued filters W_f (n = c*w*h weights each) are
+ * replaced by W~_f = alpha_f*e_f + beta_f*(1 - e_f) with a 0/1 mask e_f
+ * (Section 4.1, Theorem 2); the mask comes from a split of the sorted weights
+ * found with prefix sums (Section 4.3.1, Algorithm 1); inputs of the layer are
+ * binary, +1 / -1 (Section 4); the layer output is the ordinary convolution of
+ * the binary input with W~ (Section 4.3.2).  With A = [a = +1] and E = e as
+ * bit vectors, sum_i a_i e_i = 2*popc(A & E) - popc(E) over the taps inside
+ * the image, so every output needs one AND + popcount per 32 inputs and the
+ * two scalars recombine the counts:
+ *     y = alpha*s1 + beta*s2,  s1 = sum a_i e_i,  s2 = sum a_i (1 - e_i).
+ *
+ * General rules
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *     The caller owns every buffer; the library allocates nothing, keeps no
+ *     state between calls and never frees or retains a pointer.
+ *   - "stream" is a hipStream_t passed as void* (NULL = the null stream).
+ *     Work is enqueued on it and the call returns without synchronising.
+ *   - Every call returns a dab_status.  Arguments are validated on the host
+ *     before anything is enqueued; on any status other than DAB_OK nothing was
+ *     launched.  Launch failures give DAB_ERR_HIP and the hipError_t is kept
+ *     for dab_last_hip_error().  Faults inside a kernel surface at the
+ *     caller's next synchronisation, as with any HIP work.
+ *   - Float buffers are fp32, 4-byte aligned; packed buffers and Y are
+ *     16-byte aligned (DAB_ERR_ALIGN otherwise).
+ *   - Inputs must be finite.  A NaN activation binarizes to -1 (x >= tau is
+ *     false); NaN weights give unspecified masks.
+ *
+ * Packed layouts (bit k of a word = (word >> k) & 1, least significant first)
+ *   Activations  uint32 [B][H][W][Cw], Cw = ceil(C/32).  Bit (c mod 32) of
+ *                word (c div 32) of pixel (b,h,w) is 1 iff a[b,c,h,w] = +1.
+ *                Bits past C are 0.  A fully-connected input is H = W = 1.
+ *   Weights      uint32 [R][Fp], R = kh*kw*Cw, Fp = 64*ceil(F/64).  Row
+ *                r = (ky*kw + kx)*Cw + (c div 32), column f, bit (c mod 32) is
+ *                e[f,c,ky,kx].  Bits past C and columns past F are 0.
+ *                (Word-major so that one wavefront-uniform fetch brings the
+ *                same reduction word of 16 consecutive filters.)
+ *   Tap counts   uint32 [F][kh*kw]: ecnt[f][ky*kw+kx] = sum_c e[f,c,ky,kx].
+ */
+#ifndef DAB_H
+#define DAB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dab_status {
+    DAB_OK = 0,
+    DAB_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    DAB_ERR_SHAPE = 2,       /* a size is non-positive, n < 2, or the output empty  */
+    DAB_ERR_ALIGN = 3,       /* a buffer is not aligned as stated above             */
+    DAB_ERR_WORKSPACE = 4,   /* ws is NULL or smaller than the *_workspace_bytes    */
+    DAB_ERR_UNSUPPORTED = 5, /* valid problem outside what the kernels cover        */
+    DAB_ERR_HIP = 6          /* a HIP call failed; see dab_last_hip_error()         */
+} dab_status;
+
+typedef enum dab_layout {
+    DAB_LAYOUT_NHWC = 0,     /* X[b][h][w][c], the native layout                    */
+    DAB_LAYOUT_NCHW = 1      /* X[b][c][h][w], packed through a transposing kernel  */
+} dab_layout;
+
+/* One binarized convolution.  Output size Ho = (H + 2*pad_h - kh)/stride_h + 1,
+ * Wo likewise; both must be >= 1. */
+typedef struct dab_conv_desc {
+    int32_t B, C, H, W;                 /* input: batch, channels, height, width */
+    int32_t F, kh, kw;                  /* filters and their spatial extent      */
+    int32_t pad_h, pad_w;               /* zero padding on each side             */
+    int32_t stride_h, stride_w;
+} dab_conv_desc;
+
+/* Text for a status code (static storage, never NULL). */
+const char* dab_strerror(int status);
+
+/* hipError_t of the last failed HIP call made by this thread (0 if none). */
+int dab_last_hip_error(void);
+
+/*
+ * dab_estimate_alpha_beta - optimal alpha, beta, K and split of every filter.
+ * Section 4.1 (Theorem 2) and Section 4.3.1 / Algorithm 1: sort the n weights
+ * of a filter, form prefix sums P_i, score every split i = 1..n-1 with
+ * D_i = P_i^2/i + (T - P_i)^2/(n - i), take the largest i of maximal D.  The
+ * lower group is the i smallest weights (ties by original index), the upper
+ * group the rest; alpha is the mean of the group whose mean has the greater
+ * magnitude (the upper group if equal), beta the other mean, K the size of
+ * the alpha group.  Sums and scores are accumulated in fp64; alpha and beta
+ * are rounded to fp32 at the end.
+ *
+ *   W              [F][n] fp32, row f = filter f flattened in (c,ky,kx) order
+ *   alpha, beta    [F] fp32 out
+ *   K              [F] int32 out, 1 <= K <= n-1
+ *   thr_val        [F] fp32 out: value of the largest element of the lower group
+ *   thr_idx        [F] int32 out: its index in the row; element i is in the lower
+ *                  group iff w_i < thr_val or (w_i == thr_val and i <= thr_idx)
+ *   alpha_is_upper [F] uint8 out: 1 if the alpha group is the upper group
+ *   ws, ws_bytes   scratch of at least dab_estimate_workspace_bytes(F, n) bytes
+ *                  (may be NULL when that is 0)
+ * Errors: NULL pointers, F < 1 or n < 2 (a filter needs both groups non-empty)
+ * -> DAB_ERR_SHAPE; n above the largest supported row (dab_estimate_max_n())
+ * -> DAB_ERR_UNSUPPORTED.
+ */
+int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n,
+                            float* alpha, float* beta, int32_t* K,
+                            float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper,
+                            void* ws, size_t ws_bytes, void* stream);
+size_t dab_estimate_workspace_bytes(int32_t F, int32_t n);
+int32_t dab_estimate_max_n(void);
+
+/*
+ * dab_pack_weights - the mask e of Corollary 1 as bits, plus per-tap counts.
+ * e[f,i] = 1 iff weight i of filter f belongs to the alpha group, decided from
+ * the split descriptor of dab_estimate_alpha_beta (so the mask is defined by
+ * stable rank, not by the sign of the kept values).
+ *
+ *   W          [F][C][kh][kw] fp32 (kh = kw = 1, C = n for a fully-connected layer)
+ *   thr_val, thr_idx, alpha_is_upper   [F], as returned by the estimator
+ *   E_packed   uint32 [kh*kw*Cw][Fp] out, every word written (layout above)
+ *   ecnt       uint32 [F][kh*kw] out
+ */
+int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t kw,
+                     const float* thr_val, const int32_t* thr_idx, const uint8_t* alpha_is_upper,
+                     uint32_t* E_packed, uint32_t* ecnt, void* stream);
+
+/*
+ * dab_pack_activations - sign binarization of a layer input (Section 4: inputs
+ * are +1 / -1) into bits along the channel dimension: bit = [x >= tau_c],
+ * tau = 0 when tau is NULL (sign(0) = +1).
+ *
+ *   X          fp32, NHWC [B][H][W][C] or NCHW [B][C][H][W] according to layout
+ *   tau        [C] fp32 per-channel thresholds, or NULL
+ *   A_packed   uint32 [B][H][W][Cw] out, every word written
+ */
+int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, int32_t H, int32_t W,
+                         const float* tau, uint32_t* A_packed, void* stream);
+
+/*
+ * dab_binconv2d - binarized convolution, Section 4.3.2's I (*) W~ on packed
+ * operands: cross-correlation, zero padding (a padded tap contributes 0),
+ * no bias.  For every output pixel p and filter f
+ *     p1 = popc(A & E) over the taps inside the image,  pA = popc(A) likewise,
+ *     s1 = 2*p1 - c1,  c1 = sum of ecnt[f][tap] over those taps,
+ *     s2 = (2*pA - m) - s1,  m = C * (number of those taps),
+ *     Y[p][f] = alpha_f*s1 + beta_f*s2   evaluated in fp32 as
+ *               (alpha_f - beta_f)*s1 + beta_f*(s1 + s2), integers exact.
+ *
+ *   A_packed   uint32 [B][H][W][Cw]
+ *   E_packed   uint32 [kh*kw*Cw][Fp],  ecnt uint32 [F][kh*kw]
+ *   alpha,beta [F] fp32
+ *   Y          fp32 NHWC [B][Ho][Wo][F] out
+ *   dbg_s1     optional int32 [B][Ho][Wo][F] out: the integer s1 of every output
+ *              (NULL to skip); this is what bit-exact tests compare
+ *   ws         scratch of dab_binconv2d_workspace_bytes(d) bytes (NULL if 0)
+ */
+int dab_binconv2d(const dab_conv_desc* d /* host */, const uint32_t* A_packed, const uint32_t* E_packed,
+                  const uint32_t* ecnt, const float* alpha, const float* beta,
+                  float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, void* stream);
+size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d /* host */);
+
+/*
+ * dab_binfc - binarized fully-connected layer: the same product with a 1x1
+ * spatial extent.  Y[b][f] = alpha_f*s1 + beta_f*s2 over the Kin inputs.
+ *
+ *   A_packed   uint32 [B][ceil(Kin/32)],  E_packed uint32 [ceil(Kin/32)][Fp]
+ *   K          [F] int32, size of the alpha group of every filter (= popc of its bits)
+ *   Y          fp32 [B][F] out;  dbg_s1 optional int32 [B][F]
+ */
+int dab_binfc(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const uint32_t* E_packed,
+              const int32_t* K, const float* alpha, const float* beta,
+              float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, void* stream);
+size_t dab_binfc_workspace_bytes(int32_t B, int32_t Kin, int32_t F);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAB_H */

@@ -1,0 +1,187 @@
+"""ctypes binding of libdab_hip.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+``include/dab.h``) and does nothing but check tensor dtype / device /
+contiguity, allocate the output tensors with ``torch.empty`` and pass raw
+device pointers plus the current HIP stream.  All arithmetic of the path runs in
+the HIP kernels.  There is no CPU fallback: if the library is not built, or a
+tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_int, c_int32, c_size_t, c_void_p
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdab_hip.so")
+
+DAB_OK = 0
+DAB_LAYOUT_NHWC = 0
+DAB_LAYOUT_NCHW = 1
+
+
+class DabError(RuntimeError):
+    def __init__(self, name, status, text):
+        super().__init__(f"{name} failed: status {status} ({text})")
+        self.status = status
+
+
+class dab_conv_desc(ctypes.Structure):
+    _fields_ = [(k, c_int32) for k in
+                ("B", "C", "H", "W", "F", "kh", "kw", "pad_h", "pad_w", "stride_h", "stride_w")]
+
+    @property
+    def Ho(self):
+        return (self.H + 2 * self.pad_h - self.kh) // self.stride_h + 1
+
+    @property
+    def Wo(self):
+        return (self.W + 2 * self.pad_w - self.kw) // self.stride_w + 1
+
+
+_SIGNATURES = {
+    "dab_strerror": (c_char_p, [c_int]),
+    "dab_last_hip_error": (c_int, []),
+    "dab_estimate_alpha_beta": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "dab_estimate_workspace_bytes": (c_size_t, [c_int32, c_int32]),
+    "dab_estimate_max_n": (c_int32, []),
+    "dab_pack_weights": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                 c_void_p, c_void_p, c_void_p]),
+    "dab_pack_activations": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
+                                     c_void_p]),
+    "dab_binconv2d": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                              c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "dab_binconv2d_workspace_bytes": (c_size_t, [ctypes.POINTER(dab_conv_desc)]),
+    "dab_binfc": (c_int, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                          c_void_p, c_void_p, c_size_t, c_void_p]),
+    "dab_binfc_workspace_bytes": (c_size_t, [c_int32, c_int32, c_int32]),
+}
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (opened on first use; raises if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1804_02941_amd.build` first")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _check(name, status):
+    if status != DAB_OK:
+        raise DabError(name, status, lib().dab_strerror(status).decode())
+
+
+def _ptr(t, dtype, name):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a tensor on the GPU")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def words_per_pixel(C):
+    return (C + 31) // 32
+
+
+def padded_filters(F):
+    return 64 * ((F + 63) // 64)
+
+
+def dab_estimate_alpha_beta(W):
+    """W [F, n] fp32 -> dict(alpha, beta, K, thr_val, thr_idx, alpha_is_upper), each [F]."""
+    F, n = W.shape
+    dev = W.device
+    out = dict(
+        alpha=torch.empty(F, dtype=torch.float32, device=dev), beta=torch.empty(F, dtype=torch.float32, device=dev),
+        K=torch.empty(F, dtype=torch.int32, device=dev), thr_val=torch.empty(F, dtype=torch.float32, device=dev),
+        thr_idx=torch.empty(F, dtype=torch.int32, device=dev),
+        alpha_is_upper=torch.empty(F, dtype=torch.uint8, device=dev))
+    nbytes = lib().dab_estimate_workspace_bytes(F, n)
+    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=dev) if nbytes else None
+    _check("dab_estimate_alpha_beta", lib().dab_estimate_alpha_beta(
+        _ptr(W, torch.float32, "W"), F, n, out["alpha"].data_ptr(), out["beta"].data_ptr(), out["K"].data_ptr(),
+        out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(), out["alpha_is_upper"].data_ptr(),
+        ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return out
+
+
+def dab_pack_weights(W, thr_val, thr_idx, alpha_is_upper):
+    """W [F, C, kh, kw] fp32 + split descriptor -> (E_packed uint32-as-int32 [R, Fp], ecnt int32 [F, kh*kw])."""
+    F, C, kh, kw = W.shape
+    R, Fp = kh * kw * words_per_pixel(C), padded_filters(F)
+    E = torch.empty((R, Fp), dtype=torch.int32, device=W.device)
+    ecnt = torch.empty((F, kh * kw), dtype=torch.int32, device=W.device)
+    _check("dab_pack_weights", lib().dab_pack_weights(
+        _ptr(W, torch.float32, "W"), F, C, kh, kw, _ptr(thr_val, torch.float32, "thr_val"),
+        _ptr(thr_idx, torch.int32, "thr_idx"), _ptr(alpha_is_upper, torch.uint8, "alpha_is_upper"),
+        E.data_ptr(), ecnt.data_ptr(), _stream()))
+    return E, ecnt
+
+
+def dab_pack_activations(X, layout=DAB_LAYOUT_NHWC, tau=None, out=None):
+    """X fp32 NHWC [B,H,W,C] (or NCHW [B,C,H,W]; a 2-D [B,C] is H=W=1) -> int32 [B,H,W,Cw]."""
+    if X.dim() == 2:
+        B, C = X.shape
+        H = W = 1
+    elif layout == DAB_LAYOUT_NHWC:
+        B, H, W, C = X.shape
+    else:
+        B, C, H, W = X.shape
+    A = out if out is not None else torch.empty((B, H, W, words_per_pixel(C)), dtype=torch.int32, device=X.device)
+    _check("dab_pack_activations", lib().dab_pack_activations(
+        _ptr(X, torch.float32, "X"), layout, B, C, H, W, _ptr(tau, torch.float32, "tau"),
+        _ptr(A, torch.int32, "A_packed"), _stream()))
+    return A
+
+
+def dab_binconv2d(desc, A_packed, E_packed, ecnt, alpha, beta, want_s1=False, out=None):
+    """Binarized convolution; returns Y fp32 [B,Ho,Wo,F] (and int32 s1 of the same shape if asked)."""
+    dev = A_packed.device
+    shape = (desc.B, desc.Ho, desc.Wo, desc.F)
+    Y = out if out is not None else torch.empty(shape, dtype=torch.float32, device=dev)
+    s1 = torch.empty(shape, dtype=torch.int32, device=dev) if want_s1 else None
+    nbytes = lib().dab_binconv2d_workspace_bytes(ctypes.byref(desc))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev) if nbytes else None
+    _check("dab_binconv2d", lib().dab_binconv2d(
+        ctypes.byref(desc), _ptr(A_packed, torch.int32, "A_packed"), _ptr(E_packed, torch.int32, "E_packed"),
+        _ptr(ecnt, torch.int32, "ecnt"), _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
+        _ptr(Y, torch.float32, "Y"), s1.data_ptr() if want_s1 else None,
+        ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return (Y, s1) if want_s1 else Y
+
+
+def dab_binfc(A_packed, E_packed, K, alpha, beta, Kin, want_s1=False, out=None):
+    """Binarized fully-connected layer; A_packed [B, Kw], returns Y fp32 [B, F]."""
+    dev = A_packed.device
+    B = A_packed.shape[0]
+    F = alpha.shape[0]
+    Y = out if out is not None else torch.empty((B, F), dtype=torch.float32, device=dev)
+    s1 = torch.empty((B, F), dtype=torch.int32, device=dev) if want_s1 else None
+    nbytes = lib().dab_binfc_workspace_bytes(B, Kin, F)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev) if nbytes else None
+    _check("dab_binfc", lib().dab_binfc(
+        B, Kin, F, _ptr(A_packed, torch.int32, "A_packed"), _ptr(E_packed, torch.int32, "E_packed"),
+        _ptr(K, torch.int32, "K"), _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
+        _ptr(Y, torch.float32, "Y"), s1.data_ptr() if want_s1 else None,
+        ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return (Y, s1) if want_s1 else Y

@@ -1,0 +1,49 @@
+// Internal helpers shared by the HIP translation units of libdab (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dab.h"
+
+namespace dab {
+
+// hipError_t of the last failed HIP call on this thread, read by dab_last_hip_error().
+extern thread_local int g_last_hip_error;
+
+inline int hip_failed(hipError_t e) {
+    g_last_hip_error = static_cast<int>(e);
+    return DAB_ERR_HIP;
+}
+
+// Status of the launch that was just enqueued.
+inline int launch_status() {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? DAB_OK : hip_failed(e);
+}
+
+inline bool misaligned(const void* p, size_t a) {
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0;
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// n / d for 0 <= n < 2^31 by multiply-high and shift (d fixed per launch, 1 <= d < 2^31).
+struct FastDiv {
+    uint32_t mul, shift;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    const uint64_t m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+    return FastDiv{static_cast<uint32_t>(m), l};
+}
+__device__ __forceinline__ int fdiv(int n, FastDiv d) {
+    return static_cast<int>((__umulhi(d.mul, static_cast<uint32_t>(n)) + static_cast<uint32_t>(n)) >> d.shift);
+}
+
+constexpr int kWave = 64;            // gfx950 wavefront width
+constexpr int kNumCU = 256;          // MI355X compute units
+constexpr int kNumXCD = 8;           // accelerator complex dies, each with its own L2
+
+}  // namespace dab

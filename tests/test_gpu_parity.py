@@ -1,0 +1,239 @@
+"""GPU parity tests: every C-ABI entry point against the CPU oracle, element by element.
+
+Integers (packed bits, per-tap counts, K, s1) must match exactly; alpha/beta to 1e-6
+relative; the fp32 layer output to 1e-5 relative (see gpu_util.Y_RTOL).  Sizes are small
+enough for the oracle to finish in seconds but span several workgroup tiles and ragged
+tails.  Full-size runs are in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import estimate as oest
+from oracle import layers as olay
+from oracle import packing as opk
+from paper_1804_02941_amd import binding as dab
+from paper_1804_02941_amd import workloads as wl
+from paper_1804_02941_amd.workloads import Layer
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------ dab_pack_activations
+@pytest.mark.parametrize("C", [1, 31, 32, 33, 64, 65, 96, 100, 128, 256, 512])
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+def test_pack_activations(C, layout):
+    rng = np.random.default_rng(C)
+    B, H, W = 3, 5, 7
+    x = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    x[0, 0, 0, 0] = 0.0
+    x[0, C - 1, 0, 1] = -0.0
+    x[1, 0, 1, 1] = np.nan
+    x[2, C // 2, 2, 2] = np.inf
+    for tau in (None, rng.standard_normal(C).astype(np.float32) * 0.5):
+        ref = opk.pack_activations(olay.binarize_activations(x, tau))
+        tt = gu.to_gpu(tau) if tau is not None else None
+        if layout == "nhwc":
+            A = dab.dab_pack_activations(gu.to_gpu(np.transpose(x, (0, 2, 3, 1))), dab.DAB_LAYOUT_NHWC, tt)
+        else:
+            A = dab.dab_pack_activations(gu.to_gpu(x), dab.DAB_LAYOUT_NCHW, tt)
+        torch.cuda.synchronize()
+        assert np.array_equal(gu.u32(A), ref)
+
+
+def test_pack_activations_fc_and_ragged_sizes():
+    rng = np.random.default_rng(5)
+    for B, C in ((1, 2), (7, 9216), (130, 4096), (1025, 70), (3, 12544)):
+        x = rng.standard_normal((B, C)).astype(np.float32)
+        ref = opk.pack_activations(olay.binarize_activations(x))
+        A = dab.dab_pack_activations(gu.to_gpu(x))
+        torch.cuda.synchronize()
+        assert np.array_equal(gu.u32(A).reshape(ref.shape), ref)
+
+
+# ------------------------------------------------------------------ dab_estimate_alpha_beta
+def weight_rows(rng, F, n, kind):
+    if kind == "gauss":
+        return (rng.standard_normal((F, n)) * 0.05 + rng.uniform(-0.02, 0.02, (F, 1))).astype(np.float32)
+    if kind == "laplace":
+        return rng.laplace(0.004, 0.03, (F, n)).astype(np.float32)
+    if kind == "mixture":
+        return wl.skewed_mixture_weights(rng, rng, F, n, n)
+    if kind == "dupes":
+        return (np.round(rng.standard_normal((F, n)) * 6) / 16).astype(np.float32)
+    if kind == "onesided":
+        return np.abs(rng.standard_normal((F, n))).astype(np.float32) + 0.25
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 576, 1024, 1025, 1600, 2304, 3072, 3073, 4608, 5120, 5121, 9216, 12544, 13312])
+def test_estimate_sizes(n):
+    rng = np.random.default_rng(n)
+    F = 6 if n > 3000 else 10
+    W = np.concatenate([weight_rows(rng, F // 2, n, "gauss"), weight_rows(rng, F - F // 2, n, "mixture")])
+    got, _ = gu.gpu_estimate(W)
+    _, differ = gu.check_estimate(W, got)
+    assert differ <= 1
+
+
+@pytest.mark.parametrize("kind", ["gauss", "laplace", "mixture", "dupes", "onesided"])
+def test_estimate_distributions(kind):
+    rng = np.random.default_rng(17)
+    W = weight_rows(rng, 40, 777, kind)
+    got, _ = gu.gpu_estimate(W)
+    gu.check_estimate(W, got)
+
+
+def test_estimate_degenerate_rows():
+    n = 200
+    rows = [
+        np.full(n, 0.25, np.float32),                                         # constant
+        np.concatenate([np.zeros(n // 2), -np.zeros(n // 2)]).astype(np.float32),   # +0 / -0 only
+        np.concatenate([np.full(n - 1, -1.0), [3.0]]).astype(np.float32),     # one outlier
+        np.concatenate([np.full(n // 2, -0.5), np.full(n // 2, 0.5)]).astype(np.float32),   # symmetric two-point
+        np.arange(n, dtype=np.float32) / n,                                   # already sorted
+        -np.arange(n, dtype=np.float32) / n,                                  # reverse sorted
+    ]
+    W = np.stack(rows)
+    got, _ = gu.gpu_estimate(W)
+    e, differ = gu.check_estimate(W, got)
+    assert differ == 0
+    assert got["K"][0] == 1 and got["thr_idx"][0] == n - 2
+    assert got["K"][3] == n // 2 and got["alpha"][3] == 0.5 and got["beta"][3] == -0.5
+
+
+def test_estimate_xnor_special_case():
+    """Symmetric filter: K = n/2 and alpha = -beta = mean|W| (Section 4.2's XNOR-Net simulation)."""
+    rng = np.random.default_rng(23)
+    h = np.abs(rng.standard_normal((8, 300))).astype(np.float32) + 0.01
+    W = np.concatenate([h, -h], axis=1)
+    W = np.take_along_axis(W, rng.permuted(np.tile(np.arange(600), (8, 1)), axis=1), axis=1)
+    got, _ = gu.gpu_estimate(W)
+    assert np.all(got["K"] == 300) and np.all(got["alpha_is_upper"] == 1)
+    assert np.allclose(got["alpha"], np.abs(W.astype(np.float64)).mean(axis=1), rtol=1e-6)
+    assert np.allclose(got["alpha"], -got["beta"], rtol=1e-6)
+
+
+# ------------------------------------------------------------------ dab_pack_weights
+@pytest.mark.parametrize("F,C,kh,kw", [(5, 3, 1, 1), (64, 64, 3, 3), (70, 45, 2, 3), (130, 100, 5, 5),
+                                       (9, 256, 7, 7), (33, 9216, 1, 1), (3, 13000, 1, 1), (4, 330, 3, 3)])
+def test_pack_weights_with_oracle_split(F, C, kh, kw):
+    """The packer alone, fed the oracle's split descriptor: bits and counts exact."""
+    rng = np.random.default_rng(F * C)
+    n = C * kh * kw
+    W = weight_rows(rng, F, n, "dupes" if C == 45 else "laplace").reshape(F, C, kh, kw)
+    r = oest.estimate_alpha_beta(W)
+    E, ecnt = dab.dab_pack_weights(gu.to_gpu(W), gu.to_gpu(r["thr_val"].astype(np.float32)),
+                                   gu.to_gpu(r["thr_idx"].astype(np.int32)), gu.to_gpu(r["alpha_is_upper"].astype(np.uint8)))
+    torch.cuda.synchronize()
+    E_ref, ecnt_ref = opk.pack_weights(r["e"])
+    assert np.array_equal(gu.u32(E), E_ref)
+    assert np.array_equal(gu.u32(ecnt), ecnt_ref)
+    assert np.array_equal(gu.u32(ecnt).sum(axis=1), r["K"])
+
+
+# ------------------------------------------------------------------ layers, end to end
+SMALL_LAYERS = [
+    Layer("c3x3_pad", C=37, H=6, W=5, F=7, kh=3, kw=3, pad=1),
+    Layer("c3x5_stride", C=100, H=11, W=10, F=70, kh=3, kw=3, pad=1, stride=2),
+    Layer("c5x5_pad2_s2", C=33, H=9, W=9, F=5, kh=5, kw=5, pad=2, stride=2),
+    Layer("whole_image", C=70, H=7, W=7, F=130, kh=7, kw=7),
+    Layer("pointwise", C=3, H=4, W=4, F=3, kh=1, kw=1),
+    Layer("c64", C=64, H=12, W=13, F=64, kh=3, kw=3, pad=1),
+    Layer("c96_f100", C=96, H=9, W=8, F=100, kh=3, kw=3),
+    Layer("wide", C=32, H=3, W=40, F=16, kh=3, kw=3, pad=1),
+]
+
+
+@pytest.mark.parametrize("L", SMALL_LAYERS, ids=lambda L: L.name)
+@pytest.mark.parametrize("B", [1, 3])
+def test_small_conv_layers(L, B):
+    rng = np.random.default_rng(abs(hash(L.name)) % 1000 + B)
+    x = rng.standard_normal((B, L.C, L.H, L.W)).astype(np.float32)
+    W = weight_rows(rng, L.F, L.n, "mixture")
+    gu.check_layer(L, x, W, tau=None, layout="nhwc")
+    gu.check_layer(L, x, W, tau=(rng.standard_normal(L.C) * 0.3).astype(np.float32), layout="nchw")
+
+
+@pytest.mark.parametrize("B,K,F", [(1, 2, 1), (5, 70, 9), (64, 512, 512), (65, 1000, 130), (300, 4096, 48), (130, 9216, 40)])
+def test_small_fc_layers(B, K, F):
+    rng = np.random.default_rng(B + K + F)
+    L = Layer("fc", C=K, H=1, W=1, F=F, kh=1, kw=1)
+    x = rng.standard_normal((B, K)).astype(np.float32)
+    W = weight_rows(rng, F, K, "gauss" if K > 2 else "onesided")
+    gu.check_layer(L, x, W)
+
+
+def test_config1_tiny_layer():
+    L, x, w = wl.config1()
+    gu.check_layer(L, x, w)                                  # half-normal input: every bit is 1
+    gu.check_layer(L, x, w, tau=x.mean(axis=(0, 2, 3)))      # mixed bits
+
+
+def test_config2_shape_small_batch():
+    L, x, w = wl.config2(batch=3)
+    gu.check_layer(L, x, w, tau=x.mean(axis=(0, 2, 3)))
+
+
+def test_all_plus_one_input_gives_filter_sums():
+    """Non-negative input with tau = 0: every bit is 1 and a valid conv returns sum_i w~_i = sum_i w_i."""
+    L, x, w = wl.config2(batch=2)
+    g = gu.gpu_layer(L, x, w)
+    T = w.astype(np.float64).reshape(L.F, -1).sum(axis=1)
+    scale = np.abs(w.astype(np.float64)).reshape(L.F, -1).sum(axis=1)
+    assert np.all(np.abs(g["Y"] - T) <= 2e-6 * scale)
+    assert np.array_equal(g["s1"], np.broadcast_to(g["est"]["K"], g["s1"].shape))
+
+
+def test_config3_layers_small_batch():
+    """Sketch-A-Net trunk, batch 2, chained through the oracle; each layer checked on identical inputs."""
+    B = 2
+    imgs = wl.sketch_images(B)
+    w1, ws = wl.config3_weights()
+    x = wl.config3_conv1_features(imgs, w1).numpy()
+    for L, W in zip(wl.CFG3_LAYERS, ws):
+        if L.is_fc:
+            x = x.reshape(B, -1)
+        tau = x.mean(axis=(0, 2, 3)) if x.ndim == 4 else x.mean(axis=0)
+        gu.check_layer(L, x, W, tau=tau.astype(np.float32))
+        # the next layer's input: this layer's oracle output (float64 -> fp32), pooled where the net pools
+        r = oest.estimate_alpha_beta(W)
+        a = olay.binarize_activations(x if x.ndim == 4 else x[:, :, None, None], tau.astype(np.float32))
+        y = olay.conv2d(a, olay.two_valued_filters(r["e"], r["alpha"], r["beta"]), (L.pad, L.pad), (L.stride, L.stride))
+        y = torch.from_numpy(y.astype(np.float32)).permute(0, 3, 1, 2)
+        if L.pool_after:
+            y = torch.nn.functional.max_pool2d(y, 3, 2)
+        x = y.numpy()
+
+
+@pytest.mark.parametrize("stage", [0, 1, 2, 3])
+def test_config4_stages_small_batch(stage):
+    L, x, w = wl.config4(stage, batch=1 if stage == 0 else 2)
+    gu.check_layer(L, x, w)
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_config5_reduced(which):
+    L, x, w = wl.config5(which, batch=96, filters=72)
+    gu.check_layer(L, x, w)
+
+
+# ------------------------------------------------------------------ error paths (host validation only)
+def test_error_codes():
+    lib = dab.lib()
+    x = torch.zeros(64, device=gu.DEV)
+    a = torch.zeros(64, dtype=torch.int32, device=gu.DEV)
+    assert lib.dab_pack_activations(None, 0, 1, 1, 1, 1, None, a.data_ptr(), None) == 1
+    assert lib.dab_pack_activations(x.data_ptr(), 0, 0, 1, 1, 1, None, a.data_ptr(), None) == 2
+    assert lib.dab_pack_activations(x.data_ptr(), 7, 1, 1, 1, 1, None, a.data_ptr(), None) == 2
+    assert lib.dab_pack_activations(x.data_ptr(), 0, 1, 1, 1, 1, None, a.data_ptr() + 4, None) == 3
+    with pytest.raises(dab.DabError):
+        dab.dab_estimate_alpha_beta(torch.zeros((3, 1), device=gu.DEV))
+    with pytest.raises(dab.DabError) as ei:
+        dab.dab_estimate_alpha_beta(torch.zeros((1, lib.dab_estimate_max_n() + 1), device=gu.DEV))
+    assert ei.value.status == 5
+    with pytest.raises(TypeError):
+        dab.dab_pack_activations(torch.zeros((1, 4)))        # CPU tensor: no fallback
+    torch.cuda.synchronize()
