@@ -1,0 +1,203 @@
+"""Benchmark of the binarized-layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload: the binarized layers of the Sketch-A-Net trunk at batch 256 (config 3 of
+the benchmark spec: conv2..conv6 + fc7 on synthetic sketches).  One step is one pass of the whole
+path over the batch: for every layer, alpha/beta estimation of its filters, weight bit
+packing, activation bit packing and the binary convolution / fully-connected product.  The
+fp32 inputs of all layers and the fp32 weights are resident in HBM before the timed region.
+
+Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
+kernel (binary convolution, VALU-bound) from HIP-event timings taken inside the timed
+region, and the CPU oracle timed on a small slice of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 64 VALU lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s.  One AND + one BCNT
+# serve 32 binary multiply-accumulates of one lane, so the instruction-set floor is
+# MACs / 16 lane-ops and the matching peak is 629 T binary MAC/s.
+VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9
+OPS_PER_MAC = 2.0 / 32.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
+    ap.add_argument("--cpu-batch", type=int, default=128, help="images of the CPU-oracle sample (0 = skip)")
+    return ap.parse_args()
+
+
+class LayerState:
+    """Device buffers of one binarized layer, allocated once."""
+
+    def __init__(self, L, W, X, tau, dab, torch):
+        self.L, self.W, self.X, self.tau = L, W, X, tau
+        B = X.shape[0]
+        self.B = B
+        self.W2 = W.reshape(L.F, -1)
+        if L.is_fc:
+            self.desc = None
+            self.Y = torch.empty((B, L.F), dtype=torch.float32, device=X.device)
+            self.A = torch.empty((B, 1, 1, dab.words_per_pixel(L.C)), dtype=torch.int32, device=X.device)
+        else:
+            self.desc = dab.dab_conv_desc(B, L.C, L.H, L.W, L.F, L.kh, L.kw, L.pad, L.pad, L.stride, L.stride)
+            self.Y = torch.empty((B, L.Ho, L.Wo, L.F), dtype=torch.float32, device=X.device)
+            self.A = torch.empty((B, L.H, L.W, dab.words_per_pixel(L.C)), dtype=torch.int32, device=X.device)
+        self.macs = L.macs(B)
+
+
+def run_layer(s, dab, events=None):
+    """estimate -> pack weights -> pack activations -> binary product, all on the current stream."""
+    est = dab.dab_estimate_alpha_beta(s.W2)
+    E, ecnt = dab.dab_pack_weights(s.W, est["thr_val"], est["thr_idx"], est["alpha_is_upper"])
+    dab.dab_pack_activations(s.X, dab.DAB_LAYOUT_NHWC, s.tau, out=s.A)
+    if events is not None:
+        events[0].record()
+    if s.desc is None:
+        dab.dab_binfc(s.A.view(s.B, -1), E, est["K"], est["alpha"], est["beta"], s.L.C, out=s.Y)
+    else:
+        dab.dab_binconv2d(s.desc, s.A, E, ecnt, est["alpha"], est["beta"], out=s.Y)
+    if events is not None:
+        events[1].record()
+    return s.Y
+
+
+def build_states(batch, dab, torch, wl):
+    """Synthetic sketches -> fp32 conv1 features -> inputs of all six layers (chained through the GPU path)."""
+    dev = torch.device("cuda:0")
+    imgs = wl.sketch_images(batch)
+    w1, ws = wl.config3_weights()
+    x = wl.config3_conv1_features(imgs, w1, device=dev)            # [B, 64, 35, 35], untimed fp32 prologue
+    x = x.permute(0, 2, 3, 1).contiguous()                        # NHWC
+    states = []
+    for L, W in zip(wl.CFG3_LAYERS, ws):
+        if L.is_fc:
+            x = x.reshape(batch, -1).contiguous()
+            tau = x.mean(dim=0)
+        else:
+            tau = x.mean(dim=(0, 1, 2))
+        s = LayerState(L, torch.from_numpy(W).to(dev), x, tau.contiguous(), dab, torch)
+        states.append(s)
+        y = run_layer(s, dab).clone()
+        if L.pool_after:
+            y = torch.nn.functional.max_pool2d(y.permute(0, 3, 1, 2), 3, 2).permute(0, 2, 3, 1).contiguous()
+        x = y
+    torch.cuda.synchronize()
+    return states
+
+
+def cpu_oracle_baseline(batch, wl):
+    """The float64 CPU oracle, as it stands, on a small slice of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import estimate as oest
+    from oracle import layers as olay
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    imgs = wl.sketch_images(batch)
+    w1, ws = wl.config3_weights()
+    x = wl.config3_conv1_features(imgs, w1).numpy()
+    macs = 0
+    t0 = time.perf_counter()
+    for L, W in zip(wl.CFG3_LAYERS, ws):
+        if L.is_fc:
+            x = x.reshape(batch, -1)
+        x4 = x if x.ndim == 4 else x[:, :, None, None]
+        tau = x4.mean(axis=(0, 2, 3)).astype(np.float32)
+        r = oest.estimate_alpha_beta(W)
+        a = olay.binarize_activations(x4, tau)
+        y = olay.conv2d(a, olay.two_valued_filters(r["e"], r["alpha"], r["beta"]), (L.pad, L.pad), (L.stride, L.stride))
+        macs += L.macs(batch)
+        y = torch.from_numpy(y.astype(np.float32)).permute(0, 3, 1, 2)
+        if L.pool_after:
+            y = torch.nn.functional.max_pool2d(y, 3, 2)
+        x = y.numpy()
+    dt = time.perf_counter() - t0
+    return {"value": macs / dt, "unit": "binary MAC/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"config 3, all six layers incl. alpha/beta estimation, batch {batch} of 256, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every layer is computed whole on one MI355X); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1804_02941_amd import binding as dab
+    from paper_1804_02941_amd import workloads as wl
+    if not os.path.exists(dab.LIB_PATH):
+        from paper_1804_02941_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+
+    states = build_states(args.batch, dab, torch, wl)
+    total_macs = sum(s.macs for s in states)
+
+    for _ in range(args.warmup):
+        for s in states:
+            run_layer(s, dab)
+    torch.cuda.synchronize()
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in states]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for s, e in zip(states, ev[k]):
+            run_layer(s, dab, e)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * dt / args.steps
+    value = total_macs * args.steps / dt
+    # binary-product kernel: per-layer and aggregate, from the events recorded in the timed region
+    per_layer = {}
+    conv_ms = 0.0
+    for i, s in enumerate(states):
+        ms = sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
+        conv_ms += ms
+        per_layer[s.L.name] = {"ms": round(ms, 4), "gmacs": round(s.macs / 1e9, 3),
+                               "frac_of_valu_peak": round(s.macs * OPS_PER_MAC / (ms * 1e-3) / VALU_LANE_OPS_PER_S, 4)}
+    achieved = total_macs * OPS_PER_MAC / (conv_ms * 1e-3) / 1e12
+    peak = VALU_LANE_OPS_PER_S / 1e12
+    roofline = {"bound": "alu", "kernel": "binconv_kernel (all six launches of a step)",
+                "achieved": round(achieved, 3), "peak": round(peak, 3), "unit": "TOP/s (32-bit VALU lane-ops: AND + BCNT per 32 MACs)",
+                "frac": round(achieved / peak, 4), "frac_of_bcnt_only_peak": round(achieved / peak / 2, 4),
+                "kernel_ms_per_step": round(conv_ms, 4), "traffic": None, "per_layer": per_layer}
+
+    cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
+    line = {
+        "metric": "effective binary MACs/s on Sketch-A-Net binarized layers",
+        "value": value, "unit": "binary MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 popcount / int32 accumulate, fp32 epilogue, fp64 estimation", "data": "synthetic",
+        "config": {"workload": "config 3: Sketch-A-Net binarized trunk (conv2-conv6, fc7), batch %d, "
+                               "estimate + pack weights + pack activations + binary product per layer" % args.batch,
+                   "batch": args.batch, "binary_macs_per_step": total_macs},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

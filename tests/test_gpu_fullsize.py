@@ -1,0 +1,103 @@
+"""GPU parity at the full sizes of the five configurations, in the launch shapes bench.py times.
+
+The oracle cannot evaluate a whole layer at these sizes in seconds, so the fp32 outputs and
+the integers s1 are checked on sampled outputs computed one by one (always including image
+corners and borders and the last pixel / filter), while everything that is cheap on the
+CPU is still checked in full: alpha/beta/K of every filter, every packed weight bit and
+per-tap count, every packed activation bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layers as olay
+from oracle import packing as opk
+from paper_1804_02941_amd import binding as dab
+from paper_1804_02941_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_points(rng, B, Ho, Wo, F, count):
+    pts = {(0, 0, 0, 0), (B - 1, Ho - 1, Wo - 1, F - 1), (0, 0, Wo - 1, F // 2), (B - 1, Ho - 1, 0, 0),
+           (B // 2, Ho // 2, Wo // 2, F - 1), (0, Ho - 1, Wo // 2, 1 % F)}
+    while len(pts) < count:
+        pts.add((int(rng.integers(B)), int(rng.integers(Ho)), int(rng.integers(Wo)), int(rng.integers(F))))
+    return sorted(pts)
+
+
+def check_full_layer(L, x_nchw, W, tau, g, count=96, seed=0):
+    """g = gu.gpu_layer(...) result (or equivalent dict) for this layer at full size."""
+    W4 = W.reshape(L.F, L.C, L.kh, L.kw)
+    e, differ = gu.check_estimate(W4, g["est"])
+    E_ref, ecnt_ref = opk.pack_weights(e)
+    assert np.array_equal(g["E"], E_ref) and np.array_equal(g["ecnt"], ecnt_ref)
+    x4 = x_nchw if x_nchw.ndim == 4 else x_nchw[:, :, None, None]
+    a = olay.binarize_activations(x4, tau)
+    A_ref = opk.pack_activations(a)
+    assert np.array_equal(g["A"].reshape(A_ref.shape), A_ref)
+    B = x4.shape[0]
+    pts = sample_points(np.random.default_rng(seed), B, L.Ho, L.Wo, L.F, count)
+    alpha = g["est"]["alpha"].astype(np.float64)
+    beta = g["est"]["beta"].astype(np.float64)
+    Wt = olay.two_valued_filters(e, alpha, beta)
+    pad, stride = (L.pad, L.pad), (L.stride, L.stride)
+    y_ref = olay.conv2d_at(a, Wt, pad, stride, pts)
+    s1_ref = olay.conv2d_at(a, e, pad, stride, pts)
+    sA_ref = olay.conv2d_at(a, np.ones((1,) + e.shape[1:]), pad, stride, [(b, oy, ox, 0) for b, oy, ox, _ in pts])
+    Y = g["Y"].reshape(B, L.Ho, L.Wo, L.F)
+    S1 = g["s1"].reshape(B, L.Ho, L.Wo, L.F)
+    for j, p in enumerate(pts):
+        f = p[3]
+        assert S1[p] == int(round(s1_ref[j])), f"s1 at {p}"
+        bound = abs(alpha[f]) * abs(s1_ref[j]) + abs(beta[f]) * abs(sA_ref[j] - s1_ref[j])
+        assert abs(float(Y[p]) - y_ref[j]) <= gu.Y_RTOL * max(abs(y_ref[j]), bound), f"Y at {p}"
+    # a property that holds at any size: s1 and K have the same parity as the number of valid taps' e-bits,
+    # and |s1| never exceeds the e-bits inside the window
+    K = g["est"]["K"].astype(np.int64)
+    assert np.all(np.abs(S1.astype(np.int64)) <= K)
+    if L.pad == 0:
+        assert np.all((S1.astype(np.int64) - K) % 2 == 0)
+    return differ
+
+
+def test_config2_full():
+    L, x, w = wl.config2()
+    tau = x.mean(axis=(0, 2, 3)).astype(np.float32)
+    g = gu.gpu_layer(L, x, w, tau)
+    check_full_layer(L, x, w, tau, g)
+
+
+def test_config3_full_chain():
+    """Batch 256, every layer's input produced by the previous GPU layer, as in the benchmark."""
+    import bench
+    states = bench.build_states(256, dab, torch, wl)
+    for s in states:
+        L = s.L
+        x = s.X.cpu().numpy()
+        x_nchw = np.ascontiguousarray(np.transpose(x, (0, 3, 1, 2))) if x.ndim == 4 else x
+        tau = s.tau.cpu().numpy()
+        W = s.W.cpu().numpy()
+        g = gu.gpu_layer(L, x_nchw, W, tau)
+        # the benchmark's own launch (no s1 output, preallocated buffers) gives the same Y
+        y_bench = bench.run_layer(s, dab)
+        torch.cuda.synchronize()
+        assert torch.equal(y_bench.reshape(-1), g["Y_gpu"].reshape(-1))
+        check_full_layer(L, x_nchw, W, tau, g, count=64)
+
+
+@pytest.mark.parametrize("stage", [0, 1, 2, 3])
+def test_config4_full(stage):
+    L, x, w = wl.config4(stage)
+    g = gu.gpu_layer(L, x, w)
+    check_full_layer(L, x, w, None, g, count=64, seed=stage)
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_config5_full(which):
+    L, x, w = wl.config5(which)
+    g = gu.gpu_layer(L, x, w)
+    differ = check_full_layer(L, x, w, None, g, count=128, seed=which)
+    assert differ <= 8        # near-ties in D among 4096 long rows are rare
