@@ -15,6 +15,7 @@ region, and the CPU oracle timed on a small slice of the same workload.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -58,6 +59,9 @@ class LayerState:
             self.Y = torch.empty((B, L.Ho, L.Wo, L.F), dtype=torch.float32, device=X.device)
             self.A = torch.empty((B, L.H, L.W, dab.words_per_pixel(L.C)), dtype=torch.int32, device=X.device)
         self.macs = L.macs(B)
+        nbytes = (dab.lib().dab_binfc_workspace_bytes(B, L.C, L.F) if L.is_fc
+                  else dab.lib().dab_binconv2d_workspace_bytes(ctypes.byref(self.desc)))
+        self.ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=X.device)
 
 
 def run_layer(s, dab, events=None):
@@ -68,9 +72,9 @@ def run_layer(s, dab, events=None):
     if events is not None:
         events[0].record()
     if s.desc is None:
-        dab.dab_binfc(s.A.view(s.B, -1), E, est["K"], est["alpha"], est["beta"], s.L.C, out=s.Y)
+        dab.dab_binfc(s.A.view(s.B, -1), E, est["alpha"], est["beta"], s.L.C, out=s.Y, ws=s.ws)
     else:
-        dab.dab_binconv2d(s.desc, s.A, E, ecnt, est["alpha"], est["beta"], out=s.Y)
+        dab.dab_binconv2d(s.desc, s.A, E, est["alpha"], est["beta"], out=s.Y, ws=s.ws)
     if events is not None:
         events[1].record()
     return s.Y

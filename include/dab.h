@@ -8,11 +8,12 @@
  * (Section 4.1, Theorem 2); the mask comes from a split of the sorted weights
  * found with prefix sums (Section 4.3.1, Algorithm 1); inputs of the layer are
  * binary, +1 / -1 (Section 4); the layer output is the ordinary convolution of
- * the binary input with W~ (Section 4.3.2).  With A = [a = +1] and E = e as
- * bit vectors, sum_i a_i e_i = 2*popc(A & E) - popc(E) over the taps inside
- * the image, so every output needs one AND + popcount per 32 inputs and the
- * two scalars recombine the counts:
- *     y = alpha*s1 + beta*s2,  s1 = sum a_i e_i,  s2 = sum a_i (1 - e_i).
+ * the binary input with W~ (Section 4.3.2).  Since W~ takes two values,
+ *     y = alpha*s1 + beta*s2,  s1 = sum a_i e_i,  s2 = sum a_i (1 - e_i),
+ * over the taps inside the image, with s1 + s2 = sA = sum a_i.  One bit per
+ * weight and per activation is what crosses this interface; s1 is an exact
+ * integer contraction of the two bit tensors and the two scalars recombine it
+ * with the per-pixel sum sA.
  *
  * General rules
  *   - All data pointers are DEVICE pointers unless a comment says "host".
@@ -37,9 +38,11 @@
  *   Weights      uint32 [R][Fp], R = kh*kw*Cw, Fp = 64*ceil(F/64).  Row
  *                r = (ky*kw + kx)*Cw + (c div 32), column f, bit (c mod 32) is
  *                e[f,c,ky,kx].  Bits past C and columns past F are 0.
- *                (Word-major so that one wavefront-uniform fetch brings the
- *                same reduction word of 16 consecutive filters.)
- *   Tap counts   uint32 [F][kh*kw]: ecnt[f][ky*kw+kx] = sum_c e[f,c,ky,kx].
+ *                (Word-major: the word of one reduction position is contiguous
+ *                over the filters, which is how both packing and expansion walk it.)
+ *   Tap counts   uint32 [F][kh*kw]: ecnt[f][ky*kw+kx] = sum_c e[f,c,ky,kx]; their sum
+ *                over the taps is K_f.  They describe the mask (and check it); the
+ *                layer kernels do not need them.
  */
 #ifndef DAB_H
 #define DAB_H
@@ -142,23 +145,28 @@ int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, i
 /*
  * dab_binconv2d - binarized convolution, Section 4.3.2's I (*) W~ on packed
  * operands: cross-correlation, zero padding (a padded tap contributes 0),
- * no bias.  For every output pixel p and filter f
- *     p1 = popc(A & E) over the taps inside the image,  pA = popc(A) likewise,
- *     s1 = 2*p1 - c1,  c1 = sum of ecnt[f][tap] over those taps,
- *     s2 = (2*pA - m) - s1,  m = C * (number of those taps),
- *     Y[p][f] = alpha_f*s1 + beta_f*s2   evaluated in fp32 as
- *               (alpha_f - beta_f)*s1 + beta_f*(s1 + s2), integers exact.
+ * no bias.  For every output pixel p and filter f, over the taps inside the image,
+ *     s1 = sum a_i e_i   (exact integer; a = +1/-1 from the activation bits, e from the weight bits),
+ *     sA = sum a_i = 2*popc(A) - C * (number of those taps),
+ *     Y[p][f] = alpha_f*s1 + beta_f*(sA - s1), evaluated in fp32 as
+ *               (alpha_f - beta_f)*s1 + beta_f*sA  (|beta| <= |alpha|, so the rounding
+ *               error stays within a few ulp of |alpha||s1| + |beta||s2|).
  *
  *   A_packed   uint32 [B][H][W][Cw]
- *   E_packed   uint32 [kh*kw*Cw][Fp],  ecnt uint32 [F][kh*kw]
+ *   E_packed   uint32 [kh*kw*Cw][Fp]
  *   alpha,beta [F] fp32
  *   Y          fp32 NHWC [B][Ho][Wo][F] out
  *   dbg_s1     optional int32 [B][Ho][Wo][F] out: the integer s1 of every output
  *              (NULL to skip); this is what bit-exact tests compare
- *   ws         scratch of dab_binconv2d_workspace_bytes(d) bytes (NULL if 0)
+ *   ws         scratch of at least dab_binconv2d_workspace_bytes(d) bytes, 256-byte
+ *              aligned; it holds the operands expanded for the matrix cores and is
+ *              dead when the call's work has completed (DAB_ERR_WORKSPACE if NULL,
+ *              too small or misaligned)
+ * Errors: |s1| can reach C*kh*kw, which must stay below 2^24 -> DAB_ERR_UNSUPPORTED
+ * beyond (also for padding >= the kernel extent and tensors past 2^31 bytes expanded).
  */
 int dab_binconv2d(const dab_conv_desc* d /* host */, const uint32_t* A_packed, const uint32_t* E_packed,
-                  const uint32_t* ecnt, const float* alpha, const float* beta,
+                  const float* alpha, const float* beta,
                   float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, void* stream);
 size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d /* host */);
 
@@ -167,11 +175,11 @@ size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d /* host */);
  * spatial extent.  Y[b][f] = alpha_f*s1 + beta_f*s2 over the Kin inputs.
  *
  *   A_packed   uint32 [B][ceil(Kin/32)],  E_packed uint32 [ceil(Kin/32)][Fp]
- *   K          [F] int32, size of the alpha group of every filter (= popc of its bits)
  *   Y          fp32 [B][F] out;  dbg_s1 optional int32 [B][F]
+ *   ws         as for dab_binconv2d, sized by dab_binfc_workspace_bytes
  */
 int dab_binfc(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const uint32_t* E_packed,
-              const int32_t* K, const float* alpha, const float* beta,
+              const float* alpha, const float* beta,
               float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, void* stream);
 size_t dab_binfc_workspace_bytes(int32_t B, int32_t Kin, int32_t F);
 

@@ -53,10 +53,10 @@ _SIGNATURES = {
                                  c_void_p, c_void_p, c_void_p]),
     "dab_pack_activations": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
                                      c_void_p]),
-    "dab_binconv2d": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+    "dab_binconv2d": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p,
                               c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_binconv2d_workspace_bytes": (c_size_t, [ctypes.POINTER(dab_conv_desc)]),
-    "dab_binfc": (c_int, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+    "dab_binfc": (c_int, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                           c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_binfc_workspace_bytes": (c_size_t, [c_int32, c_int32, c_int32]),
 }
@@ -154,23 +154,32 @@ def dab_pack_activations(X, layout=DAB_LAYOUT_NHWC, tau=None, out=None):
     return A
 
 
-def dab_binconv2d(desc, A_packed, E_packed, ecnt, alpha, beta, want_s1=False, out=None):
+def _workspace(nbytes, dev, ws):
+    """A caller-supplied workspace tensor if it is large enough, else a fresh one (None when none is needed)."""
+    if nbytes == 0:
+        return None
+    if ws is not None and ws.numel() * ws.element_size() >= nbytes:
+        return ws
+    return torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+
+def dab_binconv2d(desc, A_packed, E_packed, alpha, beta, want_s1=False, out=None, ws=None):
     """Binarized convolution; returns Y fp32 [B,Ho,Wo,F] (and int32 s1 of the same shape if asked)."""
     dev = A_packed.device
     shape = (desc.B, desc.Ho, desc.Wo, desc.F)
     Y = out if out is not None else torch.empty(shape, dtype=torch.float32, device=dev)
     s1 = torch.empty(shape, dtype=torch.int32, device=dev) if want_s1 else None
     nbytes = lib().dab_binconv2d_workspace_bytes(ctypes.byref(desc))
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev) if nbytes else None
+    ws = _workspace(nbytes, dev, ws)
     _check("dab_binconv2d", lib().dab_binconv2d(
         ctypes.byref(desc), _ptr(A_packed, torch.int32, "A_packed"), _ptr(E_packed, torch.int32, "E_packed"),
-        _ptr(ecnt, torch.int32, "ecnt"), _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
+        _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
         _ptr(Y, torch.float32, "Y"), s1.data_ptr() if want_s1 else None,
         ws.data_ptr() if ws is not None else None, nbytes, _stream()))
     return (Y, s1) if want_s1 else Y
 
 
-def dab_binfc(A_packed, E_packed, K, alpha, beta, Kin, want_s1=False, out=None):
+def dab_binfc(A_packed, E_packed, alpha, beta, Kin, want_s1=False, out=None, ws=None):
     """Binarized fully-connected layer; A_packed [B, Kw], returns Y fp32 [B, F]."""
     dev = A_packed.device
     B = A_packed.shape[0]
@@ -178,10 +187,10 @@ def dab_binfc(A_packed, E_packed, K, alpha, beta, Kin, want_s1=False, out=None):
     Y = out if out is not None else torch.empty((B, F), dtype=torch.float32, device=dev)
     s1 = torch.empty((B, F), dtype=torch.int32, device=dev) if want_s1 else None
     nbytes = lib().dab_binfc_workspace_bytes(B, Kin, F)
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev) if nbytes else None
+    ws = _workspace(nbytes, dev, ws)
     _check("dab_binfc", lib().dab_binfc(
         B, Kin, F, _ptr(A_packed, torch.int32, "A_packed"), _ptr(E_packed, torch.int32, "E_packed"),
-        _ptr(K, torch.int32, "K"), _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
+        _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
         _ptr(Y, torch.float32, "Y"), s1.data_ptr() if want_s1 else None,
         ws.data_ptr() if ws is not None else None, nbytes, _stream()))
     return (Y, s1) if want_s1 else Y

@@ -1,282 +1,345 @@
-// Binarized convolution / fully-connected layer on bit-packed operands (gfx950).
+// Binarized convolution / fully-connected product on the matrix cores (gfx950).
 //
-// Computes Section 4.3.2's forward product of arXiv 1804.02941, the convolution of a
-// +1/-1 input with the two-valued filter W~ = alpha*e + beta*(1-e) of Section 4.1, as
-//   y = alpha*s1 + beta*s2,  s1 = 2*popc(A&E) - popc(E&valid),  s1 + s2 = 2*popc(A) - #valid.
+// Section 4.3.2 of arXiv 1804.02941: the layer output is the ordinary convolution of the
+// +1/-1 input with the two-valued filter W~ = alpha*e + beta*(1-e) (Section 4.1), i.e.
+//   y = alpha*s1 + beta*s2,  s1 = sum_i a_i e_i,  s1 + s2 = sA = sum_i a_i   (taps inside the image).
+// s1 is a dense contraction, so it runs on the MFMA units: both operands are expanded from
+// their packed bits to 4-bit floats (E2M1: +1 = 0x2, -1 = 0xA, 0 = 0x0 for padding), which
+// every product and, in the fp32 accumulator, every sum below 2^24 represents exactly, and
+// multiplied with v_mfma_scale_f32_32x32x64_f8f6f4 (unit scales).  Measured on MI355X this
+// instruction sustains 4.2e15 multiply-accumulates/s at 4 bits per operand element, 6.7 times
+// the AND + BCNT ceiling of the vector ALU on the same bits, which is why the popcount form
+// of the product is not the one that ships.
 //
-// Mapping to the machine.  One lane owns PX output pixels and PX*NT accumulators, one per
-// (pixel, filter) of the wavefront's tile.  The activation words of the lane's pixels come
-// from an LDS copy of the input patch (zero-filled where the window leaves the image);
-// the filter words are the same for every lane of the wavefront, so they are fetched
-// through the scalar data path into SGPRs, 16 consecutive filters per fetch (the weights
-// are stored word-major for exactly this), and used as the scalar operand of v_and_b32.
-// Each AND is followed by one v_bcnt_u32_b32, which adds the population count to the
-// accumulator.  Two VALU instructions per 32 binary multiply-accumulates per lane is the
-// floor for this instruction set; everything else (LDS read, scalar fetch, loop control)
-// is issued on other ports.  A scalar fetch of 16 filter words feeds 32*PX VALU
-// instructions, so PX > 1 both divides the scalar-cache traffic and lengthens the work
-// that hides its latency.
-//
-// Layers with too few outputs to occupy the chip are split along the channel words of the
-// reduction: every split writes integer partial sums to a workspace and a small second
-// kernel adds them and applies the scalars.
+// A launch is two or three kernels:
+//   prepare   one streaming kernel whose blocks (a) expand the activation bits to fp4 with a
+//             zero halo of the padding width, so the main loop needs no bounds checks, and
+//             (b) expand the weight bits to fp4 in the order B fragments are consumed;
+//   main      one workgroup owns 128 filters and keeps their B fragments in LDS (the whole
+//             reduction if it fits in 144 KB, else chunk by chunk).  Each wavefront computes
+//             64 pixels x 128 filters: A fragments (32 pixels x 64 channels, 16 bytes per lane)
+//             come straight from global memory through a register prefetch queue, B fragments
+//             from LDS one step ahead, accumulators stay in registers.  Big layers run
+//             persistent workgroups (one per compute unit) that walk over pixel tiles and
+//             write y directly; layers too small to fill the chip are also split along the
+//             reduction and write their exact partial sums to the workspace.  sA needs no
+//             pass of its own: -1 is the only code with bit 3 set, so two VALU instructions
+//             per fragment word, in the shadow of the MFMAs, count the -1 entries of every
+//             row as the A fragments stream by, and sA = C * (taps inside the image) - 2 * that;
+//   finish    (split launches only) adds the partials, y = (alpha-beta)*s1 + beta*sA.
 #include "dab_internal.h"
 
 namespace dab {
 
 thread_local int g_last_hip_error = 0;
 
-typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-struct ConvGeom {
+constexpr int kNTile = 128;          // filters per workgroup
+constexpr int kMaxChunk = 36;        // k-steps of B fragments held in LDS at a time (36 x 4 KB)
+constexpr int kPrefetch = 4;         // A fragments in flight per 32-pixel row block
+
+struct MfmaGeom {
     int B, H, W, F, kh, kw, ph, pw, sh, sw;
-    int cbits;               // activation bits per tap that count as inputs (C)
-    int Ho, Wo, HoWo, M;     // output extent, M = B*Ho*Wo pixels
-    int Cw, Fp;              // 32-bit words per pixel, filters rounded up to 64
-    int Hp, Wp;              // input extent with the zero border
-    int cc, nchunks;         // channel words held in LDS at a time, number of such chunks
-    int cc_shift;            // log2(cc) when nchunks > 1 (cc is then a power of two)
-    int patch_words;         // LDS words reserved for the input patch
-    int n_mtiles, n_ftiles;  // workgroup tiles over pixels and over filters
-    int ksplit, chunks_per_split;
-    int tiles_per_xcd;       // ceil(n_mtiles * n_ftiles * ksplit / 8)
-    int ecnt_taps;           // entries per filter in the per-tap count array
-    FastDiv d_HoWo, d_Wo, d_Hp, d_roww, d_ftiles, d_ksplit;
+    int C, Cw, KB;                 // channels, 32-bit words per pixel, 64-channel blocks per tap
+    int Ho, Wo, HoWo, M, Hp, Wp, Fp;
+    int nk;                        // k-steps of the whole reduction: taps x KB
+    int ksplit, split_steps;       // reduction splits and k-steps per split
+    int kchunk;                    // k-steps staged in LDS at a time
+    int n_ntiles, n_mtiles;        // 128-filter tiles, pixel tiles of 64 * WAVES
+    int wg_per_ntile;              // persistent workgroups per filter tile (direct mode)
+    FastDiv d_HoWo, d_Wo, d_KB, d_Wp, d_HpWp, d_words, d_nk, d_mtiles, d_ksplit;
+    // block ranges of the prepare kernel
+    unsigned blk_act, blk_wgt;
 };
 
-// acc + popc(x) in one instruction.  Written as asm because the compiler otherwise splits
-// chains of popcount-accumulates into bcnt(x,0) + bcnt(y,0) + a three-operand add, which
-// costs 2.5 instead of 2 VALU instructions per word.
-__device__ __forceinline__ uint32_t popc_add(uint32_t x, uint32_t acc) {
-    uint32_t r;
-    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
-    return r;
+// 8 bits -> 8 nibbles, bit i in bit 0 of nibble i.
+__device__ __forceinline__ uint32_t spread8(uint32_t x) {
+    x = (x | (x << 12)) & 0x000F000Fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    x = (x | (x << 3)) & 0x11111111u;
+    return x;
 }
 
-enum { kModeY = 0, kModeYDebug = 1, kModeSplit = 2 };
-
-// One workgroup: PX * blockDim.x consecutive output pixels (flat index over b, oy, ox;
-// lane t owns pixels m0 + p*blockDim.x + t) times NT consecutive filters.  The grid is
-// one-dimensional; workgroup ids are dealt round-robin to the eight XCDs by the hardware,
-// so id % 8 selects a contiguous eighth of the tile list and the tiles that share an input
-// patch stay on one L2.
-template <int PX, int NT, bool PADDED, int MODE>
-__global__ __launch_bounds__(256) void binconv_kernel(const ConvGeom g, const uint32_t* __restrict__ A,
-                               const uint32_t* __restrict__ E, const uint32_t* __restrict__ ecnt,
-                               const float* __restrict__ alpha, const float* __restrict__ beta,
-                               float* __restrict__ Y, int32_t* __restrict__ dbg_s1,
-                               int32_t* __restrict__ ws_s1, int32_t* __restrict__ ws_sA) {
-    extern __shared__ __align__(16) uint32_t lds[];
-    uint32_t* patch = lds;
-    int* sat = reinterpret_cast<int*>(lds + g.patch_words);   // PADDED: [(kh+1)*(kw+1)][NT], else [NT]
-
-    const int tid = threadIdx.x;
-    const int NTHR = blockDim.x;
-    const int MT = NTHR * PX;
-    int tile = (blockIdx.x & (kNumXCD - 1)) * g.tiles_per_xcd + (blockIdx.x >> 3);
-    if (tile >= g.n_mtiles * g.n_ftiles * g.ksplit) return;
-    int ks = 0;
-    if (MODE == kModeSplit) {
-        const int t = fdiv(tile, g.d_ksplit);
-        ks = tile - t * g.ksplit;
-        tile = t;
-    }
-    const int mt = fdiv(tile, g.d_ftiles);
-    const int m0 = mt * MT;
-    const int ft = tile - mt * g.n_ftiles;
-    const int f0 = ft * NT;
-
-    // ---- geometry of the tile (uniform) and of this lane's pixels
-    const int m_last = min(m0 + MT, g.M) - 1;
-    const int b_first = fdiv(m0, g.d_HoWo);
-    const int oy_first = fdiv(m0 - b_first * g.HoWo, g.d_Wo);
-    const int b_last = fdiv(m_last, g.d_HoWo);
-    const int oy_last = fdiv(m_last - b_last * g.HoWo, g.d_Wo);
-    const int q_lo = b_first * g.Hp + oy_first * g.sh;                 // first padded input row
-    const int rows = b_last * g.Hp + oy_last * g.sh + g.kh - q_lo;     // rows in the patch
-
-    int mpix[PX], oy[PX], ox[PX], lane_base[PX];
+// ---------------------------------------------------------------- prepare
+__global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, const uint32_t* __restrict__ A,
+                                                              const uint32_t* __restrict__ E,
+                                                              uint4* __restrict__ A4, uint4* __restrict__ E4) {
+    unsigned blk = blockIdx.x;
+    if (blk < g.blk_act) {
+        // activations: one thread per 32 channels (one bit word, 16 bytes of fp4) of a padded pixel
+        const long long i = 1ll * blk * 256 + threadIdx.x;
+        const int words = 2 * g.KB;
+        if (i >= 1ll * g.B * g.Hp * g.Wp * words) return;
+        const int pp = fdiv(static_cast<int>(i), g.d_words);      // padded pixel index (< 2^31 / 32)
+        const int w = static_cast<int>(i) - pp * words;
+        const int b = fdiv(pp, g.d_HpWp);
+        const int r = pp - b * g.Hp * g.Wp;
+        const int yp = fdiv(r, g.d_Wp);
+        const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
+        uint4 out = make_uint4(0, 0, 0, 0);
+        if (y >= 0 && y < g.H && x >= 0 && x < g.W && w < g.Cw) {
+            const uint32_t bits = A[((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.Cw + w];
+            const int nv = min(32, g.C - 32 * w);
+            const uint32_t valid = nv == 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
+            uint32_t o[4];
 #pragma unroll
-    for (int p = 0; p < PX; ++p) {
-        mpix[p] = min(m0 + p * NTHR + tid, g.M - 1);
-        const int b = fdiv(mpix[p], g.d_HoWo);
-        const int r_ = mpix[p] - b * g.HoWo;
-        oy[p] = fdiv(r_, g.d_Wo);
-        ox[p] = r_ - oy[p] * g.Wo;
-        lane_base[p] = ((b * g.Hp + oy[p] * g.sh - q_lo) * g.Wp + ox[p] * g.sw) * g.cc;
-    }
-
-    // ---- per-filter counts of this tile: summed-area table over the taps when the window
-    // can leave the image, the plain total (= K_f) otherwise
-    const int ntaps = g.kh * g.kw;
-    if (PADDED) {
-        const int sw1 = g.kw + 1;
-        for (int f = tid; f < NT; f += NTHR) {
-            const bool live = f0 + f < g.F;
-            for (int kx = 0; kx <= g.kw; ++kx) sat[kx * NT + f] = 0;
-            for (int ky = 0; ky < g.kh; ++ky) {
-                int run = 0;
-                sat[((ky + 1) * sw1) * NT + f] = 0;
-                for (int kx = 0; kx < g.kw; ++kx) {
-                    run += live ? static_cast<int>(ecnt[(size_t)(f0 + f) * ntaps + ky * g.kw + kx]) : 0;
-                    sat[((ky + 1) * sw1 + kx + 1) * NT + f] = sat[(ky * sw1 + kx + 1) * NT + f] + run;
-                }
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t s = spread8((bits >> (8 * q)) & 0xFFu);
+                const uint32_t v = spread8((valid >> (8 * q)) & 0xFFu) * 0xFu;
+                o[q] = (0xAAAAAAAAu ^ (s << 3)) & v;                // bit 1 -> +1.0, bit 0 -> -1.0, past C -> 0
             }
+            out = make_uint4(o[0], o[1], o[2], o[3]);
         }
+        A4[i] = out;
+        return;
+    }
+    blk -= g.blk_act;
+    {
+        // weights: bits [R][Fp] -> fragments [ntile][kstep][4 column blocks][k half][32 filters][16 bytes]
+        const long long i = 1ll * blk * 256 + threadIdx.x;
+        if (i >= 1ll * g.n_ntiles * g.nk * 256) return;
+        const int fl = static_cast<int>(i & 31);
+        const int half = static_cast<int>((i >> 5) & 1);
+        const int nf = static_cast<int>((i >> 6) & 3);
+        const int tk = static_cast<int>(i >> 8);
+        const int nt = fdiv(tk, g.d_nk);
+        const int ks = tk - nt * g.nk;
+        const int tap = fdiv(ks, g.d_KB);
+        const int w = 2 * (ks - tap * g.KB) + half;
+        const int f = nt * kNTile + nf * 32 + fl;
+        uint4 out = make_uint4(0, 0, 0, 0);
+        if (w < g.Cw && f < g.Fp) {
+            const uint32_t bits = E[static_cast<size_t>(tap * g.Cw + w) * g.Fp + f];
+            out = make_uint4(spread8(bits & 0xFFu) << 1, spread8((bits >> 8) & 0xFFu) << 1,
+                             spread8((bits >> 16) & 0xFFu) << 1, spread8(bits >> 24) << 1);   // bit 1 -> 1.0
+        }
+        E4[i] = out;
+    }
+}
+
+// ---------------------------------------------------------------- main
+__device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
+    const v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0};
+    const v8i b8 = {b.x, b.y, b.z, b.w, 0, 0, 0, 0};
+    // cbsz = blgp = 4 selects fp4 for both operands; scale bytes 0x7f = 2^0
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+}
+
+enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2 };
+
+template <int WAVES, int MODE>
+__global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom g, const char* __restrict__ A4,
+                                                                  const uint4* __restrict__ E4,
+                                                                  const float* __restrict__ alpha,
+                                                                  const float* __restrict__ beta,
+                                                                  float* __restrict__ Y, int32_t* __restrict__ dbg_s1,
+                                                                  float* __restrict__ ws_s1, float* __restrict__ ws_sA) {
+    constexpr int THREADS = 64 * WAVES;
+    constexpr int MTILE = 64 * WAVES;
+    extern __shared__ __align__(16) uint4 panel[];                 // [kchunk][4][64 lanes] 16-byte groups
+    __shared__ __align__(16) float sA_lds[WAVES][64];              // row sums of each wavefront's 64 pixels
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int ntile, mt_first, mt_step, kbeg, kend, ksplit_id = 0;
+    if (MODE == kOutSplit) {
+        // one unit per workgroup: (filter tile, pixel tile, reduction split)
+        const int u = fdiv(blockIdx.x, g.d_ksplit);
+        const int ks = blockIdx.x - u * g.ksplit;
+        ksplit_id = ks;
+        ntile = fdiv(u, g.d_mtiles);
+        mt_first = u - ntile * g.n_mtiles;
+        mt_step = g.n_mtiles;                                      // a single tile
+        kbeg = ks * g.split_steps;
+        kend = min(g.nk, kbeg + g.split_steps);
     } else {
-        for (int f = tid; f < NT; f += NTHR) {
-            int tot = 0;
-            if (f0 + f < g.F)
-                for (int t = 0; t < g.ecnt_taps; ++t) tot += static_cast<int>(ecnt[(size_t)(f0 + f) * g.ecnt_taps + t]);
-            sat[f] = tot;
-        }
+        ntile = blockIdx.x / g.wg_per_ntile;
+        mt_first = blockIdx.x - ntile * g.wg_per_ntile;
+        mt_step = g.wg_per_ntile;
+        kbeg = 0;
+        kend = g.nk;
+    }
+    const int f0 = ntile * kNTile;
+    const uint4* Epanel = E4 + static_cast<size_t>(ntile) * g.nk * 256;
+    const int nchunks = (kend - kbeg + g.kchunk - 1) / g.kchunk;
+
+    // per-lane scalars of the four 32-filter column blocks
+    float dcol[4], bcol[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int f = min(f0 + j * 32 + (lane & 31), g.F - 1);
+        const float al = alpha[f], be = beta[f];
+        dcol[j] = al - be;
+        bcol[j] = be;
     }
 
-    uint32_t acc[PX][NT];
-    uint32_t pA[PX];
+    bool staged = false;
+    for (int mt = mt_first; mt < g.n_mtiles; mt += mt_step) {
+        const int m_base = mt * MTILE + wave * 64;
+        int pixoff[2], mvalid[2];
+        uint32_t neg[2] = {0u, 0u};                                  // -1 entries seen in this lane's half rows
 #pragma unroll
-    for (int p = 0; p < PX; ++p) {
-        pA[p] = 0;
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[p][j] = 0;
-    }
-
-    const int row_words = g.Wp * g.cc;
-    const int patch_fill = rows * row_words;
-    const int chunk_lo = MODE == kModeSplit ? ks * g.chunks_per_split : 0;
-    const int chunk_hi = MODE == kModeSplit ? min(g.nchunks, chunk_lo + g.chunks_per_split) : g.nchunks;
-
-    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
-        const int c0 = chunk * g.cc;
-        if (chunk != chunk_lo) __syncthreads();
-        // ---- stage the patch, zero outside the image
-        if (g.nchunks == 1) {
-            // whole channel depth: a padded row is [zeros | W*Cw contiguous source words | zeros]
-            const int lo = g.pw * g.Cw, hi = (g.pw + g.W) * g.Cw;
-            for (int el = tid; el < patch_fill; el += NTHR) {
-                const int r = fdiv(el, g.d_roww);
-                const int e = el - r * row_words;
-                const int q = q_lo + r;
-                const int qb = fdiv(q, g.d_Hp);
-                const int iy = q - qb * g.Hp - g.ph;
-                const bool ok = qb < g.B && iy >= 0 && iy < g.H && e >= lo && e < hi;
-                patch[el] = ok ? A[((size_t)(qb * g.H + iy) * g.W) * g.Cw + (e - lo)] : 0u;
-            }
-        } else {
-            for (int el = tid; el < patch_fill; el += NTHR) {
-                const int r = fdiv(el, g.d_roww);
-                const int e = el - r * row_words;
-                const int xp = e >> g.cc_shift, k = e & (g.cc - 1);
-                const int q = q_lo + r;
-                const int qb = fdiv(q, g.d_Hp);
-                const int iy = q - qb * g.Hp - g.ph;
-                const int ix = xp - g.pw, c = c0 + k;
-                const bool ok = qb < g.B && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W && c < g.Cw;
-                patch[el] = ok ? A[((size_t)(qb * g.H + iy) * g.W + ix) * g.Cw + c] : 0u;
-            }
+        for (int i = 0; i < 2; ++i) {
+            const int m = min(m_base + i * 32 + (lane & 31), g.M - 1);
+            const int b = fdiv(m, g.d_HoWo);
+            const int r = m - b * g.HoWo;
+            const int oy = fdiv(r, g.d_Wo);
+            const int ox = r - oy * g.Wo;
+            pixoff[i] = (((b * g.Hp + oy * g.sh) * g.Wp + ox * g.sw) * g.KB) * 32 + (lane >> 5) * 16;
+            const int ty = min(g.H, oy * g.sh - g.ph + g.kh) - max(0, oy * g.sh - g.ph);
+            const int tx = min(g.W, ox * g.sw - g.pw + g.kw) - max(0, ox * g.sw - g.pw);
+            mvalid[i] = g.C * ty * tx;                               // inputs of this pixel inside the image
         }
-        __syncthreads();
+        v16f acc[2][4];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-        // ---- AND + popcount over taps and channel words, one activation word per pixel and
-        // step.  The filter words of the next group of 16 filters (and the next activation
-        // words) are requested before the current group is consumed, so the scalar fetch
-        // latency overlaps 32*PX VALU instructions.
-        const int cc_here = min(g.cc, g.Cw - c0);
-        const int nsteps = ntaps * cc_here;
-        constexpr int NJ = NT / 16;
-        const u32x16* Eb = reinterpret_cast<const u32x16*>(E + f0);
-        const int stride16 = g.Fp >> 4;
-        int ky = 0, kx = 0, k = 0, erow = c0;
-        u32x16 cur = Eb[(size_t)erow * stride16];
-        uint32_t a[PX];
+        for (int chunk = 0; chunk < nchunks; ++chunk) {
+            const int ks0 = kbeg + chunk * g.kchunk;
+            const int ks1 = min(kend, ks0 + g.kchunk);
+            // k-steps of this chunk rounded up to the prefetch depth; the extra steps multiply
+            // zero B fragments (and re-read the last valid A fragment), so the loop has no tail
+            const int steps = (ks1 - ks0 + kPrefetch - 1) / kPrefetch * kPrefetch;
+            if (!staged || nchunks > 1) {
+                __syncthreads();                                   // previous users of the panel are done
+                const int groups = (ks1 - ks0) * 256;
+                // eight 16-byte groups in flight per thread: the copy is latency-bound otherwise
+                for (int e0 = 0; e0 < steps * 256; e0 += 8 * THREADS) {
+                    uint4 t[8];
 #pragma unroll
-        for (int p = 0; p < PX; ++p) a[p] = patch[lane_base[p]];
-        for (int s = 0; s < nsteps; ++s) {
-            int nk = k + 1, nkx = kx, nky = ky;
-            if (nk == cc_here) { nk = 0; ++nkx; if (nkx == g.kw) { nkx = 0; ++nky; } }
-            const bool last = s + 1 == nsteps;
-            const int nerow = last ? c0 : (nky * g.kw + nkx) * g.Cw + c0 + nk;
-            const int ntap = last ? 0 : (nky * g.Wp + nkx) * g.cc + nk;
-            uint32_t a_next[PX];
+                    for (int u = 0; u < 8; ++u) {
+                        const int e = e0 + u * THREADS + tid;
+                        t[u] = e < groups ? Epanel[static_cast<size_t>(ks0) * 256 + e] : make_uint4(0, 0, 0, 0);
+                    }
 #pragma unroll
-            for (int p = 0; p < PX; ++p) a_next[p] = patch[lane_base[p] + ntap];
-            const u32x16* ethis = Eb + (size_t)erow * stride16;
-            const u32x16* enext = Eb + (size_t)nerow * stride16;
-#pragma unroll
-            for (int p = 0; p < PX; ++p) pA[p] = popc_add(a[p], pA[p]);
-#pragma unroll
-            for (int jb = 0; jb < NJ; ++jb) {
-                const u32x16 nxt = jb + 1 < NJ ? ethis[jb + 1] : enext[0];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-#pragma unroll
-                    for (int p = 0; p < PX; ++p)
-                        acc[p][jb * 16 + j] = popc_add(a[p] & cur[j], acc[p][jb * 16 + j]);
+                    for (int u = 0; u < 8; ++u) {
+                        const int e = e0 + u * THREADS + tid;
+                        if (e < steps * 256) panel[e] = t[u];
+                    }
                 }
-                cur = nxt;
+                __syncthreads();
+                staged = true;
             }
+            // A fragments: a queue of kPrefetch k-steps per row block, refilled as it drains.
+            // The byte offset of the k-step being fetched is tracked with scalar counters
+            // (channel block, then tap column, then tap row) and stops at the last step.
+            int pf = ks0;
+            int pkb, pkx, pky;
+            {
+                const int tap = ks0 / g.KB;
+                pkb = ks0 - tap * g.KB;
+                pky = tap / g.kw;
+                pkx = tap - pky * g.kw;
+            }
+            int poff = ((pky * g.Wp + pkx) * g.KB + pkb) * 32;
+            auto advance = [&]() {   // branch-free, so the k loop stays one basic block
+                const int go = pf < ks1 - 1 ? 1 : 0;
+                pf += go;
+                pkb += go;
+                const int wrap_b = pkb == g.KB ? 1 : 0;
+                pkb = wrap_b ? 0 : pkb;
+                pkx += wrap_b;
+                const int wrap_x = pkx == g.kw ? 1 : 0;
+                pkx = wrap_x ? 0 : pkx;
+                pky += wrap_x;
+                poff = ((pky * g.Wp + pkx) * g.KB + pkb) * 32;
+            };
+            v4i abuf[kPrefetch][2];
 #pragma unroll
-            for (int p = 0; p < PX; ++p) a[p] = a_next[p];
-            k = nk; kx = nkx; ky = nky; erow = nerow;
-        }
-    }
-
-    // ---- epilogue: integers -> fp32, recombined with the per-filter scalars.
-    // alpha*s1 + beta*s2 is evaluated as (alpha-beta)*s1 + beta*(s1+s2): |beta| <= |alpha|, so
-    // the rounding error stays within a few ulp of |alpha||s1| + |beta||s2|.
-    const bool full = f0 + NT <= g.F && (g.F & 3) == 0;
-    const bool first_split = MODE != kModeSplit || ks == 0;
+            for (int d = 0; d < kPrefetch; ++d) {
 #pragma unroll
-    for (int p = 0; p < PX; ++p) {
-        int ky0 = 0, ky1 = g.kh, kx0 = 0, kx1 = g.kw;
-        if (PADDED) {
-            ky0 = max(0, g.ph - oy[p] * g.sh);
-            ky1 = min(g.kh, g.H + g.ph - oy[p] * g.sh);
-            kx0 = max(0, g.pw - ox[p] * g.sw);
-            kx1 = min(g.kw, g.W + g.pw - ox[p] * g.sw);
-        }
-        const int mvalid = g.cbits * (ky1 - ky0) * (kx1 - kx0);
-        const int sA = 2 * static_cast<int>(pA[p]) - (first_split ? mvalid : 0);   // s1 + s2
-        const float fsA = static_cast<float>(sA);
-        const int sw1 = g.kw + 1;
-        const int* s11 = PADDED ? sat + (ky1 * sw1 + kx1) * NT : sat;
-        const int* s01 = sat + (ky0 * sw1 + kx1) * NT;
-        const int* s10 = sat + (ky1 * sw1 + kx0) * NT;
-        const int* s00 = sat + (ky0 * sw1 + kx0) * NT;
-        const bool live = m0 + p * NTHR + tid < g.M;
-        const size_t orow = (size_t)mpix[p] * g.F + f0;
-        if (MODE == kModeSplit && live && ft == 0) ws_sA[(size_t)ks * g.M + mpix[p]] = sA;
-        int32_t* irow = MODE == kModeSplit ? ws_s1 + (size_t)ks * g.M * g.F + orow
-                                           : (MODE == kModeYDebug ? dbg_s1 + orow : nullptr);
+                for (int i = 0; i < 2; ++i) abuf[d][i] = *reinterpret_cast<const v4i*>(A4 + pixoff[i] + poff);
+                advance();
+            }
+            const uint4* bp = panel + lane;
+            uint4 bq[2][4];
 #pragma unroll
-        for (int j4 = 0; j4 < NT / 4; ++j4) {
-            float y[4];
-            int s1v[4];
+            for (int j = 0; j < 4; ++j) bq[0][j] = bp[j * 64];
+            for (int st = 0; st < steps; st += kPrefetch) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int j = j4 * 4 + t;
-                int c1 = s11[j];
-                if (PADDED) c1 = c1 - s01[j] - s10[j] + s00[j];
-                const int s1 = 2 * static_cast<int>(acc[p][j]) - (first_split ? c1 : 0);
-                s1v[t] = s1;
-                if (MODE != kModeSplit) {
-                    const int f = min(f0 + j, g.F - 1);
-                    const float al = alpha[f], be = beta[f];
-                    y[t] = fmaf(al - be, static_cast<float>(s1), be * fsA);
+                for (int d = 0; d < kPrefetch; ++d) {
+                    // B fragments of the next step are read while this step multiplies
+                    const uint4* bn = bp + static_cast<size_t>(min(st + d + 1, steps - 1)) * 256;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) bq[(d + 1) & 1][j] = bn[j * 64];
+                    const v4i a0 = abuf[d][0], a1 = abuf[d][1];
+                    {
+                        // bit 3 of a nibble is set only for -1; steps past the chunk's end repeat the
+                        // last fragment and are masked out
+                        const uint32_t keep = ks0 + st + d < ks1 ? 0x88888888u : 0u;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            neg[0] += __builtin_popcount(static_cast<uint32_t>(a0[c]) & keep);
+                            neg[1] += __builtin_popcount(static_cast<uint32_t>(a1[c]) & keep);
+                        }
+                    }
+                    abuf[d][0] = *reinterpret_cast<const v4i*>(A4 + pixoff[0] + poff);
+                    abuf[d][1] = *reinterpret_cast<const v4i*>(A4 + pixoff[1] + poff);
+                    advance();
+                    __builtin_amdgcn_sched_barrier(0);   // keep the fetches ahead of the multiplies
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint4 bu = bq[d & 1][j];
+                        const v4i bv = {static_cast<int>(bu.x), static_cast<int>(bu.y), static_cast<int>(bu.z),
+                                        static_cast<int>(bu.w)};
+                        acc[0][j] = mfma_fp4(a0, bv, acc[0][j]);
+                        acc[1][j] = mfma_fp4(a1, bv, acc[1][j]);
+                    }
                 }
             }
-            if (live) {
-                if (full) {
-                    if (MODE != kModeSplit)
-                        *reinterpret_cast<float4*>(Y + orow + j4 * 4) = make_float4(y[0], y[1], y[2], y[3]);
-                    if (MODE != kModeY)
-                        *reinterpret_cast<int4*>(irow + j4 * 4) = make_int4(s1v[0], s1v[1], s1v[2], s1v[3]);
-                } else {
+        }
+
+        // ---- row sums: the two k halves of a row sit in lanes l and l + 32
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        if (f0 + j4 * 4 + t < g.F) {
-                            if (MODE != kModeSplit) Y[orow + j4 * 4 + t] = y[t];
-                            if (MODE != kModeY) irow[j4 * 4 + t] = s1v[t];
+        for (int i = 0; i < 2; ++i) {
+            const int n2 = static_cast<int>(neg[i]) + __shfl_xor(static_cast<int>(neg[i]), 32, 64);
+            const bool first = MODE != kOutSplit || ksplit_id == 0;
+            const float srow = static_cast<float>((first ? mvalid[i] : 0) - 2 * n2);   // sA (or this split's share)
+            if (lane < 32) sA_lds[wave][i * 32 + lane] = srow;
+        }
+        // (the wavefront reads back only what it wrote itself: no workgroup barrier needed)
+
+        // ---- epilogue.  Register v of a 32x32 block is row (v/4)*8 + (lane/32)*4 + v%4,
+        // column lane%32, so the 32 lanes of a half-wavefront touch 128 contiguous bytes of one
+        // output row.  Direct mode: y = (alpha - beta)*s1 + beta*sA; interior tiles store
+        // without any predicate, so nothing orders one store behind another.  Split mode: the
+        // exact partial s1 (and the partial row sum) go to this split's slice of the workspace.
+        const bool interior = m_base + 64 <= g.M && f0 + kNTile <= g.F;
+        float4 s4[2][4];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                s4[i][q] = *reinterpret_cast<const float4*>(&sA_lds[wave][i * 32 + q * 8 + (lane >> 5) * 4]);
+        float* out = MODE == kOutSplit ? ws_s1 + static_cast<size_t>(ksplit_id) * g.M * g.F : Y;
+        if (MODE == kOutSplit && ntile == 0 && lane < 32) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = m_base + i * 32 + lane;
+                if (row < g.M) ws_sA[static_cast<size_t>(ksplit_id) * g.M + row] = sA_lds[wave][i * 32 + lane];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int row = m_base + i * 32 + q * 8 + (lane >> 5) * 4 + t;
+                    const size_t o = static_cast<size_t>(row) * g.F + f0 + (lane & 31);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float s1 = acc[i][j][q * 4 + t];
+                        if (interior || (row < g.M && f0 + j * 32 + (lane & 31) < g.F)) {
+                            out[o + j * 32] = MODE == kOutSplit ? s1 : fmaf(dcol[j], s1, bcol[j] * sv[t]);
+                            if (MODE == kOutYDebug) dbg_s1[o + j * 32] = static_cast<int>(s1);
                         }
                     }
                 }
@@ -285,9 +348,9 @@ __global__ __launch_bounds__(256) void binconv_kernel(const ConvGeom g, const ui
     }
 }
 
-// Second kernel of a split launch: add the integer partial sums and apply the scalars.
-__global__ __launch_bounds__(256) void binconv_finish_kernel(const int32_t* __restrict__ ws_s1,
-                                                             const int32_t* __restrict__ ws_sA,
+// ---------------------------------------------------------------- finish (split launches)
+__global__ __launch_bounds__(256) void binconv_finish_kernel(const float* __restrict__ ws_s1,
+                                                             const float* __restrict__ ws_sA,
                                                              const float* __restrict__ alpha,
                                                              const float* __restrict__ beta, float* __restrict__ Y,
                                                              int32_t* __restrict__ dbg_s1, int M, int F, int ksplit) {
@@ -296,193 +359,141 @@ __global__ __launch_bounds__(256) void binconv_finish_kernel(const int32_t* __re
     if (i >= total) return;
     const int m = static_cast<int>(i / F);
     const int f = static_cast<int>(i - static_cast<size_t>(m) * F);
-    int s1 = 0, sA = 0;
+    float s1 = 0.f, sA = 0.f;                       // integer-valued, exact in any order
     for (int k = 0; k < ksplit; ++k) {
         s1 += ws_s1[static_cast<size_t>(k) * total + i];
         sA += ws_sA[static_cast<size_t>(k) * M + m];
     }
     const float al = alpha[f], be = beta[f];
-    Y[i] = fmaf(al - be, static_cast<float>(s1), be * static_cast<float>(sA));
-    if (dbg_s1) dbg_s1[i] = s1;
+    Y[i] = fmaf(al - be, s1, be * sA);
+    if (dbg_s1) dbg_s1[i] = static_cast<int>(s1);
 }
 
 // ------------------------------------------------------------------ host side
 
-constexpr int kPatchCapWords = 12 * 1024;   // 48 KB of LDS for the input patch
-
-struct ConvPlan {
-    ConvGeom g;
-    int PX, NT, NW;          // pixels per lane, filters per tile, wavefronts per workgroup
-    bool padded;
-    size_t lds_bytes, ws_bytes;
+struct MfmaPlan {
+    MfmaGeom g;
+    int waves;
+    bool split;
+    size_t a4_bytes, e4_bytes, sa_bytes, s1_bytes, ws_bytes, lds_bytes;
+    unsigned grid;
 };
 
-#ifdef DAB_TUNING
-static int g_force[4] = {0, 0, 0, 0};   // PX, NT, NW, KS; 0 = heuristic
-#endif
+static size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
-// Largest number of padded input rows any tile of MT consecutive pixels touches.
-static int max_patch_rows(const ConvGeom& g, int MT) {
-    int worst = 0;
-    for (int m0 = 0; m0 < g.M; m0 += MT) {
-        const int ml = (m0 + MT < g.M ? m0 + MT : g.M) - 1;
-        const int b0 = m0 / g.HoWo, oy0 = (m0 % g.HoWo) / g.Wo;
-        const int b1 = ml / g.HoWo, oy1 = (ml % g.HoWo) / g.Wo;
-        const int rows = b1 * g.Hp + oy1 * g.sh + g.kh - (b0 * g.Hp + oy0 * g.sh);
-        if (rows > worst) worst = rows;
-    }
-    return worst;
-}
-
-static int plan_conv(const dab_conv_desc& d, ConvPlan* plan) {
-    ConvGeom& g = plan->g;
-    g = ConvGeom{};
+static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
+    MfmaGeom& g = pl->g;
+    g = MfmaGeom{};
     g.B = d.B; g.H = d.H; g.W = d.W; g.F = d.F; g.kh = d.kh; g.kw = d.kw;
     g.ph = d.pad_h; g.pw = d.pad_w; g.sh = d.stride_h; g.sw = d.stride_w;
+    g.C = d.C; g.Cw = ceil_div(d.C, 32); g.KB = ceil_div(d.C, 64);
     g.Ho = (d.H + 2 * d.pad_h - d.kh) / d.stride_h + 1;
     g.Wo = (d.W + 2 * d.pad_w - d.kw) / d.stride_w + 1;
-    g.Cw = ceil_div(d.C, 32);
-    g.cbits = d.C;
-    g.ecnt_taps = d.kh * d.kw;
-    if (1ll * d.kh * d.kw * g.Cw >= (1ll << 24)) return DAB_ERR_UNSUPPORTED;
-    if (g.Ho == 1 && g.Wo == 1 && d.pad_h == 0 && d.pad_w == 0) {
-        // The window is the whole image: the same product as a fully-connected layer over
-        // kh*kw*Cw words per image (the packed layouts coincide).
-        g.Cw *= d.kh * d.kw;
-        g.cbits *= d.kh * d.kw;
-        g.H = g.W = g.kh = g.kw = 1;
-        g.sh = g.sw = 1;
-    }
     g.HoWo = g.Ho * g.Wo;
-    const long long M = 1ll * d.B * g.HoWo;
+    g.Hp = d.H + 2 * d.pad_h; g.Wp = d.W + 2 * d.pad_w;
     g.Fp = 64 * ceil_div(d.F, 64);
-    g.Hp = g.H + 2 * g.ph;
-    g.Wp = g.W + 2 * g.pw;
-    if (M >= (1ll << 30) || 1ll * M * d.F >= (1ll << 40) || 1ll * d.B * g.Hp >= (1ll << 30))
-        return DAB_ERR_UNSUPPORTED;
+    const long long M = 1ll * d.B * g.HoWo;
+    const long long a4 = 1ll * d.B * g.Hp * g.Wp * g.KB * 32;
+    const long long nk = 1ll * d.kh * d.kw * g.KB;
+    if (M >= (1ll << 30) || a4 >= (1ll << 31) || nk >= (1 << 20) || 1ll * M * d.F >= (1ll << 40)) return DAB_ERR_UNSUPPORTED;
+    if (1ll * d.C * d.kh * d.kw >= (1ll << 24)) return DAB_ERR_UNSUPPORTED;   // |s1| must stay exact in fp32
     g.M = static_cast<int>(M);
+    g.nk = static_cast<int>(nk);
+    g.n_ntiles = ceil_div(d.F, kNTile);
+    if (1ll * g.n_ntiles * g.nk >= (1ll << 22)) return DAB_ERR_UNSUPPORTED;
 
-    // Tile shape.  Measured on MI355X, one pixel per lane and 16 filters per tile is the best
-    // or within a few percent of the best on every layer shape tried: the scalar fetches are
-    // not the limiter, and many small wavefront tiles balance the SIMDs and spread the output
-    // stores over the run.  Layers that still leave SIMDs idle are split along the reduction,
-    // unless they are so small that a second kernel costs more than it saves.
-    int PX = 1, NT = 16;
-    const long long waves = 1ll * ceil_div(g.M, 64 * PX) * ceil_div(d.F, NT);
-    const long long steps = 1ll * g.kh * g.kw * g.Cw;
-    int KS = 1;
-    if (waves < 2ll * 4 * kNumCU && steps >= 64) KS = static_cast<int>((4ll * 4 * kNumCU + waves - 1) / waves);
-    int NW = 4;
-    while (NW > 1 && 1ll * ceil_div(g.M, 64 * PX * NW) * ceil_div(d.F, NT) * KS < 2 * kNumCU) NW >>= 1;
-#ifdef DAB_TUNING
-    if (g_force[0]) PX = g_force[0];
-    if (g_force[1]) NT = g_force[1];
-    if (g_force[2]) NW = g_force[2];
-    if (g_force[3]) KS = g_force[3];
-#endif
-
-    // Channel words per LDS pass: everything if the patch fits and no split is wanted,
-    // else a power of two small enough for both.
-    int rows = 0;
-    for (;; NW >>= 1) {
-        rows = max_patch_rows(g, 64 * PX * NW);
-        if (1ll * rows * g.Wp <= kPatchCapWords || NW == 1) break;
+    // Workgroup shape and split.  Eight wavefronts (two per SIMD, 512 pixels per tile) overlap
+    // one wavefront's stores with another's multiplies and win on large layers; four keep more
+    // compute units busy on mid-sized ones.  When even 256-pixel tiles leave most compute
+    // units idle, the reduction is split until about one unit per compute unit exists.
+    const int tiles256 = ceil_div(g.M, 256) * g.n_ntiles;
+    pl->waves = 1ll * ceil_div(g.M, 512) * g.n_ntiles >= kNumCU ? 8 : 4;
+    g.ksplit = 1;
+    if (tiles256 * 2 <= kNumCU) {
+        g.ksplit = kNumCU / tiles256;
+        const int max_split = g.nk / (2 * kPrefetch);              // at least two prefetch groups per split
+        if (g.ksplit > max_split) g.ksplit = max_split;
+        if (g.ksplit < 1) g.ksplit = 1;
     }
-    if (1ll * rows * g.Wp > kPatchCapWords) return DAB_ERR_UNSUPPORTED;
-    if (KS > g.Cw) KS = g.Cw;
-    if (KS == 1 && 1ll * rows * g.Wp * g.Cw <= kPatchCapWords) {
-        g.cc = g.Cw; g.nchunks = 1; g.cc_shift = 0;
-    } else {
-        int sh = 0;
-        while (1ll * rows * g.Wp * (2 << sh) <= kPatchCapWords && (2 << sh) * KS <= g.Cw) ++sh;
-        g.cc = 1 << sh; g.cc_shift = sh; g.nchunks = ceil_div(g.Cw, g.cc);
-    }
-    g.chunks_per_split = ceil_div(g.nchunks, KS);
-    g.ksplit = ceil_div(g.nchunks, g.chunks_per_split);
-    g.patch_words = (rows * g.Wp * g.cc + 3) & ~3;
-    g.n_mtiles = ceil_div(g.M, 64 * PX * NW);
-    g.n_ftiles = ceil_div(d.F, NT);
-    const long long ntiles = 1ll * g.n_mtiles * g.n_ftiles * g.ksplit;
-    if (ntiles >= (1ll << 28)) return DAB_ERR_UNSUPPORTED;
-    g.tiles_per_xcd = static_cast<int>((ntiles + kNumXCD - 1) / kNumXCD);
-    g.d_HoWo = make_fastdiv(g.HoWo);
-    g.d_Wo = make_fastdiv(g.Wo);
-    g.d_Hp = make_fastdiv(g.Hp);
-    g.d_roww = make_fastdiv(g.Wp * g.cc);
-    g.d_ftiles = make_fastdiv(g.n_ftiles);
-    g.d_ksplit = make_fastdiv(g.ksplit);
+    g.split_steps = ceil_div(g.nk, g.ksplit);
+    g.ksplit = ceil_div(g.nk, g.split_steps);
+    pl->split = g.ksplit > 1;
+    if (pl->split) pl->waves = 4;
+    const int span = pl->split ? g.split_steps : g.nk;
+    const int nchunks = ceil_div(span, kMaxChunk);
+    g.kchunk = ceil_div(ceil_div(span, nchunks), kPrefetch) * kPrefetch;
+    g.n_mtiles = ceil_div(g.M, 64 * pl->waves);
+    g.wg_per_ntile = kNumCU / g.n_ntiles;
+    if (g.wg_per_ntile < 1) g.wg_per_ntile = 1;
+    if (g.wg_per_ntile > g.n_mtiles) g.wg_per_ntile = g.n_mtiles;
+    pl->grid = pl->split ? static_cast<unsigned>(g.n_ntiles * g.n_mtiles * g.ksplit)
+                         : static_cast<unsigned>(g.wg_per_ntile * g.n_ntiles);
 
-    plan->PX = PX; plan->NT = NT; plan->NW = NW;
-    plan->padded = g.ph > 0 || g.pw > 0;
-    const size_t sat_words = plan->padded ? static_cast<size_t>(g.kh + 1) * (g.kw + 1) * NT : NT;
-    plan->lds_bytes = (g.patch_words + sat_words) * sizeof(uint32_t);
-    if (plan->lds_bytes > 64 * 1024) return DAB_ERR_UNSUPPORTED;
-    plan->ws_bytes = g.ksplit > 1 ? static_cast<size_t>(g.ksplit) * g.M * (static_cast<size_t>(d.F) + 1) * sizeof(int32_t) : 0;
+    g.d_HoWo = make_fastdiv(g.HoWo); g.d_Wo = make_fastdiv(g.Wo); g.d_KB = make_fastdiv(g.KB);
+    g.d_Wp = make_fastdiv(g.Wp); g.d_HpWp = make_fastdiv(g.Hp * g.Wp); g.d_words = make_fastdiv(2 * g.KB);
+    g.d_nk = make_fastdiv(g.nk); g.d_mtiles = make_fastdiv(g.n_mtiles); g.d_ksplit = make_fastdiv(g.ksplit);
+
+    pl->a4_bytes = round256(static_cast<size_t>(a4));
+    pl->e4_bytes = static_cast<size_t>(g.n_ntiles) * g.nk * 4096;
+    pl->sa_bytes = pl->split ? round256(static_cast<size_t>(g.ksplit) * g.M * 4) : 0;
+    pl->s1_bytes = pl->split ? round256(static_cast<size_t>(g.ksplit) * g.M * d.F * 4) : 0;
+    pl->ws_bytes = pl->a4_bytes + pl->e4_bytes + pl->sa_bytes + pl->s1_bytes;
+    pl->lds_bytes = static_cast<size_t>(g.kchunk) * 4096;
+
+    g.blk_act = static_cast<unsigned>((a4 / 16 + 255) / 256);
+    g.blk_wgt = static_cast<unsigned>((1ll * g.n_ntiles * g.nk * 256 + 255) / 256);
     return DAB_OK;
 }
 
-template <int PX, int NT>
-static void launch_tile(const ConvPlan& pl, int mode, hipStream_t st, const uint32_t* A, const uint32_t* E,
-                        const uint32_t* ecnt, const float* alpha, const float* beta, float* Y, int32_t* dbg_s1,
-                        int32_t* ws_s1, int32_t* ws_sA) {
-    const dim3 grid(pl.g.tiles_per_xcd * kNumXCD), block(64 * pl.NW);
-#define DAB_GO(PAD, MODE)                                                                                   \
-    hipLaunchKernelGGL((binconv_kernel<PX, NT, PAD, MODE>), grid, block, pl.lds_bytes, st, pl.g, A, E, ecnt, \
-                       alpha, beta, Y, dbg_s1, ws_s1, ws_sA)
-    if (pl.padded) {
-        if (mode == kModeY) DAB_GO(true, kModeY);
-        else if (mode == kModeYDebug) DAB_GO(true, kModeYDebug);
-        else DAB_GO(true, kModeSplit);
-    } else {
-        if (mode == kModeY) DAB_GO(false, kModeY);
-        else if (mode == kModeYDebug) DAB_GO(false, kModeYDebug);
-        else DAB_GO(false, kModeSplit);
+template <int WAVES, int MODE>
+static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const uint4* e4, float* sa,
+                       const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, float* ws_s1) {
+    static thread_local size_t granted = 0;
+    if (pl.lds_bytes > 48 * 1024 && pl.lds_bytes > granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pl.lds_bytes));
+        if (e != hipSuccess) return hip_failed(e);
+        granted = pl.lds_bytes;
     }
-#undef DAB_GO
+    hipLaunchKernelGGL((binconv_mfma_kernel<WAVES, MODE>), dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4,
+                       e4, alpha, beta, Y, dbg_s1, ws_s1, sa);
+    return launch_status();
 }
 
-static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t* E, const uint32_t* ecnt,
-                       const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes,
-                       hipStream_t st) {
-    ConvPlan pl;
-    if (int rc = plan_conv(d, &pl)) return rc;
-    int32_t* ws_s1 = nullptr;
-    int32_t* ws_sA = nullptr;
-    int mode = dbg_s1 ? kModeYDebug : kModeY;
-    if (pl.g.ksplit > 1) {
-        if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 16)) return DAB_ERR_WORKSPACE;
-        ws_s1 = static_cast<int32_t*>(ws);
-        ws_sA = ws_s1 + static_cast<size_t>(pl.g.ksplit) * pl.g.M * d.F;
-        mode = kModeSplit;
-    }
-    const int key = pl.PX * 100 + pl.NT;
-    switch (key) {
-        case 416: launch_tile<4, 16>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-        case 216: launch_tile<2, 16>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-        case 116: launch_tile<1, 16>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-#ifdef DAB_TUNING
-        case 232: launch_tile<2, 32>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-        case 164: launch_tile<1, 64>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-        case 432: launch_tile<4, 32>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-        case 816: launch_tile<8, 16>(pl, mode, st, A, E, ecnt, alpha, beta, Y, dbg_s1, ws_s1, ws_sA); break;
-#endif
-        default: return DAB_ERR_UNSUPPORTED;
-    }
+static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t* E, const float* alpha,
+                       const float* beta, float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, hipStream_t st) {
+    MfmaPlan pl;
+    if (int rc = plan_binconv(d, &pl)) return rc;
+    if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
+    char* a4 = static_cast<char*>(ws);
+    uint4* e4 = reinterpret_cast<uint4*>(a4 + pl.a4_bytes);
+    float* sa = reinterpret_cast<float*>(a4 + pl.a4_bytes + pl.e4_bytes);
+    float* s1 = reinterpret_cast<float*>(a4 + pl.a4_bytes + pl.e4_bytes + pl.sa_bytes);
+    const MfmaGeom& g = pl.g;
+
+    hipLaunchKernelGGL(binconv_prepare_kernel, dim3(g.blk_act + g.blk_wgt), dim3(256), 0, st, g, A, E,
+                       reinterpret_cast<uint4*>(a4), e4);
     if (int rc = launch_status()) return rc;
-    if (mode == kModeSplit) {
-        const size_t total = static_cast<size_t>(pl.g.M) * d.F;
-        hipLaunchKernelGGL(binconv_finish_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
-                           ws_s1, ws_sA, alpha, beta, Y, dbg_s1, pl.g.M, d.F, pl.g.ksplit);
+
+    if (pl.split) {
+        if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1)) return rc;
+        const size_t total = static_cast<size_t>(g.M) * d.F;
+        hipLaunchKernelGGL(binconv_finish_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, s1,
+                           sa, alpha, beta, Y, dbg_s1, g.M, d.F, g.ksplit);
         return launch_status();
     }
-    return DAB_OK;
+    if (pl.waves == 8)
+        return dbg_s1 ? launch_main<8, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1)
+                      : launch_main<8, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1);
+    return dbg_s1 ? launch_main<4, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1)
+                  : launch_main<4, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1);
 }
 
-static int check_common(const void* A, const void* E, const void* cnt, const void* alpha, const void* beta,
-                        const void* Y, const void* dbg) {
-    if (!A || !E || !cnt || !alpha || !beta || !Y) return DAB_ERR_NULL;
-    if (misaligned(A, 16) || misaligned(E, 64) || misaligned(Y, 16) || misaligned(cnt, 4) ||
-        misaligned(alpha, 4) || misaligned(beta, 4) || (dbg && misaligned(dbg, 16)))
+static int check_common(const void* A, const void* E, const void* alpha, const void* beta, const void* Y,
+                        const void* dbg) {
+    if (!A || !E || !alpha || !beta || !Y) return DAB_ERR_NULL;
+    if (misaligned(A, 16) || misaligned(E, 64) || misaligned(Y, 16) || misaligned(alpha, 4) ||
+        misaligned(beta, 4) || (dbg && misaligned(dbg, 16)))
         return DAB_ERR_ALIGN;
     return DAB_OK;
 }
@@ -501,15 +512,9 @@ static int check_desc(const dab_conv_desc* d) {
 
 extern "C" {
 
-#ifdef DAB_TUNING
-void dab_tuning_force(int px, int nt, int nw, int ks) {
-    dab::g_force[0] = px; dab::g_force[1] = nt; dab::g_force[2] = nw; dab::g_force[3] = ks;
-}
-#endif
-
 size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d) {
-    dab::ConvPlan pl;
-    if (!d || dab::check_desc(d) != DAB_OK || dab::plan_conv(*d, &pl) != DAB_OK) return 0;
+    dab::MfmaPlan pl;
+    if (!d || dab::check_desc(d) != DAB_OK || dab::plan_binconv(*d, &pl) != DAB_OK) return 0;
     return pl.ws_bytes;
 }
 
@@ -520,24 +525,23 @@ size_t dab_binfc_workspace_bytes(int32_t B, int32_t Kin, int32_t F) {
 }
 
 int dab_binconv2d(const dab_conv_desc* d, const uint32_t* A_packed, const uint32_t* E_packed,
-                  const uint32_t* ecnt, const float* alpha, const float* beta, float* Y, int32_t* dbg_s1,
+                  const float* alpha, const float* beta, float* Y, int32_t* dbg_s1,
                   void* ws, size_t ws_bytes, void* stream) {
     if (!d) return DAB_ERR_NULL;
-    if (int rc = dab::check_common(A_packed, E_packed, ecnt, alpha, beta, Y, dbg_s1)) return rc;
+    if (int rc = dab::check_common(A_packed, E_packed, alpha, beta, Y, dbg_s1)) return rc;
     if (int rc = dab::check_desc(d)) return rc;
-    return dab::run_binconv(*d, A_packed, E_packed, ecnt, alpha, beta, Y, dbg_s1, ws, ws_bytes,
+    return dab::run_binconv(*d, A_packed, E_packed, alpha, beta, Y, dbg_s1, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
 }
 
 int dab_binfc(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const uint32_t* E_packed,
-              const int32_t* K, const float* alpha, const float* beta, float* Y, int32_t* dbg_s1,
+              const float* alpha, const float* beta, float* Y, int32_t* dbg_s1,
               void* ws, size_t ws_bytes, void* stream) {
-    if (int rc = dab::check_common(A_packed, E_packed, K, alpha, beta, Y, dbg_s1)) return rc;
+    if (int rc = dab::check_common(A_packed, E_packed, alpha, beta, Y, dbg_s1)) return rc;
     if (B < 1 || Kin < 2 || F < 1) return DAB_ERR_SHAPE;
     const dab_conv_desc d{B, Kin, 1, 1, F, 1, 1, 0, 0, 1, 1};
-    // with a single tap the per-tap count of a filter is its K
-    return dab::run_binconv(d, A_packed, E_packed, reinterpret_cast<const uint32_t*>(K), alpha, beta, Y, dbg_s1,
-                            ws, ws_bytes, static_cast<hipStream_t>(stream));
+    return dab::run_binconv(d, A_packed, E_packed, alpha, beta, Y, dbg_s1, ws, ws_bytes,
+                            static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

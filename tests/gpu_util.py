@@ -100,10 +100,10 @@ def gpu_layer(L, x_nchw, W, tau=None, layout="nhwc", want_s1=True):
         A = dab.dab_pack_activations(to_gpu(x_nchw), dab.DAB_LAYOUT_NCHW, tau_t)
     B = x_nchw.shape[0]
     if L.is_fc:
-        res = dab.dab_binfc(A.reshape(B, -1), E, est["K"], est["alpha"], est["beta"], L.C, want_s1=want_s1)
+        res = dab.dab_binfc(A.reshape(B, -1), E, est["alpha"], est["beta"], L.C, want_s1=want_s1)
     else:
         d = dab.dab_conv_desc(B, L.C, L.H, L.W, L.F, L.kh, L.kw, L.pad, L.pad, L.stride, L.stride)
-        res = dab.dab_binconv2d(d, A, E, ecnt, est["alpha"], est["beta"], want_s1=want_s1)
+        res = dab.dab_binconv2d(d, A, E, est["alpha"], est["beta"], want_s1=want_s1)
     torch.cuda.synchronize()
     Y, s1 = res if want_s1 else (res, None)
     return dict(est=est_np, E=u32(E), ecnt=u32(ecnt), A=u32(A), Y=Y.cpu().numpy(),
