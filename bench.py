@@ -9,8 +9,8 @@ packing, activation bit packing and the binary convolution / fully-connected pro
 fp32 inputs of all layers and the fp32 weights are resident in HBM before the timed region.
 
 Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
-kernel (binary convolution, VALU-bound) from HIP-event timings taken inside the timed
-region, and the CPU oracle timed on a small slice of the same workload.
+kernel (the binary product on the matrix cores) from HIP-event timings taken inside the
+timed region, and the CPU oracle timed on a slice of the same workload.
 """
 from __future__ import annotations
 
@@ -25,11 +25,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 64 VALU lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s.  One AND + one BCNT
-# serve 32 binary multiply-accumulates of one lane, so the instruction-set floor is
-# MACs / 16 lane-ops and the matching peak is 629 T binary MAC/s.
-VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9
-OPS_PER_MAC = 2.0 / 32.0
+# Rooflines of the binary product on MI355X.
+#   MFMA, fp4 operands (the kernel that ships): published dense peak 10.1 PFLOP/s = 5.05e15 MAC/s.
+#   Vector ALU popcount form, for comparison: 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s and
+#   one AND + one BCNT per 32 binary MACs of a lane, i.e. at most 6.29e14 binary MAC/s.
+#   HBM: 8 TB/s; a layer writes 4 bytes per output and reads its packed/expanded operands.
+MFMA_FP4_FLOPS = 10.1e15
+VALU_PAIR_MACS = 256 * 64 * 2.4e9 * 16
+HBM_BYTES_PER_S = 8.0e12
 
 
 def parse():
@@ -39,6 +42,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
     ap.add_argument("--cpu-batch", type=int, default=128, help="images of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
+                         "HBM byte counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -156,6 +162,12 @@ def main():
 
     states = build_states(args.batch, dab, torch, wl)
     total_macs = sum(s.macs for s in states)
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     for _ in range(args.warmup):
         for s in states:
@@ -177,24 +189,33 @@ def main():
     # binary-product kernel: per-layer and aggregate, from the events recorded in the timed region
     per_layer = {}
     conv_ms = 0.0
+    out_bytes = 0
     for i, s in enumerate(states):
         ms = sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
         conv_ms += ms
+        out_bytes += s.Y.numel() * 4
         per_layer[s.L.name] = {"ms": round(ms, 4), "gmacs": round(s.macs / 1e9, 3),
-                               "frac_of_valu_peak": round(s.macs * OPS_PER_MAC / (ms * 1e-3) / VALU_LANE_OPS_PER_S, 4)}
-    achieved = total_macs * OPS_PER_MAC / (conv_ms * 1e-3) / 1e12
-    peak = VALU_LANE_OPS_PER_S / 1e12
-    roofline = {"bound": "alu", "kernel": "binconv_kernel (all six launches of a step)",
-                "achieved": round(achieved, 3), "peak": round(peak, 3), "unit": "TOP/s (32-bit VALU lane-ops: AND + BCNT per 32 MACs)",
-                "frac": round(achieved / peak, 4), "frac_of_bcnt_only_peak": round(achieved / peak / 2, 4),
-                "kernel_ms_per_step": round(conv_ms, 4), "traffic": None, "per_layer": per_layer}
+                               "tflops": round(2 * s.macs / (ms * 1e-3) / 1e12, 1),
+                               "frac_of_mfma_fp4_peak": round(2 * s.macs / (ms * 1e-3) / MFMA_FP4_FLOPS, 4),
+                               "output_gb_per_s": round(s.Y.numel() * 4 / (ms * 1e-3) / 1e9, 1)}
+    achieved = 2 * total_macs / (conv_ms * 1e-3) / 1e12
+    peak = MFMA_FP4_FLOPS / 1e12
+    roofline = {"bound": "mfma", "kernel": "binconv (prepare + binconv_mfma_kernel [+ finish]) of all six layers of a step",
+                "achieved": round(achieved, 1), "peak": round(peak, 1), "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": None,
+                "kernel_ms_per_step": round(conv_ms, 4),
+                "binary_macs_per_s": total_macs / (conv_ms * 1e-3),
+                "vs_valu_popcount_peak": round(total_macs / (conv_ms * 1e-3) / VALU_PAIR_MACS, 3),
+                "output_bytes_per_step": out_bytes,
+                "output_frac_of_hbm_peak": round(out_bytes / (conv_ms * 1e-3) / HBM_BYTES_PER_S, 4),
+                "per_layer": per_layer}
 
     cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
     line = {
         "metric": "effective binary MACs/s on Sketch-A-Net binarized layers",
         "value": value, "unit": "binary MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 popcount / int32 accumulate, fp32 epilogue, fp64 estimation", "data": "synthetic",
+        "dtype": "fp4 (e2m1) operands expanded from 1-bit, fp32 MFMA accumulate (exact integers), fp32 epilogue, fp64 estimation", "data": "synthetic",
         "config": {"workload": "config 3: Sketch-A-Net binarized trunk (conv2-conv6, fc7), batch %d, "
                                "estimate + pack weights + pack activations + binary product per layer" % args.batch,
                    "batch": args.batch, "binary_macs_per_step": total_macs},
