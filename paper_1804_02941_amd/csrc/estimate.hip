@@ -7,14 +7,17 @@
 // Section 4.3.1 handles all filters of a layer together; here a filter is a segment and
 // one workgroup owns one segment, so the sorted row, P and D never leave the chip:
 //
-//   1. load the row, map fp32 -> order-preserving uint32 keys (-0.0 folded onto +0.0);
-//   2. least-significant-digit radix sort in LDS, 4 passes of 8 bits, ping-pong buffers.
-//      Each wavefront owns a contiguous stretch of positions and ranks 64 keys at a time:
-//      eight ballots find the lanes holding the same digit, the popcount below the lane
-//      is the key's rank among them, per-wavefront digit counters in LDS carry the rank
-//      across batches, and one scan over (digit, wavefront) turns counters into offsets;
-//   3. fp64 prefix sums (serial per thread, scanned across threads), D_i in fp64, and a
-//      workgroup arg-max that prefers the larger i on equal D;
+//   1. load the row, map fp32 -> order-preserving uint32 keys (-0.0 folded onto +0.0), pad
+//      to THREADS * ITEMS keys with 0xFFFFFFFF (above every finite key);
+//   2. least-significant-digit radix sort in LDS, 8 passes of 4 bits.  A thread owns ITEMS
+//      consecutive keys and holds them in registers for the whole pass; its sixteen digit
+//      counters (each at most ITEMS <= 15) live in one 64-bit register, 4 bits apiece, so
+//      counting costs no memory traffic.  The counters go to LDS packed two to a word
+//      (digit d and d + 8), one scan over the words in (digit, thread) order turns them
+//      into stable offsets, and the keys are scattered back into the same buffer;
+//   3. fp64 prefix sums (serial per thread, scanned across threads) and the arg-max of D_i,
+//      compared as fractions (numerators cross-multiplied) so that no division is needed
+//      per element; ties prefer the larger i;
 //   4. the split descriptor: the value at the split and, among equal values, the original
 //      index up to which they belong to the lower group (recovered from the unsorted row,
 //      so the sort itself carries no indices).
@@ -40,28 +43,29 @@ __device__ __forceinline__ T wave_inclusive_scan(T v, int lane) {
     return v;
 }
 
+// Candidate split: D = num / den with den > 0; P is the prefix sum at the split.
 struct Best {
-    double D, P;
+    double num, den, P;
     int i;
 };
-__device__ __forceinline__ bool better(double D, int i, double D0, int i0) {
-    return D > D0 || (D == D0 && i > i0);
+__device__ __forceinline__ bool better(const Best& a, const Best& b) {   // a beats b
+    const double l = a.num * b.den, r = b.num * a.den;
+    return l > r || (l == r && a.i > b.i);
 }
 
-// THREADS = workgroup size, MAXB = most 64-key batches one wavefront ranks per pass.
-template <int THREADS, int MAXB>
+template <int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restrict__ Wt, int n,
                                                            float* __restrict__ alpha, float* __restrict__ beta,
                                                            int32_t* __restrict__ Kout, float* __restrict__ thr_val,
                                                            int32_t* __restrict__ thr_idx,
                                                            uint8_t* __restrict__ alpha_is_upper) {
+    static_assert(ITEMS >= 1 && ITEMS <= 15, "a digit counter has 4 bits");
     constexpr int NW = THREADS / 64;
-    extern __shared__ __align__(16) uint32_t smem[];
-    uint32_t* bufA = smem;                  // [n]
-    uint32_t* bufB = smem + n;              // [n]
-    uint32_t* hist = smem + 2 * n;          // [NW][256]
+    constexpr int N = THREADS * ITEMS;
+    __shared__ uint32_t keys[N];
+    __shared__ __align__(16) uint32_t counters[8 * THREADS];   // word w*THREADS + t: digits w (low half), w + 8 (high half)
+    __shared__ uint32_t wave_tot[NW];
     __shared__ double wave_sum[NW];
-    __shared__ uint32_t wave_cnt[NW];
     __shared__ Best wave_best[NW];
     __shared__ double total_s;
     __shared__ int r_s;
@@ -70,82 +74,72 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* row = Wt + static_cast<size_t>(blockIdx.x) * n;
 
-    for (int i = tid; i < n; i += THREADS) bufA[i] = float_to_key(row[i]);
+    for (int i = tid; i < N; i += THREADS) keys[i] = i < n ? float_to_key(row[i]) : 0xFFFFFFFFu;
+    __syncthreads();
 
-    // ---- radix sort, stable per pass
-    const int seg = 64 * ((((n + NW - 1) / NW) + 63) / 64);   // positions per wavefront
-    const int seg_lo = wave * seg;
-    const int nb = min(MAXB, max(0, (min(n, seg_lo + seg) - seg_lo + 63) / 64));
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    uint32_t* src = bufA;
-    uint32_t* dst = bufB;
-    for (int shift = 0; shift < 32; shift += 8) {
-        for (int i = tid; i < NW * 256; i += THREADS) hist[i] = 0u;
-        __syncthreads();
-        uint32_t lrank[MAXB];
+    // ---- radix sort
+    for (int shift = 0; shift < 32; shift += 4) {
+        uint32_t k[ITEMS];
 #pragma unroll
-        for (int bi = 0; bi < MAXB; ++bi) {
-            lrank[bi] = 0;
-            if (bi < nb) {
-                const int pos = seg_lo + bi * 64 + lane;
-                const bool valid = pos < n;
-                const uint32_t d = valid ? (src[pos] >> shift) & 255u : 0u;
-                unsigned long long peers = __ballot(valid);
+        for (int j = 0; j < ITEMS; ++j) k[j] = keys[tid * ITEMS + j];
+        // digit counters of this thread and, per key, how many earlier keys of the thread share its digit
+        unsigned long long cnt = 0, pfx = 0;
 #pragma unroll
-                for (int bit = 0; bit < 8; ++bit) {
-                    const bool one = (d >> bit) & 1u;
-                    const unsigned long long m = __ballot(valid && one);
-                    peers &= one ? m : ~m;
-                }
-                if (valid) {
-                    const uint32_t below = __popcll(peers & lt_mask);
-                    const uint32_t prev = hist[wave * 256 + d];
-                    lrank[bi] = prev + below;
-                    if (below == 0) hist[wave * 256 + d] = prev + __popcll(peers);
-                }
-            }
+        for (int j = 0; j < ITEMS; ++j) {
+            const int sh = ((k[j] >> shift) & 15u) * 4;
+            pfx |= ((cnt >> sh) & 15ull) << (4 * j);
+            cnt += 1ull << sh;
         }
+#pragma unroll
+        for (int w = 0; w < 8; ++w)
+            counters[w * THREADS + tid] = static_cast<uint32_t>((cnt >> (4 * w)) & 15ull) |
+                                          (static_cast<uint32_t>((cnt >> (4 * w + 32)) & 15ull) << 16);
         __syncthreads();
-        // exclusive scan of the counters in (digit, wavefront) order
+        // exclusive scan over the words in linear order (both halves at once: totals stay below 2^16)
+        uint32_t c[8];
         {
-            uint32_t tot = 0;
-            if (tid < 256)
-                for (int w = 0; w < NW; ++w) tot += hist[w * 256 + tid];
-            uint32_t inc = wave_inclusive_scan(tot, lane);
-            if (lane == 63) wave_cnt[wave] = inc;
-            __syncthreads();
-            uint32_t base = inc - tot;
-            for (int w = 0; w < wave; ++w) base += wave_cnt[w];
-            if (tid < 256) {
-                for (int w = 0; w < NW; ++w) {
-                    const uint32_t c = hist[w * 256 + tid];
-                    hist[w * 256 + tid] = base;
-                    base += c;
-                }
-            }
+            const uint4 lo = *reinterpret_cast<const uint4*>(&counters[tid * 8]);
+            const uint4 hi = *reinterpret_cast<const uint4*>(&counters[tid * 8 + 4]);
+            c[0] = lo.x; c[1] = lo.y; c[2] = lo.z; c[3] = lo.w; c[4] = hi.x; c[5] = hi.y; c[6] = hi.z; c[7] = hi.w;
         }
-        __syncthreads();
+        uint32_t run = 0;
 #pragma unroll
-        for (int bi = 0; bi < MAXB; ++bi) {
-            if (bi < nb) {
-                const int pos = seg_lo + bi * 64 + lane;
-                if (pos < n) {
-                    const uint32_t key = src[pos];
-                    dst[hist[wave * 256 + ((key >> shift) & 255u)] + lrank[bi]] = key;
-                }
-            }
+        for (int w = 0; w < 8; ++w) { const uint32_t t = c[w]; c[w] = run; run += t; }
+        const uint32_t inc = wave_inclusive_scan(run, lane);
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        uint32_t base = inc - run, all = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const uint32_t t = wave_tot[w];
+            if (w < wave) base += t;
+            all += t;
+        }
+        *reinterpret_cast<uint4*>(&counters[tid * 8]) = make_uint4(c[0] + base, c[1] + base, c[2] + base, c[3] + base);
+        *reinterpret_cast<uint4*>(&counters[tid * 8 + 4]) = make_uint4(c[4] + base, c[5] + base, c[6] + base, c[7] + base);
+        __syncthreads();
+        const uint32_t low_total = all & 0xFFFFu;                  // keys with digits 0..7 precede digits 8..15
+        // every thread holds its keys in registers, so the buffer can be overwritten in place
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const uint32_t d = (k[j] >> shift) & 15u;
+            const uint32_t word = counters[(d & 7u) * THREADS + tid];
+            const uint32_t off = d < 8u ? (word & 0xFFFFu) : (word >> 16) + low_total;
+            keys[off + static_cast<uint32_t>((pfx >> (4 * j)) & 15ull)] = k[j];
         }
         __syncthreads();
-        uint32_t* t = src; src = dst; dst = t;
     }
-    // four passes: the sorted keys are back in bufA (= src)
 
-    // ---- prefix sums in fp64: thread t owns sorted positions [t*per, t*per + per)
-    const int per = (n + THREADS - 1) / THREADS;
-    const int lo = min(n, tid * per), hi = min(n, lo + per);
+    // ---- prefix sums in fp64: thread t owns sorted positions [t*ITEMS, t*ITEMS + ITEMS), clipped to n
+    const int lo = min(n, tid * ITEMS), hi = min(n, lo + ITEMS);
+    double x[ITEMS];
     double local = 0.0;
-    for (int i = lo; i < hi; ++i) local += static_cast<double>(key_to_float(src[i]));
-    double inc = wave_inclusive_scan(local, lane);
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        x[j] = lo + j < hi ? static_cast<double>(key_to_float(keys[lo + j])) : 0.0;
+        local += x[j];
+    }
+    const double inc = wave_inclusive_scan(local, lane);
     if (lane == 63) wave_sum[wave] = inc;
     __syncthreads();
     double base = inc - local;
@@ -155,22 +149,24 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     const double T = total_s;
 
     // ---- D_i over this thread's positions; split i = position + 1, i in 1 .. n-1
-    Best best{-1.0, 0.0, 0};
+    Best best{-1.0, 1.0, 0.0, 0};
     double P = base;
-    for (int p = lo; p < hi; ++p) {
-        P += static_cast<double>(key_to_float(src[p]));
-        const int i = p + 1;
-        if (i < n) {
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        P += x[j];
+        const int i = lo + j + 1;
+        if (lo + j < hi && i < n) {
             const double rest = T - P;
-            const double D = P * P / static_cast<double>(i) + rest * rest / static_cast<double>(n - i);
-            if (better(D, i, best.D, best.i)) best = Best{D, P, i};
+            const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
+            const Best cand{P * P * fr + rest * rest * fi, fi * fr, P, i};
+            if (better(cand, best)) best = cand;
         }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
-        const double oD = __shfl_xor(best.D, d, 64), oP = __shfl_xor(best.P, d, 64);
-        const int oi = __shfl_xor(best.i, d, 64);
-        if (better(oD, oi, best.D, best.i)) best = Best{oD, oP, oi};
+        const Best o{__shfl_xor(best.num, d, 64), __shfl_xor(best.den, d, 64), __shfl_xor(best.P, d, 64),
+                     __shfl_xor(best.i, d, 64)};
+        if (better(o, best)) best = o;
     }
     if (lane == 0) wave_best[wave] = best;
     __syncthreads();
@@ -178,7 +174,7 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     if (tid == 0) {
         Best b = wave_best[0];
         for (int w = 1; w < NW; ++w)
-            if (better(wave_best[w].D, wave_best[w].i, b.D, b.i)) b = wave_best[w];
+            if (better(wave_best[w], b)) b = wave_best[w];
         const int is = b.i;
         const double mu_lower = b.P / static_cast<double>(is);
         const double mu_upper = (T - b.P) / static_cast<double>(n - is);
@@ -189,11 +185,11 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
         Kout[f] = upper ? n - is : is;
         alpha_is_upper[f] = upper ? 1 : 0;
         // value at the split and how many of its duplicates fall in the lower group
-        const uint32_t tk = src[is - 1];
+        const uint32_t tk = keys[is - 1];
         int a = 0, c = is - 1;                      // first position holding tk (lower bound)
         while (a < c) {
             const int mid = (a + c) >> 1;
-            if (src[mid] < tk) a = mid + 1; else c = mid;
+            if (keys[mid] < tk) a = mid + 1; else c = mid;
         }
         thr_s = key_to_float(tk);
         thr_val[f] = thr_s;
@@ -203,18 +199,18 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
 
     // ---- original index of the r-th copy (in index order) of the split value
     const float tv = thr_s;
-    const int r = r_s;
+    const uint32_t r = static_cast<uint32_t>(r_s);
     uint32_t cnt = 0;
     for (int i = lo; i < hi; ++i) cnt += (row[i] == tv) ? 1u : 0u;
-    uint32_t cinc = wave_inclusive_scan(cnt, lane);
-    if (lane == 63) wave_cnt[wave] = cinc;
+    const uint32_t cinc = wave_inclusive_scan(cnt, lane);
+    if (lane == 63) wave_tot[wave] = cinc;
     __syncthreads();
     uint32_t cbase = cinc - cnt;
-    for (int w = 0; w < wave; ++w) cbase += wave_cnt[w];
-    if (cnt > 0 && static_cast<uint32_t>(r) > cbase && static_cast<uint32_t>(r) <= cbase + cnt) {
+    for (int w = 0; w < wave; ++w) cbase += wave_tot[w];
+    if (cnt > 0 && r > cbase && r <= cbase + cnt) {
         uint32_t seen = cbase;
         for (int i = lo; i < hi; ++i) {
-            if (row[i] == tv && ++seen == static_cast<uint32_t>(r)) {
+            if (row[i] == tv && ++seen == r) {
                 thr_idx[blockIdx.x] = i;
                 break;
             }
@@ -222,27 +218,12 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     }
 }
 
-struct EstimateConfig {
-    int threads, maxb, max_n;
-};
-constexpr EstimateConfig kEstimateConfigs[] = {
-    {256, 4, 4 * 64 * 4}, {256, 12, 4 * 64 * 12}, {1024, 5, 16 * 64 * 5}, {1024, 13, 16 * 64 * 13}};
-constexpr int kEstimateMaxN = 16 * 64 * 13;
+constexpr int kEstimateMaxN = 1024 * 13;
 
-template <int THREADS, int MAXB>
+template <int THREADS, int ITEMS>
 static int launch_estimate(const float* W, int F, int n, float* alpha, float* beta, int32_t* K, float* thr_val,
                            int32_t* thr_idx, uint8_t* aiu, hipStream_t st) {
-    const size_t lds = (2 * static_cast<size_t>(n) + (THREADS / 64) * 256) * sizeof(uint32_t);
-    if (lds > 48 * 1024) {
-        static thread_local size_t granted = 0;
-        if (lds > granted) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&estimate_kernel<THREADS, MAXB>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-            if (e != hipSuccess) return hip_failed(e);
-            granted = lds;
-        }
-    }
-    hipLaunchKernelGGL((estimate_kernel<THREADS, MAXB>), dim3(F), dim3(THREADS), lds, st, W, n, alpha, beta, K,
+    hipLaunchKernelGGL((estimate_kernel<THREADS, ITEMS>), dim3(F), dim3(THREADS), 0, st, W, n, alpha, beta, K,
                        thr_val, thr_idx, aiu);
     return launch_status();
 }
@@ -266,10 +247,23 @@ int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n, float* alpha, 
         return DAB_ERR_ALIGN;
     if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (n <= kEstimateConfigs[0].max_n) return launch_estimate<256, 4>(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, st);
-    if (n <= kEstimateConfigs[1].max_n) return launch_estimate<256, 12>(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, st);
-    if (n <= kEstimateConfigs[2].max_n) return launch_estimate<1024, 5>(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, st);
-    return launch_estimate<1024, 13>(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, st);
+#define DAB_EST(T, I) return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, st)
+    // smallest padded size that holds the row; odd item counts keep the per-thread key runs off
+    // each other's LDS banks
+    if (n <= 64 * 3) DAB_EST(64, 3);
+    if (n <= 256 * 3) DAB_EST(256, 3);
+    if (n <= 256 * 5) DAB_EST(256, 5);
+    if (n <= 256 * 7) DAB_EST(256, 7);
+    if (n <= 256 * 9) DAB_EST(256, 9);
+    if (n <= 256 * 11) DAB_EST(256, 11);
+    if (n <= 512 * 7) DAB_EST(512, 7);
+    if (n <= 512 * 9) DAB_EST(512, 9);
+    if (n <= 512 * 11) DAB_EST(512, 11);
+    if (n <= 1024 * 7) DAB_EST(1024, 7);
+    if (n <= 1024 * 9) DAB_EST(1024, 9);
+    if (n <= 1024 * 11) DAB_EST(1024, 11);
+    DAB_EST(1024, 13);
+#undef DAB_EST
 }
 
 }  // extern "C"
