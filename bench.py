@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
     ap.add_argument("--cpu-batch", type=int, default=128, help="images of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--side-streams", type=int, default=3,
+                    help="HIP streams for the weight side (estimation + weight packing) of the layers; 0 = one stream")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time eager launches instead of one captured HIP graph per step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
                          "HBM byte counters of a rocprofv3 --pmc run)")
@@ -54,36 +58,116 @@ class LayerState:
     def __init__(self, L, W, X, tau, dab, torch):
         self.L, self.W, self.X, self.tau = L, W, X, tau
         B = X.shape[0]
+        dev = X.device
         self.B = B
         self.W2 = W.reshape(L.F, -1)
         if L.is_fc:
             self.desc = None
-            self.Y = torch.empty((B, L.F), dtype=torch.float32, device=X.device)
-            self.A = torch.empty((B, 1, 1, dab.words_per_pixel(L.C)), dtype=torch.int32, device=X.device)
+            self.Y = torch.empty((B, L.F), dtype=torch.float32, device=dev)
+            self.A = torch.empty((B, 1, 1, dab.words_per_pixel(L.C)), dtype=torch.int32, device=dev)
         else:
             self.desc = dab.dab_conv_desc(B, L.C, L.H, L.W, L.F, L.kh, L.kw, L.pad, L.pad, L.stride, L.stride)
-            self.Y = torch.empty((B, L.Ho, L.Wo, L.F), dtype=torch.float32, device=X.device)
-            self.A = torch.empty((B, L.H, L.W, dab.words_per_pixel(L.C)), dtype=torch.int32, device=X.device)
+            self.Y = torch.empty((B, L.Ho, L.Wo, L.F), dtype=torch.float32, device=dev)
+            self.A = torch.empty((B, L.H, L.W, dab.words_per_pixel(L.C)), dtype=torch.int32, device=dev)
         self.macs = L.macs(B)
         nbytes = (dab.lib().dab_binfc_workspace_bytes(B, L.C, L.F) if L.is_fc
                   else dab.lib().dab_binconv2d_workspace_bytes(ctypes.byref(self.desc)))
-        self.ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=X.device)
+        self.ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=dev)
+        self.est = dab.estimate_outputs(L.F, dev)
+        self.EW = dab.pack_weights_outputs(L.F, W.shape[1], W.shape[2], W.shape[3], dev)
+        self.est_ws = torch.empty(max(dab.lib().dab_estimate_workspace_bytes(L.F, self.W2.shape[1]), 1),
+                                  dtype=torch.uint8, device=dev)
+
+
+def weight_side(s, dab):
+    """alpha/beta estimation and weight bit packing of one layer (independent of the activations)."""
+    est = dab.dab_estimate_alpha_beta(s.W2, out=s.est, ws=s.est_ws)
+    dab.dab_pack_weights(s.W, est["thr_val"], est["thr_idx"], est["alpha_is_upper"], out=s.EW)
+
+
+def activation_side(s, dab):
+    dab.dab_pack_activations(s.X, dab.DAB_LAYOUT_NHWC, s.tau, out=s.A)
+
+
+def product(s, dab):
+    if s.desc is None:
+        dab.dab_binfc(s.A.view(s.B, -1), s.EW[0], s.est["alpha"], s.est["beta"], s.L.C, out=s.Y, ws=s.ws)
+    else:
+        dab.dab_binconv2d(s.desc, s.A, s.EW[0], s.est["alpha"], s.est["beta"], out=s.Y, ws=s.ws)
 
 
 def run_layer(s, dab, events=None):
     """estimate -> pack weights -> pack activations -> binary product, all on the current stream."""
-    est = dab.dab_estimate_alpha_beta(s.W2)
-    E, ecnt = dab.dab_pack_weights(s.W, est["thr_val"], est["thr_idx"], est["alpha_is_upper"])
-    dab.dab_pack_activations(s.X, dab.DAB_LAYOUT_NHWC, s.tau, out=s.A)
+    weight_side(s, dab)
+    activation_side(s, dab)
     if events is not None:
         events[0].record()
-    if s.desc is None:
-        dab.dab_binfc(s.A.view(s.B, -1), E, est["alpha"], est["beta"], s.L.C, out=s.Y, ws=s.ws)
-    else:
-        dab.dab_binconv2d(s.desc, s.A, E, est["alpha"], est["beta"], out=s.Y, ws=s.ws)
+    product(s, dab)
     if events is not None:
         events[1].record()
     return s.Y
+
+
+class Schedule:
+    """One step of all layers over HIP streams of equal (default) priority.
+
+    The weight side of a layer (estimation, weight packing) depends on no activation, so the
+    weight sides of all layers run first, spread over side streams (they are latency-bound
+    one-workgroup-per-filter kernels that share the chip well), while the current stream packs
+    the first layer's activations.  The current stream then waits for all of them and runs,
+    layer by layer, activation packing and the binary product with the chip to itself.  A step
+    forks from and joins back into the current stream, so steps never overlap, and the whole
+    step can be captured into one HIP graph.
+    """
+
+    def __init__(self, states, n_side, torch):
+        self.torch = torch
+        self.states = states
+        self.side = [torch.cuda.Stream() for _ in range(n_side)]
+        # longest-processing-time assignment by sort work F * n; layer order kept inside a stream
+        load = [0.0] * max(n_side, 1)
+        self.assign = [[] for _ in range(max(n_side, 1))]
+        for i in sorted(range(len(states)), key=lambda i: -states[i].W2.numel()):
+            q = min(range(len(load)), key=lambda q: load[q])
+            load[q] += states[i].W2.numel()
+            self.assign[q].append(i)
+        for a in self.assign:
+            a.sort()
+        self.fork = torch.cuda.Event()
+        self.ready = [torch.cuda.Event() for _ in self.side]
+
+    def step(self, dab, events=None):
+        torch, states = self.torch, self.states
+        if not self.side:
+            for i, s in enumerate(states):
+                run_layer(s, dab, None if events is None else events[i])
+            return
+        main = torch.cuda.current_stream()
+        self.fork.record(main)
+        for q, idxs, done in zip(self.side, self.assign, self.ready):
+            q.wait_event(self.fork)
+            with torch.cuda.stream(q):
+                for i in idxs:
+                    weight_side(states[i], dab)
+            done.record(q)
+        for i, s in enumerate(states):
+            activation_side(s, dab)
+            if i == 0:
+                for done in self.ready:
+                    main.wait_event(done)
+            if events is not None:
+                events[i][0].record()
+            product(s, dab)
+            if events is not None:
+                events[i][1].record()
+
+    def capture(self, dab):
+        """The step as one HIP graph (kernel launches and stream dependencies only)."""
+        torch = self.torch
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            self.step(dab)
+        return graph
 
 
 def build_states(batch, dab, torch, wl):
@@ -169,24 +253,48 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    sched = Schedule(states, args.side_streams, torch)
     for _ in range(args.warmup):
-        for s in states:
-            run_layer(s, dab)
+        sched.step(dab)
     torch.cuda.synchronize()
 
+    # Kernel timing pass: every layer launched eagerly on one stream with a HIP event pair around its
+    # binary product (events cannot be recorded inside a captured graph on this platform, and with
+    # several streams the eager launches are host-bound, which would put launch gaps between the
+    # product's kernels).  In the schedule the products have the chip to themselves, as they do here.
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in states]
           for _ in range(args.steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
     for k in range(args.steps):
         for s, e in zip(states, ev[k]):
             run_layer(s, dab, e)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+
+    # The schedule launched eagerly (host-bound with side streams; reported for comparison)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        sched.step(dab)
+    t_enqueued = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    dt_eager = time.perf_counter() - t0
+
+    # Timed region: exactly `steps` steps, each one launch of the captured HIP graph
+    if args.no_graph:
+        dt = dt_eager
+    else:
+        graph = sched.capture(dab)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
 
     ms_per_step = 1e3 * dt / args.steps
     value = total_macs * args.steps / dt
-    # binary-product kernel: per-layer and aggregate, from the events recorded in the timed region
+    # binary-product kernel: per-layer and aggregate, from the events of the kernel timing pass
     per_layer = {}
     conv_ms = 0.0
     out_bytes = 0
@@ -218,7 +326,11 @@ def main():
         "dtype": "fp4 (e2m1) operands expanded from 1-bit, fp32 MFMA accumulate (exact integers), fp32 epilogue, fp64 estimation", "data": "synthetic",
         "config": {"workload": "config 3: Sketch-A-Net binarized trunk (conv2-conv6, fc7), batch %d, "
                                "estimate + pack weights + pack activations + binary product per layer" % args.batch,
-                   "batch": args.batch, "binary_macs_per_step": total_macs},
+                   "batch": args.batch, "binary_macs_per_step": total_macs,
+                   "streams": 1 + args.side_streams,
+                   "launch": "eager" if args.no_graph else "one captured HIP graph per step",
+                   "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
+                   "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -107,17 +107,34 @@ def padded_filters(F):
     return 64 * ((F + 63) // 64)
 
 
-def dab_estimate_alpha_beta(W):
-    """W [F, n] fp32 -> dict(alpha, beta, K, thr_val, thr_idx, alpha_is_upper), each [F]."""
-    F, n = W.shape
-    dev = W.device
-    out = dict(
+def _workspace(nbytes, dev, ws):
+    """A caller-supplied workspace tensor if it is large enough, else a fresh one (None when none is needed)."""
+    if nbytes == 0:
+        return None
+    if ws is not None and ws.numel() * ws.element_size() >= nbytes:
+        return ws
+    return torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+
+def estimate_outputs(F, dev):
+    """Empty output tensors of dab_estimate_alpha_beta for F filters."""
+    return dict(
         alpha=torch.empty(F, dtype=torch.float32, device=dev), beta=torch.empty(F, dtype=torch.float32, device=dev),
         K=torch.empty(F, dtype=torch.int32, device=dev), thr_val=torch.empty(F, dtype=torch.float32, device=dev),
         thr_idx=torch.empty(F, dtype=torch.int32, device=dev),
         alpha_is_upper=torch.empty(F, dtype=torch.uint8, device=dev))
+
+
+def dab_estimate_alpha_beta(W, out=None, ws=None):
+    """W [F, n] fp32 -> dict(alpha, beta, K, thr_val, thr_idx, alpha_is_upper), each [F].
+
+    out: a dict from estimate_outputs() to write into instead of fresh tensors."""
+    F, n = W.shape
+    dev = W.device
+    if out is None:
+        out = estimate_outputs(F, dev)
     nbytes = lib().dab_estimate_workspace_bytes(F, n)
-    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=dev) if nbytes else None
+    ws = _workspace(nbytes, dev, ws)
     _check("dab_estimate_alpha_beta", lib().dab_estimate_alpha_beta(
         _ptr(W, torch.float32, "W"), F, n, out["alpha"].data_ptr(), out["beta"].data_ptr(), out["K"].data_ptr(),
         out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(), out["alpha_is_upper"].data_ptr(),
@@ -125,16 +142,23 @@ def dab_estimate_alpha_beta(W):
     return out
 
 
-def dab_pack_weights(W, thr_val, thr_idx, alpha_is_upper):
-    """W [F, C, kh, kw] fp32 + split descriptor -> (E_packed uint32-as-int32 [R, Fp], ecnt int32 [F, kh*kw])."""
-    F, C, kh, kw = W.shape
+def pack_weights_outputs(F, C, kh, kw, dev):
+    """Empty (E_packed, ecnt) of dab_pack_weights."""
     R, Fp = kh * kw * words_per_pixel(C), padded_filters(F)
-    E = torch.empty((R, Fp), dtype=torch.int32, device=W.device)
-    ecnt = torch.empty((F, kh * kw), dtype=torch.int32, device=W.device)
+    return (torch.empty((R, Fp), dtype=torch.int32, device=dev),
+            torch.empty((F, kh * kw), dtype=torch.int32, device=dev))
+
+
+def dab_pack_weights(W, thr_val, thr_idx, alpha_is_upper, out=None):
+    """W [F, C, kh, kw] fp32 + split descriptor -> (E_packed uint32-as-int32 [R, Fp], ecnt int32 [F, kh*kw]).
+
+    out: an (E_packed, ecnt) pair from pack_weights_outputs() to write into."""
+    F, C, kh, kw = W.shape
+    E, ecnt = out if out is not None else pack_weights_outputs(F, C, kh, kw, W.device)
     _check("dab_pack_weights", lib().dab_pack_weights(
         _ptr(W, torch.float32, "W"), F, C, kh, kw, _ptr(thr_val, torch.float32, "thr_val"),
         _ptr(thr_idx, torch.int32, "thr_idx"), _ptr(alpha_is_upper, torch.uint8, "alpha_is_upper"),
-        E.data_ptr(), ecnt.data_ptr(), _stream()))
+        _ptr(E, torch.int32, "E_packed"), _ptr(ecnt, torch.int32, "ecnt"), _stream()))
     return E, ecnt
 
 
@@ -152,15 +176,6 @@ def dab_pack_activations(X, layout=DAB_LAYOUT_NHWC, tau=None, out=None):
         _ptr(X, torch.float32, "X"), layout, B, C, H, W, _ptr(tau, torch.float32, "tau"),
         _ptr(A, torch.int32, "A_packed"), _stream()))
     return A
-
-
-def _workspace(nbytes, dev, ws):
-    """A caller-supplied workspace tensor if it is large enough, else a fresh one (None when none is needed)."""
-    if nbytes == 0:
-        return None
-    if ws is not None and ws.numel() * ws.element_size() >= nbytes:
-        return ws
-    return torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
 
 def dab_binconv2d(desc, A_packed, E_packed, alpha, beta, want_s1=False, out=None, ws=None):

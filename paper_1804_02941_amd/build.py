@@ -25,7 +25,52 @@ FLAGS = [
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    # per-kernel register / LDS report, parsed below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+
+def kernel_resources(log: str) -> dict:
+    """{kernel name: {"VGPRs": .., "AGPRs": .., "ScratchSize [bytes/lane]": .., ...}} from hipcc's remarks."""
+    out, cur = {}, None
+    for line in log.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1].split("[-Rpass-analysis", 1)[0].strip()
+        if text.startswith("Function Name:"):
+            cur = out.setdefault(text.split(":", 1)[1].strip(), {})
+        elif cur is not None and ":" in text:
+            key, val = text.rsplit(":", 1)
+            try:
+                cur[key.strip()] = int(val)
+            except ValueError:
+                pass
+    return out
+
+
+def check_resources(res: dict) -> None:
+    """Refuse a build with a kernel whose register allocation is exactly 64 VGPRs (granule 8, no AGPRs).
+
+    Measured on MI355X with the estimation kernel: such an allocation gave wrong results whenever two
+    workgroups shared a compute unit, the same instructions with a 72-register allocation did not."""
+    for name, r in res.items():
+        v, a = r.get("VGPRs", 0), r.get("AGPRs", 0)
+        if a == 0 and 56 < v <= 64:
+            raise RuntimeError(f"kernel {name} is allocated exactly 64 VGPRs; reserve one more register in it")
+
+
+def _without_remarks(text: str) -> str:
+    """Compiler output minus the resource remarks (and their source excerpts) and a known harmless warning."""
+    keep, skipping = [], False
+    for line in text.splitlines():
+        if "-Rpass-analysis=kernel-resource-usage" in line or "is not a recognized feature for this target" in line:
+            skipping = True
+            continue
+        if skipping and (line.lstrip().startswith("|") or line.split("|", 1)[0].strip().isdigit()):
+            continue
+        skipping = False
+        keep.append(line)
+    return "\n".join(keep)
 
 
 def build(verbose: bool = False) -> str:
@@ -36,12 +81,20 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    noise = "is not a recognized feature for this target"
-    log = "\n".join(line for line in proc.stdout.splitlines() if noise not in line)
+    log = _without_remarks(proc.stdout)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + log)
     if verbose and log.strip():
         print(log, flush=True)
+    res = kernel_resources(proc.stdout)
+    if not res:
+        raise RuntimeError("hipcc printed no kernel resource report")
+    check_resources(res)
+    if verbose:
+        for name, r in sorted(res.items()):
+            print(f"  {name}: VGPRs {r.get('VGPRs')} AGPRs {r.get('AGPRs')} SGPRs {r.get('TotalSGPRs')} "
+                  f"LDS {r.get('LDS Size [bytes/block]')} scratch {r.get('ScratchSize [bytes/lane]')} "
+                  f"waves/SIMD {r.get('Occupancy [waves/SIMD]')}", flush=True)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 

@@ -12,20 +12,27 @@
 // of the product is not the one that ships.
 //
 // A launch is two or three kernels:
-//   prepare   one streaming kernel whose blocks (a) expand the activation bits to fp4 with a
-//             zero halo of the padding width, so the main loop needs no bounds checks, and
-//             (b) expand the weight bits to fp4 in the order B fragments are consumed;
+//   prepare   one streaming kernel whose blocks (a) expand the activation bits to fp4, with a
+//             zero halo of the padding width so the main loop needs no bounds checks, laid out
+//             as planes [32-channel word][padded pixel][16 bytes] (a half-wavefront then reads
+//             512 contiguous bytes for 32 neighbouring pixels), (b) expand the weight bits to
+//             fp4 in the order B fragments are consumed, (c) sum the +1/-1 inputs of every
+//             padded pixel, (d) write the table of A4 byte offsets of the k-steps (k-steps run
+//             over the taps of one 64-channel block, then the next block, so consecutive steps
+//             touch neighbouring pixels of the same planes), and, for split launches, (e) sA;
 //   main      one workgroup owns 128 filters and keeps their B fragments in LDS (the whole
 //             reduction if it fits in 144 KB, else chunk by chunk).  Each wavefront computes
 //             64 pixels x 128 filters: A fragments (32 pixels x 64 channels, 16 bytes per lane)
-//             come straight from global memory through a register prefetch queue, B fragments
-//             from LDS one step ahead, accumulators stay in registers.  Big layers run
-//             persistent workgroups (one per compute unit) that walk over pixel tiles and
-//             write y directly; layers too small to fill the chip are also split along the
-//             reduction and write their exact partial sums to the workspace.  sA needs no
-//             pass of its own: -1 is the only code with bit 3 set, so two VALU instructions
-//             per fragment word, in the shadow of the MFMAs, count the -1 entries of every
-//             row as the A fragments stream by, and sA = C * (taps inside the image) - 2 * that;
+//             come from global memory by buffer loads (pixel offset per lane, k-step offset in
+//             a scalar register read from the table) through a queue of register slots, B
+//             fragments from LDS one step ahead, accumulators stay in registers.  The eight
+//             MFMAs of a k-step are issued with one LDS read or buffer load in the shadow of
+//             each (measured: issued back to back in front of them, the memory instructions
+//             cost their full issue time).  Big layers run persistent workgroups (one per
+//             compute unit) that walk over pixel tiles and write y directly; sA of a row is the
+//             box sum of the per-pixel sums over the window, read before the reduction loop.
+//             Layers too small to fill the chip are also split along the reduction and write
+//             their exact partial sums to the workspace;
 //   finish    (split launches only) adds the partials, y = (alpha-beta)*s1 + beta*sA.
 #include "dab_internal.h"
 
@@ -40,6 +47,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int kNTile = 128;          // filters per workgroup
 constexpr int kMaxChunk = 36;        // k-steps of B fragments held in LDS at a time (36 x 4 KB)
 constexpr int kPrefetch = 4;         // A fragments in flight per 32-pixel row block
+constexpr int kTabPad = 16;          // entries of the k-step offset table past the last step
 
 struct MfmaGeom {
     int B, H, W, F, kh, kw, ph, pw, sh, sw;
@@ -50,9 +58,12 @@ struct MfmaGeom {
     int kchunk;                    // k-steps staged in LDS at a time
     int n_ntiles, n_mtiles;        // 128-filter tiles, pixel tiles of 64 * WAVES
     int wg_per_ntile;              // persistent workgroups per filter tile (direct mode)
-    FastDiv d_HoWo, d_Wo, d_KB, d_Wp, d_HpWp, d_words, d_nk, d_mtiles, d_ksplit;
+    int T, npix, plane;            // taps, padded pixels, bytes of one 32-channel plane of A4
+    int act_p, act_w, act_wt;      // prepare: pixels x words of a transpose tile (product 256), word tiles
+    int sum_shift;                 // prepare: log2 of the lanes that share one pixel's row sum
+    FastDiv d_HoWo, d_Wo, d_Wp, d_HpWp, d_nk, d_mtiles, d_ksplit, d_T, d_kw, d_act_wt, d_Cw;
     // block ranges of the prepare kernel
-    unsigned blk_act, blk_wgt;
+    unsigned blk_act, blk_wgt, blk_sum, blk_tab, blk_sa;
 };
 
 // 8 bits -> 8 nibbles, bit i in bit 0 of nibble i.
@@ -66,39 +77,55 @@ __device__ __forceinline__ uint32_t spread8(uint32_t x) {
 // ---------------------------------------------------------------- prepare
 __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, const uint32_t* __restrict__ A,
                                                               const uint32_t* __restrict__ E,
-                                                              uint4* __restrict__ A4, uint4* __restrict__ E4) {
+                                                              uint4* __restrict__ A4, uint4* __restrict__ E4,
+                                                              int32_t* __restrict__ pixsum, int32_t* __restrict__ ktab,
+                                                              float* __restrict__ sA) {
+    __shared__ uint4 tile[256];
     unsigned blk = blockIdx.x;
     if (blk < g.blk_act) {
-        // activations: one thread per 32 channels (one bit word, 16 bytes of fp4) of a padded pixel
-        const long long i = 1ll * blk * 256 + threadIdx.x;
-        const int words = 2 * g.KB;
-        if (i >= 1ll * g.B * g.Hp * g.Wp * words) return;
-        const int pp = fdiv(static_cast<int>(i), g.d_words);      // padded pixel index (< 2^31 / 32)
-        const int w = static_cast<int>(i) - pp * words;
-        const int b = fdiv(pp, g.d_HpWp);
-        const int r = pp - b * g.Hp * g.Wp;
-        const int yp = fdiv(r, g.d_Wp);
-        const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
-        uint4 out = make_uint4(0, 0, 0, 0);
-        if (y >= 0 && y < g.H && x >= 0 && x < g.W && w < g.Cw) {
-            const uint32_t bits = A[((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.Cw + w];
-            const int nv = min(32, g.C - 32 * w);
-            const uint32_t valid = nv == 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
-            uint32_t o[4];
+        // activations: 32 channels (one bit word) of a padded pixel become 16 bytes of fp4, written as
+        // planes [word][padded pixel] so that a half-wavefront of the main kernel reads 512 contiguous
+        // bytes for 32 neighbouring pixels.  A block transposes a tile of act_p pixels x act_w words
+        // through LDS: bit words are read along the channels, fp4 is written along the pixels.
+        const int tp = fdiv(static_cast<int>(blk), g.d_act_wt);            // pixel tile
+        const int tw = static_cast<int>(blk) - tp * g.act_wt;              // word tile
+        {
+            const int pl = threadIdx.x / g.act_w, wl = threadIdx.x - pl * g.act_w;
+            const int pp = tp * g.act_p + pl, w = tw * g.act_w + wl;
+            uint4 out = make_uint4(0, 0, 0, 0);
+            if (pp < g.npix && w < g.Cw) {
+                const int b = fdiv(pp, g.d_HpWp);
+                const int r = pp - b * g.Hp * g.Wp;
+                const int yp = fdiv(r, g.d_Wp);
+                const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
+                if (y >= 0 && y < g.H && x >= 0 && x < g.W) {
+                    const uint32_t bits = A[((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.Cw + w];
+                    const int nv = min(32, g.C - 32 * w);
+                    const uint32_t valid = nv == 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
+                    uint32_t o[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t s = spread8((bits >> (8 * q)) & 0xFFu);
-                const uint32_t v = spread8((valid >> (8 * q)) & 0xFFu) * 0xFu;
-                o[q] = (0xAAAAAAAAu ^ (s << 3)) & v;                // bit 1 -> +1.0, bit 0 -> -1.0, past C -> 0
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t s = spread8((bits >> (8 * q)) & 0xFFu);
+                        const uint32_t v = spread8((valid >> (8 * q)) & 0xFFu) * 0xFu;
+                        o[q] = (0xAAAAAAAAu ^ (s << 3)) & v;            // bit 1 -> +1.0, bit 0 -> -1.0, past C -> 0
+                    }
+                    out = make_uint4(o[0], o[1], o[2], o[3]);
+                }
             }
-            out = make_uint4(o[0], o[1], o[2], o[3]);
+            tile[threadIdx.x] = out;
         }
-        A4[i] = out;
+        __syncthreads();
+        {
+            const int wl = threadIdx.x / g.act_p, pl = threadIdx.x - wl * g.act_p;
+            const int pp = tp * g.act_p + pl, w = tw * g.act_w + wl;
+            if (pp < g.npix && w < 2 * g.KB) A4[static_cast<size_t>(w) * g.npix + pp] = tile[pl * g.act_w + wl];
+        }
         return;
     }
     blk -= g.blk_act;
-    {
-        // weights: bits [R][Fp] -> fragments [ntile][kstep][4 column blocks][k half][32 filters][16 bytes]
+    if (blk < g.blk_wgt) {
+        // weights: bits [R][Fp] -> fragments [ntile][kstep][4 column blocks][k half][32 filters][16 bytes];
+        // k-steps run over the taps of one 64-channel block, then the next block
         const long long i = 1ll * blk * 256 + threadIdx.x;
         if (i >= 1ll * g.n_ntiles * g.nk * 256) return;
         const int fl = static_cast<int>(i & 31);
@@ -107,8 +134,9 @@ __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, 
         const int tk = static_cast<int>(i >> 8);
         const int nt = fdiv(tk, g.d_nk);
         const int ks = tk - nt * g.nk;
-        const int tap = fdiv(ks, g.d_KB);
-        const int w = 2 * (ks - tap * g.KB) + half;
+        const int kb = fdiv(ks, g.d_T);
+        const int tap = ks - kb * g.T;
+        const int w = 2 * kb + half;
         const int f = nt * kNTile + nf * 32 + fl;
         uint4 out = make_uint4(0, 0, 0, 0);
         if (w < g.Cw && f < g.Fp) {
@@ -117,6 +145,72 @@ __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, 
                              spread8((bits >> 16) & 0xFFu) << 1, spread8(bits >> 24) << 1);   // bit 1 -> 1.0
         }
         E4[i] = out;
+        return;
+    }
+    blk -= g.blk_wgt;
+    if (blk < g.blk_sum) {
+        // per padded pixel: sum of its +1/-1 inputs (0 in the halo); sA of an output is the box sum of
+        // these.  sum_tpp lanes (a power of two) share one pixel's words.
+        const int gi = static_cast<int>(blk * 256 + threadIdx.x);
+        const int pp = gi >> g.sum_shift, sub = gi & ((1 << g.sum_shift) - 1);
+        int ones = 0;
+        bool inside = false;
+        if (pp < g.npix) {
+            const int b = fdiv(pp, g.d_HpWp);
+            const int r = pp - b * g.Hp * g.Wp;
+            const int yp = fdiv(r, g.d_Wp);
+            const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
+            inside = y >= 0 && y < g.H && x >= 0 && x < g.W;
+            if (inside) {
+                const uint32_t* px = A + ((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.Cw;
+                for (int w = sub; w < g.Cw; w += 1 << g.sum_shift) ones += __builtin_popcount(px[w]);
+            }
+        }
+        for (int d = 1; d < (1 << g.sum_shift); d <<= 1) ones += __shfl_xor(ones, d, 64);
+        if (pp >= g.npix || sub != 0) return;
+        const int v = inside ? 2 * ones - g.C : 0;
+        pixsum[pp] = v;
+        return;
+    }
+    blk -= g.blk_sum;
+    if (blk < g.blk_tab) {
+        // byte offset into A4 of every k-step (taps of one 64-channel block, then the next block);
+        // entries past the end repeat the last step
+        const int i = static_cast<int>(blk * 256 + threadIdx.x);
+        if (i >= g.nk + kTabPad) return;
+        const int ks = min(i, g.nk - 1);
+        const int kb = fdiv(ks, g.d_T);
+        const int tap = ks - kb * g.T;
+        const int ky = fdiv(tap, g.d_kw);
+        const int kx = tap - ky * g.kw;
+        ktab[i] = kb * 2 * g.plane + (ky * g.Wp + kx) * 16;
+        return;
+    }
+    blk -= g.blk_tab;
+    {
+        // split launches only: sA of every output pixel, one wavefront per pixel, lanes over the
+        // (tap, word) pairs of its window
+        const int m = static_cast<int>(blk * 4 + (threadIdx.x >> 6));
+        if (m >= g.M) return;
+        const int lane = threadIdx.x & 63;
+        const int b = fdiv(m, g.d_HoWo);
+        const int r = m - b * g.HoWo;
+        const int oy = fdiv(r, g.d_Wo);
+        const int ox = r - oy * g.Wo;
+        int acc = 0;
+        for (int it = lane; it < g.T * g.Cw; it += 64) {
+            const int tap = fdiv(it, g.d_Cw);
+            const int w = it - tap * g.Cw;
+            const int ky = fdiv(tap, g.d_kw);
+            const int kx = tap - ky * g.kw;
+            const int y = oy * g.sh - g.ph + ky, x = ox * g.sw - g.pw + kx;
+            if (y >= 0 && y < g.H && x >= 0 && x < g.W) {
+                const int nv = min(32, g.C - 32 * w);
+                acc += 2 * __builtin_popcount(A[((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.Cw + w]) - nv;
+            }
+        }
+        for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+        if (lane == 0) sA[m] = static_cast<float>(acc);
     }
 }
 
@@ -130,13 +224,21 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
 
 enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2 };
 
+
+// One group of the k-step schedule: an MFMA, then at most one LDS read or one buffer load in its shadow.
+#define DAB_SLOT_DS()   do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); } while (0)
+#define DAB_SLOT_VMEM() do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); } while (0)
+#define DAB_SLOT_NONE() do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); } while (0)
+
 template <int WAVES, int MODE>
 __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom g, const char* __restrict__ A4,
                                                                   const uint4* __restrict__ E4,
                                                                   const float* __restrict__ alpha,
                                                                   const float* __restrict__ beta,
                                                                   float* __restrict__ Y, int32_t* __restrict__ dbg_s1,
-                                                                  float* __restrict__ ws_s1, float* __restrict__ ws_sA) {
+                                                                  float* __restrict__ ws_s1, float* __restrict__ ws_sA,
+                                                                  const int32_t* __restrict__ pixsum,
+                                                                  const int32_t* __restrict__ ktab) {
     constexpr int THREADS = 64 * WAVES;
     constexpr int MTILE = 64 * WAVES;
     extern __shared__ __align__(16) uint4 panel[];                 // [kchunk][4][64 lanes] 16-byte groups
@@ -164,6 +266,9 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
     const int f0 = ntile * kNTile;
     const uint4* Epanel = E4 + static_cast<size_t>(ntile) * g.nk * 256;
     const int nchunks = (kend - kbeg + g.kchunk - 1) / g.kchunk;
+    // A4 as a buffer resource: the per-lane pixel offset rides in a VGPR, the k-step offset in an SGPR
+    const __amdgpu_buffer_rsrc_t a4rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(A4), 0, 2 * g.KB * g.plane, 0x00020000);
 
     // per-lane scalars of the four 32-filter column blocks
     float dcol[4], bcol[4];
@@ -178,8 +283,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
     bool staged = false;
     for (int mt = mt_first; mt < g.n_mtiles; mt += mt_step) {
         const int m_base = mt * MTILE + wave * 64;
-        int pixoff[2], mvalid[2];
-        uint32_t neg[2] = {0u, 0u};                                  // -1 entries seen in this lane's half rows
+        int pixoff[2], mypix = 0;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int m = min(m_base + i * 32 + (lane & 31), g.M - 1);
@@ -187,10 +291,24 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             const int r = m - b * g.HoWo;
             const int oy = fdiv(r, g.d_Wo);
             const int ox = r - oy * g.Wo;
-            pixoff[i] = (((b * g.Hp + oy * g.sh) * g.Wp + ox * g.sw) * g.KB) * 32 + (lane >> 5) * 16;
-            const int ty = min(g.H, oy * g.sh - g.ph + g.kh) - max(0, oy * g.sh - g.ph);
-            const int tx = min(g.W, ox * g.sw - g.pw + g.kw) - max(0, ox * g.sw - g.pw);
-            mvalid[i] = g.C * ty * tx;                               // inputs of this pixel inside the image
+            const int pix = (b * g.Hp + oy * g.sh) * g.Wp + ox * g.sw;
+            pixoff[i] = pix * 16 + (lane >> 5) * g.plane;
+            if (i == (lane >> 5)) mypix = pix;                         // lane l owns row l of the 64 for the row sums
+        }
+        // sA of this lane's row: box sum of the per-pixel sums over the filter window (the first T
+        // entries of the k-step table are the window's pixel offsets, times 16).  Sixteen loads at a
+        // time; the result is needed only after the reduction loop.
+        float rowsum = 0.0f;
+        if (MODE != kOutSplit) {
+            int sum = 0;
+            for (int t0 = 0; t0 < g.T; t0 += 16) {
+                int v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = pixsum[mypix + (ktab[min(t0 + u, g.T - 1)] >> 4)];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) sum += t0 + u < g.T ? v[u] : 0;
+            }
+            rowsum = static_cast<float>(sum);
         }
         v16f acc[2][4];
 #pragma unroll
@@ -209,8 +327,12 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             if (!staged || nchunks > 1) {
                 __syncthreads();                                   // previous users of the panel are done
                 const int groups = (ks1 - ks0) * 256;
-                // eight 16-byte groups in flight per thread: the copy is latency-bound otherwise
-                for (int e0 = 0; e0 < steps * 256; e0 += 8 * THREADS) {
+                // eight 16-byte groups in flight per thread: the copy is latency-bound otherwise.
+                // Workgroups of one filter tile read the same panel; each starts at another batch.
+                const int nbatch = (steps * 256 + 8 * THREADS - 1) / (8 * THREADS);
+                int bi = blockIdx.x % nbatch;
+                for (int it = 0; it < nbatch; ++it) {
+                    const int e0 = bi * 8 * THREADS;
                     uint4 t[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -222,40 +344,28 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                         const int e = e0 + u * THREADS + tid;
                         if (e < steps * 256) panel[e] = t[u];
                     }
+                    bi = bi + 1 == nbatch ? 0 : bi + 1;
                 }
                 __syncthreads();
                 staged = true;
             }
-            // A fragments: a queue of kPrefetch k-steps per row block, refilled as it drains.
-            // The byte offset of the k-step being fetched is tracked with scalar counters
-            // (channel block, then tap column, then tap row) and stops at the last step.
-            int pf = ks0;
-            int pkb, pkx, pky;
-            {
-                const int tap = ks0 / g.KB;
-                pkb = ks0 - tap * g.KB;
-                pky = tap / g.kw;
-                pkx = tap - pky * g.kw;
-            }
-            int poff = ((pky * g.Wp + pkx) * g.KB + pkb) * 32;
-            auto advance = [&]() {   // branch-free, so the k loop stays one basic block
-                const int go = pf < ks1 - 1 ? 1 : 0;
-                pf += go;
-                pkb += go;
-                const int wrap_b = pkb == g.KB ? 1 : 0;
-                pkb = wrap_b ? 0 : pkb;
-                pkx += wrap_b;
-                const int wrap_x = pkx == g.kw ? 1 : 0;
-                pkx = wrap_x ? 0 : pkx;
-                pky += wrap_x;
-                poff = ((pky * g.Wp + pkx) * g.KB + pkb) * 32;
+            // A fragments: a queue of kPrefetch k-steps per row block, refilled as it drains.  The
+            // byte offset of a k-step comes from the table the prepare kernel wrote (four per
+            // scalar load); steps past the end re-read the last fragment against zero B fragments.
+            auto load_a = [&](int i, int poff) -> v4i {
+                const auto v = __builtin_amdgcn_raw_buffer_load_b128(a4rsrc, pixoff[i], poff, 0);
+                return v4i{static_cast<int>(v[0]), static_cast<int>(v[1]), static_cast<int>(v[2]), static_cast<int>(v[3])};
             };
+            // Slot d of the queue holds the fragments of step st + d; the slot emptied by the previous
+            // step is refilled during this one (kPrefetch - 1 steps ahead), so a register is never
+            // live as both a pending load and an operand and the loop carries no copies.
+            const int* kt = ktab + ks0;
             v4i abuf[kPrefetch][2];
 #pragma unroll
-            for (int d = 0; d < kPrefetch; ++d) {
+            for (int d = 0; d < kPrefetch - 1; ++d) {
+                const int p = kt[d];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) abuf[d][i] = *reinterpret_cast<const v4i*>(A4 + pixoff[i] + poff);
-                advance();
+                for (int i = 0; i < 2; ++i) abuf[d][i] = load_a(i, p);
             }
             const uint4* bp = panel + lane;
             uint4 bq[2][4];
@@ -268,63 +378,42 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                     const uint4* bn = bp + static_cast<size_t>(min(st + d + 1, steps - 1)) * 256;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) bq[(d + 1) & 1][j] = bn[j * 64];
-                    const v4i a0 = abuf[d][0], a1 = abuf[d][1];
-                    {
-                        // bit 3 of a nibble is set only for -1; steps past the chunk's end repeat the
-                        // last fragment and are masked out
-                        const uint32_t keep = ks0 + st + d < ks1 ? 0x88888888u : 0u;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            neg[0] += __builtin_popcount(static_cast<uint32_t>(a0[c]) & keep);
-                            neg[1] += __builtin_popcount(static_cast<uint32_t>(a1[c]) & keep);
-                        }
-                    }
-                    abuf[d][0] = *reinterpret_cast<const v4i*>(A4 + pixoff[0] + poff);
-                    abuf[d][1] = *reinterpret_cast<const v4i*>(A4 + pixoff[1] + poff);
-                    advance();
-                    __builtin_amdgcn_sched_barrier(0);   // keep the fetches ahead of the multiplies
+                    constexpr int kAhead = kPrefetch - 1;
+                    const int p = kt[st + d + kAhead];
+                    abuf[(d + kAhead) % kPrefetch][0] = load_a(0, p);
+                    abuf[(d + kAhead) % kPrefetch][1] = load_a(1, p);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const uint4 bu = bq[d & 1][j];
                         const v4i bv = {static_cast<int>(bu.x), static_cast<int>(bu.y), static_cast<int>(bu.z),
                                         static_cast<int>(bu.w)};
-                        acc[0][j] = mfma_fp4(a0, bv, acc[0][j]);
-                        acc[1][j] = mfma_fp4(a1, bv, acc[1][j]);
+                        acc[0][j] = mfma_fp4(abuf[d][0], bv, acc[0][j]);
+                        acc[1][j] = mfma_fp4(abuf[d][1], bv, acc[1][j]);
                     }
+                    // issue order of this k-step: every memory instruction in the shadow of an MFMA
+                    DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS();
+                    DAB_SLOT_VMEM(); DAB_SLOT_NONE(); DAB_SLOT_VMEM(); DAB_SLOT_NONE();
                 }
             }
         }
-
-        // ---- row sums: the two k halves of a row sit in lanes l and l + 32
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int n2 = static_cast<int>(neg[i]) + __shfl_xor(static_cast<int>(neg[i]), 32, 64);
-            const bool first = MODE != kOutSplit || ksplit_id == 0;
-            const float srow = static_cast<float>((first ? mvalid[i] : 0) - 2 * n2);   // sA (or this split's share)
-            if (lane < 32) sA_lds[wave][i * 32 + lane] = srow;
-        }
-        // (the wavefront reads back only what it wrote itself: no workgroup barrier needed)
 
         // ---- epilogue.  Register v of a 32x32 block is row (v/4)*8 + (lane/32)*4 + v%4,
         // column lane%32, so the 32 lanes of a half-wavefront touch 128 contiguous bytes of one
         // output row.  Direct mode: y = (alpha - beta)*s1 + beta*sA; interior tiles store
         // without any predicate, so nothing orders one store behind another.  Split mode: the
-        // exact partial s1 (and the partial row sum) go to this split's slice of the workspace.
+        // exact partial s1 goes to this split's slice of the workspace.
         const bool interior = m_base + 64 <= g.M && f0 + kNTile <= g.F;
         float4 s4[2][4];
+        if (MODE != kOutSplit) sA_lds[wave][lane] = rowsum;
+        // (the wavefront reads back only what it wrote itself: no workgroup barrier needed)
+        if (MODE != kOutSplit) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                s4[i][q] = *reinterpret_cast<const float4*>(&sA_lds[wave][i * 32 + q * 8 + (lane >> 5) * 4]);
-        float* out = MODE == kOutSplit ? ws_s1 + static_cast<size_t>(ksplit_id) * g.M * g.F : Y;
-        if (MODE == kOutSplit && ntile == 0 && lane < 32) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = m_base + i * 32 + lane;
-                if (row < g.M) ws_sA[static_cast<size_t>(ksplit_id) * g.M + row] = sA_lds[wave][i * 32 + lane];
-            }
+                for (int q = 0; q < 4; ++q)
+                    s4[i][q] = *reinterpret_cast<const float4*>(&sA_lds[wave][i * 32 + q * 8 + (lane >> 5) * 4]);
         }
+        float* out = MODE == kOutSplit ? ws_s1 + static_cast<size_t>(ksplit_id) * g.M * g.F : Y;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -359,11 +448,9 @@ __global__ __launch_bounds__(256) void binconv_finish_kernel(const float* __rest
     if (i >= total) return;
     const int m = static_cast<int>(i / F);
     const int f = static_cast<int>(i - static_cast<size_t>(m) * F);
-    float s1 = 0.f, sA = 0.f;                       // integer-valued, exact in any order
-    for (int k = 0; k < ksplit; ++k) {
-        s1 += ws_s1[static_cast<size_t>(k) * total + i];
-        sA += ws_sA[static_cast<size_t>(k) * M + m];
-    }
+    float s1 = 0.f;                                 // integer-valued, exact in any order
+    for (int k = 0; k < ksplit; ++k) s1 += ws_s1[static_cast<size_t>(k) * total + i];
+    const float sA = ws_sA[m];
     const float al = alpha[f], be = beta[f];
     Y[i] = fmaf(al - be, s1, be * sA);
     if (dbg_s1) dbg_s1[i] = static_cast<int>(s1);
@@ -407,7 +494,7 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     // compute units busy on mid-sized ones.  When even 256-pixel tiles leave most compute
     // units idle, the reduction is split until about one unit per compute unit exists.
     const int tiles256 = ceil_div(g.M, 256) * g.n_ntiles;
-    pl->waves = 1ll * ceil_div(g.M, 512) * g.n_ntiles >= kNumCU ? 8 : 4;
+    pl->waves = 1ll * ceil_div(g.M, 512) * g.n_ntiles >= kNumCU * 3 / 4 ? 8 : 4;
     g.ksplit = 1;
     if (tiles256 * 2 <= kNumCU) {
         g.ksplit = kNumCU / tiles256;
@@ -429,25 +516,39 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     pl->grid = pl->split ? static_cast<unsigned>(g.n_ntiles * g.n_mtiles * g.ksplit)
                          : static_cast<unsigned>(g.wg_per_ntile * g.n_ntiles);
 
-    g.d_HoWo = make_fastdiv(g.HoWo); g.d_Wo = make_fastdiv(g.Wo); g.d_KB = make_fastdiv(g.KB);
-    g.d_Wp = make_fastdiv(g.Wp); g.d_HpWp = make_fastdiv(g.Hp * g.Wp); g.d_words = make_fastdiv(2 * g.KB);
+    g.T = d.kh * d.kw; g.npix = d.B * g.Hp * g.Wp; g.plane = g.npix * 16;
+    g.d_HoWo = make_fastdiv(g.HoWo); g.d_Wo = make_fastdiv(g.Wo);
+    g.d_Wp = make_fastdiv(g.Wp); g.d_HpWp = make_fastdiv(g.Hp * g.Wp);
+    g.d_T = make_fastdiv(g.T); g.d_kw = make_fastdiv(g.kw); g.d_Cw = make_fastdiv(g.Cw);
     g.d_nk = make_fastdiv(g.nk); g.d_mtiles = make_fastdiv(g.n_mtiles); g.d_ksplit = make_fastdiv(g.ksplit);
 
     pl->a4_bytes = round256(static_cast<size_t>(a4));
     pl->e4_bytes = static_cast<size_t>(g.n_ntiles) * g.nk * 4096;
-    pl->sa_bytes = pl->split ? round256(static_cast<size_t>(g.ksplit) * g.M * 4) : 0;
+    pl->sa_bytes = round256(static_cast<size_t>(g.M) * 4) + round256(static_cast<size_t>(g.npix) * 4) +
+                   round256(static_cast<size_t>(g.nk + kTabPad) * 4);
     pl->s1_bytes = pl->split ? round256(static_cast<size_t>(g.ksplit) * g.M * d.F * 4) : 0;
     pl->ws_bytes = pl->a4_bytes + pl->e4_bytes + pl->sa_bytes + pl->s1_bytes;
     pl->lds_bytes = static_cast<size_t>(g.kchunk) * 4096;
 
-    g.blk_act = static_cast<unsigned>((a4 / 16 + 255) / 256);
+    g.act_w = 2 * g.KB >= 8 ? 8 : 2 * g.KB;                      // 2, 4, 6 (-> 4 x 64 would not divide) ...
+    while (256 % g.act_w) --g.act_w;
+    g.act_p = 256 / g.act_w;
+    g.act_wt = ceil_div(2 * g.KB, g.act_w);
+    g.d_act_wt = make_fastdiv(g.act_wt);
+    g.blk_act = static_cast<unsigned>(ceil_div(g.npix, g.act_p)) * g.act_wt;
+    g.sum_shift = 0;
+    while (g.sum_shift < 6 && (4 << g.sum_shift) < g.Cw) ++g.sum_shift;       // about four words per lane
     g.blk_wgt = static_cast<unsigned>((1ll * g.n_ntiles * g.nk * 256 + 255) / 256);
+    g.blk_sum = static_cast<unsigned>((1ll * g.npix * (1 << g.sum_shift) + 255) / 256);
+    g.blk_tab = static_cast<unsigned>((g.nk + kTabPad + 255) / 256);
+    g.blk_sa = pl->split ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
     return DAB_OK;
 }
 
 template <int WAVES, int MODE>
 static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const uint4* e4, float* sa,
-                       const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, float* ws_s1) {
+                       const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, float* ws_s1,
+                       const int32_t* pixsum, const int32_t* ktab) {
     static thread_local size_t granted = 0;
     if (pl.lds_bytes > 48 * 1024 && pl.lds_bytes > granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE>),
@@ -456,7 +557,7 @@ static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const
         granted = pl.lds_bytes;
     }
     hipLaunchKernelGGL((binconv_mfma_kernel<WAVES, MODE>), dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4,
-                       e4, alpha, beta, Y, dbg_s1, ws_s1, sa);
+                       e4, alpha, beta, Y, dbg_s1, ws_s1, sa, pixsum, ktab);
     return launch_status();
 }
 
@@ -471,22 +572,24 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
     float* s1 = reinterpret_cast<float*>(a4 + pl.a4_bytes + pl.e4_bytes + pl.sa_bytes);
     const MfmaGeom& g = pl.g;
 
-    hipLaunchKernelGGL(binconv_prepare_kernel, dim3(g.blk_act + g.blk_wgt), dim3(256), 0, st, g, A, E,
-                       reinterpret_cast<uint4*>(a4), e4);
+    int32_t* pixsum = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(sa) + round256(static_cast<size_t>(g.M) * 4));
+    int32_t* ktab = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pixsum) + round256(static_cast<size_t>(g.npix) * 4));
+    hipLaunchKernelGGL(binconv_prepare_kernel, dim3(g.blk_act + g.blk_wgt + g.blk_sum + g.blk_tab + g.blk_sa), dim3(256), 0,
+                       st, g, A, E, reinterpret_cast<uint4*>(a4), e4, pixsum, ktab, sa);
     if (int rc = launch_status()) return rc;
 
     if (pl.split) {
-        if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1)) return rc;
+        if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab)) return rc;
         const size_t total = static_cast<size_t>(g.M) * d.F;
         hipLaunchKernelGGL(binconv_finish_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, s1,
                            sa, alpha, beta, Y, dbg_s1, g.M, d.F, g.ksplit);
         return launch_status();
     }
     if (pl.waves == 8)
-        return dbg_s1 ? launch_main<8, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1)
-                      : launch_main<8, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1);
-    return dbg_s1 ? launch_main<4, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1)
-                  : launch_main<4, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1);
+        return dbg_s1 ? launch_main<8, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab)
+                      : launch_main<8, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab);
+    return dbg_s1 ? launch_main<4, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab)
+                  : launch_main<4, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab);
 }
 
 static int check_common(const void* A, const void* E, const void* alpha, const void* beta, const void* Y,

@@ -78,6 +78,32 @@ def test_estimate_sizes(n):
     assert differ <= 1
 
 
+@pytest.mark.parametrize("n", [150, 700, 1200, 1600, 1792, 2304, 2816, 3000, 3584, 4608, 5632, 7168, 9216, 11264, 13312])
+def test_estimate_many_filters_share_compute_units(n):
+    """Every kernel configuration with several workgroups resident per compute unit.
+
+    1536 filters in one launch put up to six workgroups on a compute unit; the same rows estimated
+    128 at a time (at most one workgroup per unit) must give identical results, and a sample of
+    the rows is checked against the oracle.  Regression test: configurations whose register
+    allocation was exactly 64 VGPRs passed alone and failed as soon as workgroups shared a unit.
+    """
+    rng = np.random.default_rng(1000 + n)
+    F = 1536
+    W = (rng.standard_normal((F, n)) * 0.05).astype(np.float32)
+    Wt = gu.to_gpu(W)
+    whole = dab.dab_estimate_alpha_beta(Wt)
+    again = dab.dab_estimate_alpha_beta(Wt)
+    parts = [dab.dab_estimate_alpha_beta(Wt[f0:f0 + 128].contiguous()) for f0 in range(0, F, 128)]
+    torch.cuda.synchronize()
+    for key in whole:
+        chunks = torch.cat([p[key] for p in parts])
+        assert torch.equal(whole[key], chunks), f"{key}: one launch differs from 128-filter launches"
+        assert torch.equal(whole[key], again[key]), f"{key}: two identical launches differ"
+    pick = rng.choice(F, size=24, replace=False)
+    got = {k: v.cpu().numpy()[pick] for k, v in whole.items()}
+    gu.check_estimate(W[pick], got)
+
+
 @pytest.mark.parametrize("kind", ["gauss", "laplace", "mixture", "dupes", "onesided"])
 def test_estimate_distributions(kind):
     rng = np.random.default_rng(17)
