@@ -42,6 +42,12 @@ __device__ __forceinline__ int fdiv(int n, FastDiv d) {
     return static_cast<int>((__umulhi(d.mul, static_cast<uint32_t>(n)) + static_cast<uint32_t>(n)) >> d.shift);
 }
 
+// Keeps a kernel's register allocation above 64 VGPRs by naming v71 as clobbered (it costs nothing
+// else).  Measured on MI355X: an estimation kernel that the compiler fitted into exactly 64 VGPRs
+// returned wrong results as soon as two of its workgroups shared a compute unit, the identical
+// instructions were right with a 72-register allocation; the build refuses 64-VGPR kernels.
+#define DAB_RESERVE_VGPRS() asm volatile("" ::: "v71")
+
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kNumCU = 256;          // MI355X compute units
 constexpr int kNumXCD = 8;           // accelerator complex dies, each with its own L2

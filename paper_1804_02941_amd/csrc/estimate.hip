@@ -71,11 +71,7 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     __shared__ int r_s;
     __shared__ float thr_s;
 
-    // Keep the register allocation of every instantiation above 64 VGPRs.  Measured on MI355X: the
-    // instantiations that the compiler fits into exactly 64 VGPRs (7 items per thread) return wrong
-    // splits as soon as two of their workgroups share a compute unit, with identical instructions
-    // giving correct results once the allocation is 72; naming v71 as clobbered costs nothing else.
-    asm volatile("" ::: "v71");
+    DAB_RESERVE_VGPRS();   // the 7-items-per-thread instantiations would land on exactly 64 VGPRs
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* row = Wt + static_cast<size_t>(blockIdx.x) * n;
 

@@ -10,42 +10,115 @@ namespace dab {
 
 // ---------------------------------------------------------------- activations, NHWC
 // One work item = 64 consecutive channels of one pixel.  The compare writes its result as
-// a 64-bit lane mask (the wavefront ballot), which is exactly the two packed words.  Eight
-// items are in flight per wavefront; lanes 0..15 then store the sixteen words.
-constexpr int kItemsPerWave = 8;
+// a 64-bit lane mask (the wavefront ballot), which is exactly the two packed words.  The grid
+// is sized to the chip and every wavefront walks over the items with sixteen 256-byte loads
+// in flight; lanes 0..31 then store the thirty-two words.  When the 64-channel groups of a
+// pixel divide sixteen, a wavefront meets the same groups in every batch and keeps their
+// thresholds in registers.
+constexpr int kItemsPerWave = 16;
 
+template <bool PERIODIC>
 __global__ __launch_bounds__(256) void pack_act_nhwc_kernel(const float* __restrict__ X, const float* __restrict__ tau,
                                                             uint32_t* __restrict__ A, int n_items,
                                                             int C, int Cw, int Cw64, FastDiv d_Cw64) {
+    DAB_RESERVE_VGPRS();
     const int lane = threadIdx.x & 63;
     const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const int t0 = wave * kItemsPerWave;
-    if (t0 >= n_items) return;
+    const int n_waves = gridDim.x * (blockDim.x >> 6);
 
-    float x[kItemsPerWave], th[kItemsPerWave];
-    bool ok[kItemsPerWave];
+    float th[kItemsPerWave];
+    if (PERIODIC) {
 #pragma unroll
-    for (int u = 0; u < kItemsPerWave; ++u) {
-        const int t = t0 + u;
-        const int p = fdiv(t, d_Cw64);
-        const int c = (t - p * Cw64) * 64 + lane;
-        ok[u] = t < n_items && c < C;
-        x[u] = ok[u] ? X[static_cast<size_t>(p) * C + c] : 0.0f;
-        th[u] = (ok[u] && tau) ? tau[c] : 0.0f;
+        for (int u = 0; u < kItemsPerWave; ++u) {
+            const int c = (u & (Cw64 - 1)) * 64 + lane;             // Cw64 is a power of two here
+            th[u] = (tau && c < C) ? tau[c] : 0.0f;
+        }
     }
-    // lane i stores half (i & 1) of item (i >> 1)
-    uint32_t word = 0;
+    for (int t0 = wave * kItemsPerWave; t0 < n_items; t0 += n_waves * kItemsPerWave) {
+        float x[kItemsPerWave];
+        bool ok[kItemsPerWave];
 #pragma unroll
-    for (int u = 0; u < kItemsPerWave; ++u) {
-        const unsigned long long mask = __ballot(ok[u] && x[u] >= th[u]);
-        if (lane == 2 * u) word = static_cast<uint32_t>(mask);
-        if (lane == 2 * u + 1) word = static_cast<uint32_t>(mask >> 32);
+        for (int u = 0; u < kItemsPerWave; ++u) {
+            const int t = t0 + u;
+            const int p = fdiv(t, d_Cw64);
+            const int c = (t - p * Cw64) * 64 + lane;
+            ok[u] = t < n_items && c < C;
+            x[u] = ok[u] ? X[static_cast<size_t>(p) * C + c] : 0.0f;
+            if (!PERIODIC) th[u] = (ok[u] && tau) ? tau[c] : 0.0f;
+        }
+        // lane i stores half (i & 1) of item (i >> 1)
+        uint32_t word = 0;
+#pragma unroll
+        for (int u = 0; u < kItemsPerWave; ++u) {
+            const unsigned long long mask = __ballot(ok[u] && x[u] >= th[u]);
+            if (lane == 2 * u) word = static_cast<uint32_t>(mask);
+            if (lane == 2 * u + 1) word = static_cast<uint32_t>(mask >> 32);
+        }
+        if (lane < 2 * kItemsPerWave) {
+            const int t = t0 + (lane >> 1);
+            const int p = fdiv(t, d_Cw64);
+            const int w = (t - p * Cw64) * 2 + (lane & 1);
+            if (t < n_items && w < Cw) A[static_cast<size_t>(p) * Cw + w] = word;
+        }
     }
-    if (lane < 2 * kItemsPerWave) {
-        const int t = t0 + (lane >> 1);
-        const int p = fdiv(t, d_Cw64);
-        const int w = (t - p * Cw64) * 2 + (lane & 1);
-        if (t < n_items && w < Cw) A[static_cast<size_t>(p) * Cw + w] = word;
+}
+
+// Fast path: C a multiple of 64 whose 64-channel groups divide sixteen.  Item t then starts at
+// float 64*t of X and at word 2*t of A, so a batch of sixteen items is one base address plus
+// immediate offsets, and the thresholds of the batch stay in registers.
+__global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float* __restrict__ X,
+                                                                    const float* __restrict__ tau,
+                                                                    uint32_t* __restrict__ A, int n_items, int Cw64) {
+    DAB_RESERVE_VGPRS();
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int n_waves = gridDim.x * (blockDim.x >> 6);
+    float th[kItemsPerWave];
+#pragma unroll
+    for (int u = 0; u < kItemsPerWave; ++u) th[u] = tau ? tau[(u & (Cw64 - 1)) * 64 + lane] : 0.0f;
+
+    // full batches: the loads of the next batch are issued before the current one is balloted
+    const int step = n_waves * kItemsPerWave;
+    int t0 = wave * kItemsPerWave;
+    float x[kItemsPerWave];
+    if (t0 + kItemsPerWave <= n_items) {
+        const float* px = X + static_cast<size_t>(t0) * 64 + lane;
+#pragma unroll
+        for (int u = 0; u < kItemsPerWave; ++u) x[u] = px[u * 64];
+    }
+    for (; t0 + kItemsPerWave <= n_items; t0 += step) {
+        float nx[kItemsPerWave];
+        const bool more = t0 + step + kItemsPerWave <= n_items;
+        if (more) {
+            const float* px = X + static_cast<size_t>(t0 + step) * 64 + lane;
+#pragma unroll
+            for (int u = 0; u < kItemsPerWave; ++u) nx[u] = px[u * 64];
+        }
+        uint32_t word = 0;
+#pragma unroll
+        for (int u = 0; u < kItemsPerWave; ++u) {
+            const unsigned long long mask = __ballot(x[u] >= th[u]);
+            if (lane == 2 * u) word = static_cast<uint32_t>(mask);
+            if (lane == 2 * u + 1) word = static_cast<uint32_t>(mask >> 32);
+        }
+        if (lane < 2 * kItemsPerWave) A[static_cast<size_t>(t0) * 2 + lane] = word;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < kItemsPerWave; ++u) x[u] = nx[u];
+        }
+    }
+    if (t0 < n_items) {   // the ragged last batch
+        const float* px = X + static_cast<size_t>(t0) * 64 + lane;
+#pragma unroll
+        for (int u = 0; u < kItemsPerWave; ++u) x[u] = t0 + u < n_items ? px[u * 64] : 0.0f;
+        uint32_t word = 0;
+#pragma unroll
+        for (int u = 0; u < kItemsPerWave; ++u) {
+            const unsigned long long mask = __ballot(x[u] >= th[u]);
+            if (lane == 2 * u) word = static_cast<uint32_t>(mask);
+            if (lane == 2 * u + 1) word = static_cast<uint32_t>(mask >> 32);
+        }
+        if (lane < 2 * kItemsPerWave && t0 + (lane >> 1) < n_items) A[static_cast<size_t>(t0) * 2 + lane] = word;
     }
 }
 
@@ -81,8 +154,9 @@ __global__ __launch_bounds__(256) void pack_act_nchw_kernel(const float* __restr
 // One workgroup per (padded) filter column.  The filter is brought into LDS with coalesced
 // reads, a slab of whole channels at a time; one work item is then 64 consecutive channels
 // of one tap, gathered from LDS with stride kh*kw, compared, balloted and written as two
-// words of column f.  Per-tap counts are accumulated in LDS.
-constexpr int kWeightSlabFloats = 12 * 1024;   // 48 KB
+// words of column f.  Per-tap counts are accumulated in LDS.  The slab holds a whole filter
+// of up to 24K weights, so most layers need one pass.
+constexpr int kWeightSlabFloats = 24 * 1024;   // 96 KB
 
 __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ Wt, const float* __restrict__ thr_val,
                                                            const int32_t* __restrict__ thr_idx,
@@ -106,8 +180,19 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
 
     for (int c0 = 0; c0 < C; c0 += slab_c) {
         const int nc = min(slab_c, C - c0);
+        const float* src = wf + static_cast<size_t>(c0) * T;
+        const int count = nc * T;
+        // 16-byte loads over the aligned body of the range; element i lands in sl[i], where sl is
+        // shifted so that the body is 16-byte aligned in LDS as well
+        const int mis = static_cast<int>((reinterpret_cast<uintptr_t>(src) >> 2) & 3);
+        const int head = min((4 - mis) & 3, count);
+        const int body4 = (count - head) >> 2;
+        float* sl = slab + mis;
         __syncthreads();
-        for (int i = tid; i < nc * T; i += blockDim.x) slab[i] = wf[static_cast<size_t>(c0) * T + i];
+        if (tid < head) sl[tid] = src[tid];
+        for (int q = tid; q < body4; q += blockDim.x)
+            *reinterpret_cast<float4*>(sl + head + 4 * q) = *reinterpret_cast<const float4*>(src + head + 4 * q);
+        for (int i = head + 4 * body4 + tid; i < count; i += blockDim.x) sl[i] = src[i];
         __syncthreads();
         const int groups = (nc + 63) >> 6;                 // 64-channel groups in this slab
         for (int it = wave; it < groups * T; it += nwaves) {
@@ -116,7 +201,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
             const int cl = grp * 64 + lane;                // channel within the slab
             bool bit = false;
             if (cl < nc) {
-                const float w = slab[cl * T + tap];
+                const float w = sl[cl * T + tap];
                 const int idx = (c0 + cl) * T + tap;       // position in the flattened filter
                 const bool lower = w < tv || (w == tv && idx <= ti);
                 bit = lower != upper;
@@ -154,9 +239,20 @@ int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, i
         const long long n_items = pixels * Cw64;
         if (n_items >= (1ll << 30)) return DAB_ERR_UNSUPPORTED;
         const long long waves = (n_items + kItemsPerWave - 1) / kItemsPerWave;
-        const long long blocks = (waves + 3) / 4;
-        hipLaunchKernelGGL(pack_act_nhwc_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
-                           X, tau, A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
+        long long blocks = (waves + 3) / 4;
+        if (blocks > 4ll * kNumCU) blocks = 4ll * kNumCU;           // four wavefronts per SIMD, then loop
+        // sixteen consecutive items start at a multiple of sixteen, so the channel group of item u
+        // of a batch is u mod Cw64 whenever Cw64 divides sixteen
+        const bool periodic = Cw64 <= kItemsPerWave && (Cw64 & (Cw64 - 1)) == 0;
+        if (periodic && C % 64 == 0)
+            hipLaunchKernelGGL(pack_act_nhwc_aligned_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+                               X, tau, A_packed, static_cast<int>(n_items), Cw64);
+        else if (periodic)
+            hipLaunchKernelGGL(pack_act_nhwc_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+                               X, tau, A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
+        else
+            hipLaunchKernelGGL(pack_act_nhwc_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+                               X, tau, A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
     } else {
         const long long HW = 1ll * H * W;
         if (HW >= (1ll << 31) || Cw > 65535 || B > 65535) return DAB_ERR_UNSUPPORTED;
@@ -182,7 +278,14 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
     int slab_c = (kWeightSlabFloats / T) & ~63;             // whole 64-channel groups per slab
     if (slab_c < 64) return DAB_ERR_UNSUPPORTED;
     if (slab_c > C) slab_c = 64 * ceil_div(C, 64);
-    const size_t lds = static_cast<size_t>(slab_c) * T * sizeof(float);
+    const size_t lds = (static_cast<size_t>(slab_c) * T + 4) * sizeof(float);
+    static thread_local size_t granted = 0;
+    if (lds > 48 * 1024 && lds > granted) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_weights_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return hip_failed(e);
+        granted = lds;
+    }
     hipLaunchKernelGGL(pack_weights_kernel, dim3(Fp), dim3(256), lds, static_cast<hipStream_t>(stream),
                        W, thr_val, thr_idx, alpha_is_upper, E_packed, ecnt, F, C, T, Cw, Fp, slab_c);
     return launch_status();
