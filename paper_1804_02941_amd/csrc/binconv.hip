@@ -326,26 +326,19 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             const int steps = (ks1 - ks0 + kPrefetch - 1) / kPrefetch * kPrefetch;
             if (!staged || nchunks > 1) {
                 __syncthreads();                                   // previous users of the panel are done
-                const int groups = (ks1 - ks0) * 256;
-                // eight 16-byte groups in flight per thread: the copy is latency-bound otherwise.
-                // Workgroups of one filter tile read the same panel; each starts at another batch.
-                const int nbatch = (steps * 256 + 8 * THREADS - 1) / (8 * THREADS);
-                int bi = blockIdx.x % nbatch;
-                for (int it = 0; it < nbatch; ++it) {
-                    const int e0 = bi * 8 * THREADS;
-                    uint4 t[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int e = e0 + u * THREADS + tid;
-                        t[u] = e < groups ? Epanel[static_cast<size_t>(ks0) * 256 + e] : make_uint4(0, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int e = e0 + u * THREADS + tid;
-                        if (e < steps * 256) panel[e] = t[u];
-                    }
-                    bi = bi + 1 == nbatch ? 0 : bi + 1;
+                // The B fragments go straight from global memory into LDS (16 bytes per lane, 1 KB per
+                // wavefront instruction, no registers in between), all of the chunk in flight at once.
+                // Workgroups of one filter tile read the same panel; each starts at another KB.
+                const int nkb = (ks1 - ks0) * 4;                   // 1 KB pieces: 64 groups of 16 bytes
+                const uint4* src = Epanel + static_cast<size_t>(ks0) * 256;
+                const int rot = blockIdx.x % nkb;
+                for (int i = wave; i < nkb; i += WAVES) {
+                    int kb = i + rot;
+                    kb = kb >= nkb ? kb - nkb : kb;
+                    __builtin_amdgcn_global_load_lds(src + kb * 64 + lane, panel + kb * 64, 16, 0, 0);
                 }
+                for (int e = nkb * 64 + tid; e < steps * 256; e += THREADS) panel[e] = make_uint4(0, 0, 0, 0);
+                __builtin_amdgcn_s_waitcnt(0);                     // every counter to zero: the copies have landed
                 __syncthreads();
                 staged = true;
             }
