@@ -8,9 +8,13 @@ path over the batch: for every layer, alpha/beta estimation of its filters, weig
 packing, activation bit packing and the binary convolution / fully-connected product.  The
 fp32 inputs of all layers and the fp32 weights are resident in HBM before the timed region.
 
+A step is launched as one captured HIP graph: the weight sides of all layers (they depend on
+no activation) run first on side streams, then each layer packs its activations and runs its
+product on the main stream.  The timed region is K graph launches.
+
 Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
-kernel (the binary product on the matrix cores) from HIP-event timings taken inside the
-timed region, and the CPU oracle timed on a slice of the same workload.
+call (the binary product of the largest layer) from HIP-event timings of an eager pass over
+the same kernels, and the CPU oracle timed on the same workload.
 """
 from __future__ import annotations
 
@@ -33,15 +37,18 @@ if ROOT not in sys.path:
 MFMA_FP4_FLOPS = 10.1e15
 VALU_PAIR_MACS = 256 * 64 * 2.4e9 * 16
 HBM_BYTES_PER_S = 8.0e12
+# HBM bytes of one conv2 call at batch 256 (prepare + main kernel), from the FETCH_SIZE and WRITE_SIZE
+# counter runs summarised in profiles/bench_config3_hbm_counters.md
+CONV2_CALL_HBM_BYTES = 157098928
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
-    ap.add_argument("--cpu-batch", type=int, default=128, help="images of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-batch", type=int, default=256, help="images of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--side-streams", type=int, default=3,
                     help="HIP streams for the weight side (estimation + weight packing) of the layers; 0 = one stream")
     ap.add_argument("--no-graph", action="store_true",
@@ -225,7 +232,7 @@ def cpu_oracle_baseline(batch, wl):
         x = y.numpy()
     dt = time.perf_counter() - t0
     return {"value": macs / dt, "unit": "binary MAC/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"config 3, all six layers incl. alpha/beta estimation, batch {batch} of 256, {dt:.1f} s"}
+            "sample": f"config 3, all six layers incl. alpha/beta estimation, batch {batch} of 256, one pass, {dt:.1f} s"}
 
 
 def main():
@@ -294,28 +301,44 @@ def main():
 
     ms_per_step = 1e3 * dt / args.steps
     value = total_macs * args.steps / dt
-    # binary-product kernel: per-layer and aggregate, from the events of the kernel timing pass
+    # binary product: per layer and aggregate, from the events of the kernel timing pass.  With fp32
+    # outputs every large layer sits below the ridge of the fp4 matrix cores (conv2: 784 FLOP per
+    # algorithmic byte against 10.1e15 / 8e12 = 1262), so the bound that applies is HBM; the MFMA view
+    # is printed beside it.  Algorithmic bytes of a call = fp32 outputs + activation bits + weight bits
+    # + alpha and beta.
     per_layer = {}
     conv_ms = 0.0
-    out_bytes = 0
+    algo_bytes = 0
     for i, s in enumerate(states):
         ms = sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
         conv_ms += ms
-        out_bytes += s.Y.numel() * 4
+        nbytes = s.Y.numel() * 4 + s.A.numel() * 4 + s.EW[0].numel() * 4 + 8 * s.L.F
+        algo_bytes += nbytes
         per_layer[s.L.name] = {"ms": round(ms, 4), "gmacs": round(s.macs / 1e9, 3),
+                               "algorithmic_bytes": nbytes,
+                               "gb_per_s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                               "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / HBM_BYTES_PER_S, 4),
                                "tflops": round(2 * s.macs / (ms * 1e-3) / 1e12, 1),
-                               "frac_of_mfma_fp4_peak": round(2 * s.macs / (ms * 1e-3) / MFMA_FP4_FLOPS, 4),
-                               "output_gb_per_s": round(s.Y.numel() * 4 / (ms * 1e-3) / 1e9, 1)}
-    achieved = 2 * total_macs / (conv_ms * 1e-3) / 1e12
-    peak = MFMA_FP4_FLOPS / 1e12
-    roofline = {"bound": "mfma", "kernel": "binconv (prepare + binconv_mfma_kernel [+ finish]) of all six layers of a step",
-                "achieved": round(achieved, 1), "peak": round(peak, 1), "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": None,
+                               "frac_of_mfma_fp4_peak": round(2 * s.macs / (ms * 1e-3) / MFMA_FP4_FLOPS, 4)}
+    dom = max(per_layer, key=lambda k: per_layer[k]["ms"])         # the dominant call (conv2 at batch 256)
+    d = per_layer[dom]
+    traffic = CONV2_CALL_HBM_BYTES if (dom == "conv2" and args.batch == 256) else None
+    roofline = {"bound": "hbm",
+                "kernel": "dab_binconv2d of %s: binconv_prepare_kernel + binconv_mfma_kernel, bracketed by HIP events "
+                          "on the launch stream" % dom,
+                "achieved": d["gb_per_s"], "peak": HBM_BYTES_PER_S / 1e9, "unit": "GB/s",
+                "frac": d["frac_of_hbm_peak"], "traffic": traffic,
+                "algorithmic_bytes": d["algorithmic_bytes"], "launch_ms": d["ms"],
+                "mfma_view": {"achieved": d["tflops"], "peak": MFMA_FP4_FLOPS / 1e12, "unit": "TFLOP/s",
+                              "frac": d["frac_of_mfma_fp4_peak"]},
+                "all_layers": {"kernel_ms_per_step": round(conv_ms, 4), "algorithmic_bytes": algo_bytes,
+                               "gb_per_s": round(algo_bytes / (conv_ms * 1e-3) / 1e9, 1),
+                               "frac_of_hbm_peak": round(algo_bytes / (conv_ms * 1e-3) / HBM_BYTES_PER_S, 4),
+                               "tflops": round(2 * total_macs / (conv_ms * 1e-3) / 1e12, 1),
+                               "frac_of_mfma_fp4_peak": round(2 * total_macs / (conv_ms * 1e-3) / MFMA_FP4_FLOPS, 4),
+                               "binary_macs_per_s": total_macs / (conv_ms * 1e-3),
+                               "vs_valu_popcount_peak": round(total_macs / (conv_ms * 1e-3) / VALU_PAIR_MACS, 3)},
                 "kernel_ms_per_step": round(conv_ms, 4),
-                "binary_macs_per_s": total_macs / (conv_ms * 1e-3),
-                "vs_valu_popcount_peak": round(total_macs / (conv_ms * 1e-3) / VALU_PAIR_MACS, 3),
-                "output_bytes_per_step": out_bytes,
-                "output_frac_of_hbm_peak": round(out_bytes / (conv_ms * 1e-3) / HBM_BYTES_PER_S, 4),
                 "per_layer": per_layer}
 
     cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
