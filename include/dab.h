@@ -183,6 +183,40 @@ int dab_binfc(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const
               float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, void* stream);
 size_t dab_binfc_workspace_bytes(int32_t B, int32_t Kin, int32_t F);
 
+/*
+ * dab_binconv2d_bits / dab_binfc_bits - the same products with a re-binarizing epilogue: when
+ * the next layer is binarized as well (Section 4: its inputs are +1 / -1; the appendix's block
+ * puts the sign right after the previous binarized layer), the fp32 output is never needed, only
+ *     A_next bit f of pixel p = [ Y[p][f] >= tau_out[f] ],
+ * with Y[p][f] evaluated in fp32 exactly as dab_binconv2d evaluates it, so the result is identical,
+ * bit for bit, to dab_pack_activations applied to dab_binconv2d's output.  1/32 of the output
+ * bytes are written.
+ *
+ *   tau_out    [F] fp32 thresholds of the next layer's sign, or NULL for 0
+ *   A_next     uint32 [B][Ho][Wo][ceil(F/32)] out (dab_binfc_bits: [B][ceil(F/32)]), every word
+ *              written, bits past F are 0; this is the packed activation layout above with C = F
+ *   other arguments, workspace and errors as for dab_binconv2d / dab_binfc
+ */
+int dab_binconv2d_bits(const dab_conv_desc* d /* host */, const uint32_t* A_packed, const uint32_t* E_packed,
+                       const float* alpha, const float* beta, const float* tau_out, uint32_t* A_next,
+                       void* ws, size_t ws_bytes, void* stream);
+int dab_binfc_bits(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const uint32_t* E_packed,
+                   const float* alpha, const float* beta, const float* tau_out, uint32_t* A_next,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * dab_pool_bits - max-pooling between two binarized layers, on the packed signs.  The sign of a
+ * window's maximum is +1 iff any element's sign is +1 (one threshold per channel), so
+ * sign(maxpool(y) - tau) is the bitwise OR of the window's packed words.  Windows lie inside the
+ * image (no padding): Ho = (H - kh)/stride_h + 1, Wo likewise.  Sketch-A-Net (Section 5.1) pools
+ * 3x3 with stride 2 after its second and fifth convolutions.
+ *
+ *   A_packed   uint32 [B][H][W][ceil(C/32)];  A_pooled uint32 [B][Ho][Wo][ceil(C/32)] out
+ * Errors: a window larger than the image -> DAB_ERR_SHAPE.
+ */
+int dab_pool_bits(const uint32_t* A_packed, int32_t B, int32_t C, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                  int32_t stride_h, int32_t stride_w, uint32_t* A_pooled, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -166,3 +166,32 @@ def popcount_terms_1d(a_pm1, e01):
     pA = int(np.count_nonzero(A))
     pE = int(np.count_nonzero(E))
     return 2 * pAE - pE, 2 * (pA - pAE) - (n - pE), pAE, pA, pE
+
+
+# --------------------------------------------------------------------------
+# Between two binarized layers (Section 4: the next layer's inputs are again
+# +1 / -1; Section 5.1: Sketch-A-Net max-pools 3x3 / stride 2 after its second
+# and fifth convolutions).  Written as the definition: pool the real-valued
+# output, then take the sign.
+# --------------------------------------------------------------------------
+
+def max_pool(y: np.ndarray, kh: int, kw: int, sh: int, sw: int) -> np.ndarray:
+    """Max over kh x kw windows inside the image; y is [B, H, W, F], result [B, Ho, Wo, F]."""
+    y = np.asarray(y)
+    B, H, W, F = y.shape
+    Ho, Wo = (H - kh) // sh + 1, (W - kw) // sw + 1
+    out = np.full((B, Ho, Wo, F), -np.inf, dtype=y.dtype)
+    for ky in range(kh):
+        for kx in range(kw):
+            out = np.maximum(out, y[:, ky:ky + (Ho - 1) * sh + 1:sh, kx:kx + (Wo - 1) * sw + 1:sw, :])
+    return out
+
+
+def next_layer_input(y: np.ndarray, tau=None, pool=None) -> np.ndarray:
+    """The +1/-1 input of the following binarized layer from this layer's output y [B, Ho, Wo, F].
+
+    pool = (kh, kw, sh, sw) or None.  Result is NCHW int8, as binarize_activations returns it.
+    """
+    if pool is not None:
+        y = max_pool(y, *pool)
+    return binarize_activations(np.transpose(np.asarray(y), (0, 3, 1, 2)), tau)

@@ -59,6 +59,12 @@ _SIGNATURES = {
     "dab_binfc": (c_int, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                           c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_binfc_workspace_bytes": (c_size_t, [c_int32, c_int32, c_int32]),
+    "dab_binconv2d_bits": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p,
+                                   c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "dab_binfc_bits": (c_int, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                               c_void_p, c_void_p, c_size_t, c_void_p]),
+    "dab_pool_bits": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32,
+                              c_void_p, c_void_p]),
 }
 
 _lib = None
@@ -209,3 +215,43 @@ def dab_binfc(A_packed, E_packed, alpha, beta, Kin, want_s1=False, out=None, ws=
         _ptr(Y, torch.float32, "Y"), s1.data_ptr() if want_s1 else None,
         ws.data_ptr() if ws is not None else None, nbytes, _stream()))
     return (Y, s1) if want_s1 else Y
+
+
+def dab_binconv2d_bits(desc, A_packed, E_packed, alpha, beta, tau_out=None, out=None, ws=None):
+    """Binarized convolution with the re-binarizing epilogue; returns int32 [B,Ho,Wo,ceil(F/32)]."""
+    dev = A_packed.device
+    shape = (desc.B, desc.Ho, desc.Wo, words_per_pixel(desc.F))
+    A_next = out if out is not None else torch.empty(shape, dtype=torch.int32, device=dev)
+    nbytes = lib().dab_binconv2d_workspace_bytes(ctypes.byref(desc))
+    ws = _workspace(nbytes, dev, ws)
+    _check("dab_binconv2d_bits", lib().dab_binconv2d_bits(
+        ctypes.byref(desc), _ptr(A_packed, torch.int32, "A_packed"), _ptr(E_packed, torch.int32, "E_packed"),
+        _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"), _ptr(tau_out, torch.float32, "tau_out"),
+        _ptr(A_next, torch.int32, "A_next"), ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return A_next
+
+
+def dab_binfc_bits(A_packed, E_packed, alpha, beta, Kin, tau_out=None, out=None, ws=None):
+    """Binarized fully-connected layer with the re-binarizing epilogue; returns int32 [B, ceil(F/32)]."""
+    dev = A_packed.device
+    B, F = A_packed.shape[0], alpha.shape[0]
+    A_next = out if out is not None else torch.empty((B, words_per_pixel(F)), dtype=torch.int32, device=dev)
+    nbytes = lib().dab_binfc_workspace_bytes(B, Kin, F)
+    ws = _workspace(nbytes, dev, ws)
+    _check("dab_binfc_bits", lib().dab_binfc_bits(
+        B, Kin, F, _ptr(A_packed, torch.int32, "A_packed"), _ptr(E_packed, torch.int32, "E_packed"),
+        _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"), _ptr(tau_out, torch.float32, "tau_out"),
+        _ptr(A_next, torch.int32, "A_next"), ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return A_next
+
+
+def dab_pool_bits(A_packed, C, kh, kw, stride_h, stride_w, out=None):
+    """OR-pooling of packed signs: int32 [B,H,W,Cw] -> [B,Ho,Wo,Cw] (windows inside the image)."""
+    B, H, W, Cw = A_packed.shape
+    Ho, Wo = (H - kh) // stride_h + 1, (W - kw) // stride_w + 1
+    A_pooled = out if out is not None else torch.empty((B, max(Ho, 0), max(Wo, 0), Cw), dtype=torch.int32,
+                                                        device=A_packed.device)
+    _check("dab_pool_bits", lib().dab_pool_bits(
+        _ptr(A_packed, torch.int32, "A_packed"), B, C, H, W, kh, kw, stride_h, stride_w,
+        _ptr(A_pooled, torch.int32, "A_pooled"), _stream()))
+    return A_pooled

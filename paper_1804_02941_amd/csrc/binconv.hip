@@ -222,7 +222,7 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
 }
 
-enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2 };
+enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2, kOutBits = 3 };
 
 
 // One group of the k-step schedule: an MFMA, then at most one LDS read or one buffer load in its shadow.
@@ -238,7 +238,9 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                                                                   float* __restrict__ Y, int32_t* __restrict__ dbg_s1,
                                                                   float* __restrict__ ws_s1, float* __restrict__ ws_sA,
                                                                   const int32_t* __restrict__ pixsum,
-                                                                  const int32_t* __restrict__ ktab) {
+                                                                  const int32_t* __restrict__ ktab,
+                                                                  const float* __restrict__ tau_out,
+                                                                  uint32_t* __restrict__ out_bits) {
     constexpr int THREADS = 64 * WAVES;
     constexpr int MTILE = 64 * WAVES;
     extern __shared__ __align__(16) uint4 panel[];                 // [kchunk][4][64 lanes] 16-byte groups
@@ -271,13 +273,14 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(A4), 0, 2 * g.KB * g.plane, 0x00020000);
 
     // per-lane scalars of the four 32-filter column blocks
-    float dcol[4], bcol[4];
+    float dcol[4], bcol[4], tcol[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int f = min(f0 + j * 32 + (lane & 31), g.F - 1);
         const float al = alpha[f], be = beta[f];
         dcol[j] = al - be;
         bcol[j] = be;
+        tcol[j] = (MODE == kOutBits && tau_out) ? tau_out[f] : 0.0f;
     }
 
     bool staged = false;
@@ -406,6 +409,44 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                 for (int q = 0; q < 4; ++q)
                     s4[i][q] = *reinterpret_cast<const float4*>(&sA_lds[wave][i * 32 + q * 8 + (lane >> 5) * 4]);
         }
+        if (MODE == kOutBits) {
+            // Re-binarized output: bit = [y >= tau_f] with y evaluated exactly as in the fp32 output.
+            // The ballot of one accumulator register is the 32-filter word of two rows (lanes 0..31 and
+            // 32..63); lane l collects the four words of row l and stores them side by side.
+            uint32_t wb[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int r0 = i * 32 + q * 8 + t;             // row of lanes 0..31; lanes 32..63 hold r0 + 4
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float y = fmaf(dcol[j], acc[i][j][q * 4 + t], bcol[j] * sv[t]);
+                            const bool bit = f0 + j * 32 + (lane & 31) < g.F && y >= tcol[j];
+                            const unsigned long long mask = __ballot(bit);
+                            if (lane == r0) wb[j] = static_cast<uint32_t>(mask);
+                            if (lane == r0 + 4) wb[j] = static_cast<uint32_t>(mask >> 32);
+                        }
+                    }
+                }
+            }
+            const int row = m_base + lane;
+            const int Fw = (g.F + 31) >> 5;
+            if (row < g.M) {
+                uint32_t* dst = out_bits + static_cast<size_t>(row) * Fw + ntile * 4;
+                if ((Fw & 3) == 0) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (ntile * 4 + j < Fw) dst[j] = wb[j];
+                }
+            }
+            continue;
+        }
         float* out = MODE == kOutSplit ? ws_s1 + static_cast<size_t>(ksplit_id) * g.M * g.F : Y;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -447,6 +488,35 @@ __global__ __launch_bounds__(256) void binconv_finish_kernel(const float* __rest
     const float al = alpha[f], be = beta[f];
     Y[i] = fmaf(al - be, s1, be * sA);
     if (dbg_s1) dbg_s1[i] = static_cast<int>(s1);
+}
+
+// Split launches with re-binarized output: one wavefront per (pixel, 64 filters); the ballot of the
+// compare is the two packed words.
+__global__ __launch_bounds__(256) void binconv_finish_bits_kernel(const float* __restrict__ ws_s1,
+                                                                  const float* __restrict__ ws_sA,
+                                                                  const float* __restrict__ alpha,
+                                                                  const float* __restrict__ beta,
+                                                                  const float* __restrict__ tau_out,
+                                                                  uint32_t* __restrict__ out_bits, int M, int F,
+                                                                  int ksplit) {
+    const int lane = threadIdx.x & 63;
+    const int F64 = (F + 63) >> 6, Fw = (F + 31) >> 5;
+    const long long item = 1ll * blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= 1ll * M * F64) return;
+    const int m = static_cast<int>(item / F64);
+    const int f = static_cast<int>(item - 1ll * m * F64) * 64 + lane;
+    const size_t total = static_cast<size_t>(M) * F;
+    bool bit = false;
+    if (f < F) {
+        float s1 = 0.f;
+        for (int k = 0; k < ksplit; ++k) s1 += ws_s1[static_cast<size_t>(k) * total + static_cast<size_t>(m) * F + f];
+        const float al = alpha[f], be = beta[f];
+        bit = fmaf(al - be, s1, be * ws_sA[m]) >= (tau_out ? tau_out[f] : 0.0f);
+    }
+    const unsigned long long mask = __ballot(bit);
+    const int w = (f - lane) >> 5;
+    if (lane == 0) out_bits[static_cast<size_t>(m) * Fw + w] = static_cast<uint32_t>(mask);
+    if (lane == 32 && w + 1 < Fw) out_bits[static_cast<size_t>(m) * Fw + w + 1] = static_cast<uint32_t>(mask >> 32);
 }
 
 // ------------------------------------------------------------------ host side
@@ -541,7 +611,7 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
 template <int WAVES, int MODE>
 static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const uint4* e4, float* sa,
                        const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, float* ws_s1,
-                       const int32_t* pixsum, const int32_t* ktab) {
+                       const int32_t* pixsum, const int32_t* ktab, const float* tau_out, uint32_t* out_bits) {
     static thread_local size_t granted = 0;
     if (pl.lds_bytes > 48 * 1024 && pl.lds_bytes > granted) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE>),
@@ -550,12 +620,14 @@ static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const
         granted = pl.lds_bytes;
     }
     hipLaunchKernelGGL((binconv_mfma_kernel<WAVES, MODE>), dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4,
-                       e4, alpha, beta, Y, dbg_s1, ws_s1, sa, pixsum, ktab);
+                       e4, alpha, beta, Y, dbg_s1, ws_s1, sa, pixsum, ktab, tau_out, out_bits);
     return launch_status();
 }
 
+// Y != nullptr: fp32 output (and optional dbg_s1); Y == nullptr: re-binarized output into out_bits.
 static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t* E, const float* alpha,
-                       const float* beta, float* Y, int32_t* dbg_s1, void* ws, size_t ws_bytes, hipStream_t st) {
+                       const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits,
+                       void* ws, size_t ws_bytes, hipStream_t st) {
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl)) return rc;
     if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
@@ -572,17 +644,26 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
     if (int rc = launch_status()) return rc;
 
     if (pl.split) {
-        if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab)) return rc;
+        if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)) return rc;
         const size_t total = static_cast<size_t>(g.M) * d.F;
+        if (!Y) {
+            const long long items = 1ll * g.M * ceil_div(d.F, 64);
+            hipLaunchKernelGGL(binconv_finish_bits_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st,
+                               s1, sa, alpha, beta, tau_out, out_bits, g.M, d.F, g.ksplit);
+            return launch_status();
+        }
         hipLaunchKernelGGL(binconv_finish_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, s1,
                            sa, alpha, beta, Y, dbg_s1, g.M, d.F, g.ksplit);
         return launch_status();
     }
+    if (!Y)
+        return pl.waves == 8 ? launch_main<8, kOutBits>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)
+                             : launch_main<4, kOutBits>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits);
     if (pl.waves == 8)
-        return dbg_s1 ? launch_main<8, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab)
-                      : launch_main<8, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab);
-    return dbg_s1 ? launch_main<4, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab)
-                  : launch_main<4, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab);
+        return dbg_s1 ? launch_main<8, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)
+                      : launch_main<8, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits);
+    return dbg_s1 ? launch_main<4, kOutYDebug>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)
+                  : launch_main<4, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits);
 }
 
 static int check_common(const void* A, const void* E, const void* alpha, const void* beta, const void* Y,
@@ -626,7 +707,7 @@ int dab_binconv2d(const dab_conv_desc* d, const uint32_t* A_packed, const uint32
     if (!d) return DAB_ERR_NULL;
     if (int rc = dab::check_common(A_packed, E_packed, alpha, beta, Y, dbg_s1)) return rc;
     if (int rc = dab::check_desc(d)) return rc;
-    return dab::run_binconv(*d, A_packed, E_packed, alpha, beta, Y, dbg_s1, ws, ws_bytes,
+    return dab::run_binconv(*d, A_packed, E_packed, alpha, beta, Y, dbg_s1, nullptr, nullptr, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -636,7 +717,33 @@ int dab_binfc(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const
     if (int rc = dab::check_common(A_packed, E_packed, alpha, beta, Y, dbg_s1)) return rc;
     if (B < 1 || Kin < 2 || F < 1) return DAB_ERR_SHAPE;
     const dab_conv_desc d{B, Kin, 1, 1, F, 1, 1, 0, 0, 1, 1};
-    return dab::run_binconv(d, A_packed, E_packed, alpha, beta, Y, dbg_s1, ws, ws_bytes,
+    return dab::run_binconv(d, A_packed, E_packed, alpha, beta, Y, dbg_s1, nullptr, nullptr, ws, ws_bytes,
+                            static_cast<hipStream_t>(stream));
+}
+
+int dab_binconv2d_bits(const dab_conv_desc* d, const uint32_t* A_packed, const uint32_t* E_packed,
+                       const float* alpha, const float* beta, const float* tau_out, uint32_t* A_next,
+                       void* ws, size_t ws_bytes, void* stream) {
+    if (!d) return DAB_ERR_NULL;
+    if (!A_packed || !E_packed || !alpha || !beta || !A_next) return DAB_ERR_NULL;
+    if (dab::misaligned(A_packed, 16) || dab::misaligned(E_packed, 64) || dab::misaligned(A_next, 16) ||
+        dab::misaligned(alpha, 4) || dab::misaligned(beta, 4) || (tau_out && dab::misaligned(tau_out, 4)))
+        return DAB_ERR_ALIGN;
+    if (int rc = dab::check_desc(d)) return rc;
+    return dab::run_binconv(*d, A_packed, E_packed, alpha, beta, nullptr, nullptr, tau_out, A_next, ws, ws_bytes,
+                            static_cast<hipStream_t>(stream));
+}
+
+int dab_binfc_bits(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const uint32_t* E_packed,
+                   const float* alpha, const float* beta, const float* tau_out, uint32_t* A_next,
+                   void* ws, size_t ws_bytes, void* stream) {
+    if (!A_packed || !E_packed || !alpha || !beta || !A_next) return DAB_ERR_NULL;
+    if (dab::misaligned(A_packed, 16) || dab::misaligned(E_packed, 64) || dab::misaligned(A_next, 16) ||
+        dab::misaligned(alpha, 4) || dab::misaligned(beta, 4) || (tau_out && dab::misaligned(tau_out, 4)))
+        return DAB_ERR_ALIGN;
+    if (B < 1 || Kin < 2 || F < 1) return DAB_ERR_SHAPE;
+    const dab_conv_desc d{B, Kin, 1, 1, F, 1, 1, 0, 0, 1, 1};
+    return dab::run_binconv(d, A_packed, E_packed, alpha, beta, nullptr, nullptr, tau_out, A_next, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
 }
 

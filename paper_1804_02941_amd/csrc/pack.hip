@@ -219,9 +219,44 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
     for (int t = tid; t < T; t += blockDim.x) ecnt[static_cast<size_t>(f) * T + t] = cnt[t];
 }
 
+// ---------------------------------------------------------------- max-pool on packed signs
+// sign(max over a window of y - tau) = OR over the window of sign(y - tau): pooling a re-binarized
+// layer output is a bitwise OR of its packed words.  One thread per output word.
+__global__ __launch_bounds__(256) void pool_bits_kernel(const uint32_t* __restrict__ A, uint32_t* __restrict__ out,
+                                                        int B, int H, int W, int Cw, int Ho, int Wo, int kh, int kw,
+                                                        int sh, int sw, FastDiv d_Cw, FastDiv d_Wo, FastDiv d_Ho) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * Ho * Wo * Cw) return;
+    const int p = fdiv(i, d_Cw), w = i - p * Cw;
+    const int q = fdiv(p, d_Wo), ox = p - q * Wo;
+    const int b = fdiv(q, d_Ho), oy = q - b * Ho;
+    uint32_t v = 0;
+    for (int ky = 0; ky < kh; ++ky)
+        for (int kx = 0; kx < kw; ++kx)
+            v |= A[((static_cast<size_t>(b) * H + oy * sh + ky) * W + ox * sw + kx) * Cw + w];
+    out[i] = v;
+}
+
 }  // namespace dab
 
 extern "C" {
+
+int dab_pool_bits(const uint32_t* A_packed, int32_t B, int32_t C, int32_t H, int32_t W, int32_t kh, int32_t kw,
+                  int32_t stride_h, int32_t stride_w, uint32_t* A_pooled, void* stream) {
+    using namespace dab;
+    if (!A_packed || !A_pooled) return DAB_ERR_NULL;
+    if (B < 1 || C < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || stride_h < 1 || stride_w < 1 || kh > H || kw > W)
+        return DAB_ERR_SHAPE;
+    if (misaligned(A_packed, 16) || misaligned(A_pooled, 16)) return DAB_ERR_ALIGN;
+    const int Cw = ceil_div(C, 32);
+    const int Ho = (H - kh) / stride_h + 1, Wo = (W - kw) / stride_w + 1;
+    const long long n = 1ll * B * Ho * Wo * Cw;
+    if (n >= (1ll << 31) || 1ll * B * H * W * Cw >= (1ll << 31)) return DAB_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(pool_bits_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), A_packed, A_pooled, B, H, W, Cw, Ho, Wo, kh, kw, stride_h,
+                       stride_w, make_fastdiv(Cw), make_fastdiv(Wo), make_fastdiv(Ho));
+    return launch_status();
+}
 
 int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, int32_t H, int32_t W,
                          const float* tau, uint32_t* A_packed, void* stream) {
