@@ -53,6 +53,7 @@ def parse():
                     help="HIP streams for the weight side (estimation + weight packing) of the layers; 0 = one stream")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of one captured HIP graph per step")
+    ap.add_argument("--no-fused", action="store_true", help="skip the fused-chain measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
                          "HBM byte counters of a rocprofv3 --pmc run)")
@@ -170,6 +171,66 @@ class Schedule:
 
     def capture(self, dab):
         """The step as one HIP graph (kernel launches and stream dependencies only)."""
+        torch = self.torch
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            self.step(dab)
+        return graph
+
+
+class FusedChain:
+    """The same six layers with the re-binarizing epilogue: bits are handed from layer to layer
+    (3/2 max-pooling as an OR on the bits after conv2 and conv5), so between conv2 and fc7 no fp32
+    activation is written or read.  conv2 packs its fp32 input as in the plain step and fc7 writes
+    fp32.  Thresholds of the hand-over are the per-channel means the plain step uses.  The weight
+    sides run first on the schedule's side streams, as in the plain step."""
+
+    def __init__(self, states, sched, dab, torch):
+        self.states, self.sched, self.torch = states, sched, torch
+        self.bits = []
+        for s in states:
+            L = s.L
+            if L.is_fc:
+                self.bits.append(None)
+                continue
+            out = torch.empty((s.B, L.Ho, L.Wo, dab.words_per_pixel(L.F)), dtype=torch.int32, device=s.X.device)
+            pooled = None
+            if L.pool_after:
+                pooled = torch.empty((s.B, (L.Ho - 3) // 2 + 1, (L.Wo - 3) // 2 + 1, dab.words_per_pixel(L.F)),
+                                     dtype=torch.int32, device=s.X.device)
+            self.bits.append((out, pooled))
+
+    def step(self, dab, events=None):
+        torch, states, sched = self.torch, self.states, self.sched
+        main = torch.cuda.current_stream()
+        sched.fork.record(main)
+        for q, idxs, done in zip(sched.side, sched.assign, sched.ready):
+            q.wait_event(sched.fork)
+            with torch.cuda.stream(q):
+                for i in idxs:
+                    weight_side(states[i], dab)
+            done.record(q)
+        activation_side(states[0], dab)
+        for done in sched.ready:
+            main.wait_event(done)
+        A = states[0].A
+        for i, s in enumerate(states):
+            if events is not None:
+                events[i][0].record()
+            if s.desc is None:
+                dab.dab_binfc(A.view(s.B, -1), s.EW[0], s.est["alpha"], s.est["beta"], s.L.C, out=s.Y, ws=s.ws)
+            else:
+                out, pooled = self.bits[i]
+                dab.dab_binconv2d_bits(s.desc, A, s.EW[0], s.est["alpha"], s.est["beta"], states[i + 1].tau, out=out,
+                                       ws=s.ws)
+                A = out
+                if pooled is not None:
+                    dab.dab_pool_bits(out, s.L.F, 3, 3, 2, 2, out=pooled)
+                    A = pooled
+            if events is not None:
+                events[i][1].record()
+
+    def capture(self, dab):
         torch = self.torch
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
@@ -341,6 +402,35 @@ def main():
                 "kernel_ms_per_step": round(conv_ms, 4),
                 "per_layer": per_layer}
 
+    # The next row of the scope table, measured beside the headline: the fused chain
+    fused = None
+    if args.side_streams > 0 and not args.no_fused:
+        chain = FusedChain(states, sched, dab, torch)
+        for _ in range(args.warmup):
+            chain.step(dab)
+        torch.cuda.synchronize()
+        fev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in states]
+               for _ in range(args.steps)]
+        for k in range(args.steps):
+            chain.step(dab, fev[k])
+        torch.cuda.synchronize()
+        fgraph = chain.capture(dab)
+        for _ in range(args.warmup):
+            fgraph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            fgraph.replay()
+        torch.cuda.synchronize()
+        fdt = time.perf_counter() - t0
+        fused = {"what": "same layers, bits handed from layer to layer by dab_binconv2d_bits / dab_pool_bits "
+                         "(fp32 only into conv2 and out of fc7); one HIP graph per step",
+                 "ms_per_step": round(1e3 * fdt / args.steps, 4),
+                 "binary_macs_per_s": total_macs * args.steps / fdt,
+                 "product_ms_per_layer": {s.L.name: round(sum(fev[k][i][0].elapsed_time(fev[k][i][1])
+                                                              for k in range(args.steps)) / args.steps, 4)
+                                          for i, s in enumerate(states)}}
+
     cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
     line = {
         "metric": "effective binary MACs/s on Sketch-A-Net binarized layers",
@@ -354,7 +444,7 @@ def main():
                    "launch": "eager" if args.no_graph else "one captured HIP graph per step",
                    "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
                    "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "rebinarized_chain": fused,
     }
     print(json.dumps(line))
 

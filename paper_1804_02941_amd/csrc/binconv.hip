@@ -283,7 +283,26 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         tcol[j] = (MODE == kOutBits && tau_out) ? tau_out[f] : 0.0f;
     }
 
+    // The B fragments go straight from global memory into LDS (16 bytes per lane, 1 KB per wavefront
+    // instruction, no registers in between), all of a chunk in flight at once.  Workgroups of one
+    // filter tile read the same panel; each starts at another KB.  Steps past the end of the chunk
+    // (it is rounded up to the prefetch depth) hold zeros.
+    auto stage_panel = [&](int ks0, int ks1, int steps) {
+        const int nkb = (ks1 - ks0) * 4;                           // 1 KB pieces: 64 groups of 16 bytes
+        const uint4* src = Epanel + static_cast<size_t>(ks0) * 256;
+        const int rot = blockIdx.x % nkb;
+        for (int i = wave; i < nkb; i += WAVES) {
+            int kb = i + rot;
+            kb = kb >= nkb ? kb - nkb : kb;
+            __builtin_amdgcn_global_load_lds(src + kb * 64 + lane, panel + kb * 64, 16, 0, 0);
+        }
+        for (int e = nkb * 64 + tid; e < steps * 256; e += THREADS) panel[e] = make_uint4(0, 0, 0, 0);
+    };
+    // A reduction that fits in LDS is staged once, and its copies are issued first of all so that
+    // they fly while the first tile's addresses and row sums are worked out.
     bool staged = false;
+    if (nchunks == 1 && mt_first < g.n_mtiles)
+        stage_panel(kbeg, kend, (kend - kbeg + kPrefetch - 1) / kPrefetch * kPrefetch);
     for (int mt = mt_first; mt < g.n_mtiles; mt += mt_step) {
         const int m_base = mt * MTILE + wave * 64;
         int pixoff[2], mypix = 0;
@@ -327,21 +346,14 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             // k-steps of this chunk rounded up to the prefetch depth; the extra steps multiply
             // zero B fragments (and re-read the last valid A fragment), so the loop has no tail
             const int steps = (ks1 - ks0 + kPrefetch - 1) / kPrefetch * kPrefetch;
-            if (!staged || nchunks > 1) {
+            if (nchunks > 1) {
                 __syncthreads();                                   // previous users of the panel are done
-                // The B fragments go straight from global memory into LDS (16 bytes per lane, 1 KB per
-                // wavefront instruction, no registers in between), all of the chunk in flight at once.
-                // Workgroups of one filter tile read the same panel; each starts at another KB.
-                const int nkb = (ks1 - ks0) * 4;                   // 1 KB pieces: 64 groups of 16 bytes
-                const uint4* src = Epanel + static_cast<size_t>(ks0) * 256;
-                const int rot = blockIdx.x % nkb;
-                for (int i = wave; i < nkb; i += WAVES) {
-                    int kb = i + rot;
-                    kb = kb >= nkb ? kb - nkb : kb;
-                    __builtin_amdgcn_global_load_lds(src + kb * 64 + lane, panel + kb * 64, 16, 0, 0);
-                }
-                for (int e = nkb * 64 + tid; e < steps * 256; e += THREADS) panel[e] = make_uint4(0, 0, 0, 0);
+                stage_panel(ks0, ks1, steps);
                 __builtin_amdgcn_s_waitcnt(0);                     // every counter to zero: the copies have landed
+                __syncthreads();
+            } else if (!staged) {
+                // the copies were issued before the first tile's address work and row sums
+                __builtin_amdgcn_s_waitcnt(0);
                 __syncthreads();
                 staged = true;
             }
@@ -413,7 +425,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             // Re-binarized output: bit = [y >= tau_f] with y evaluated exactly as in the fp32 output.
             // The ballot of one accumulator register is the 32-filter word of two rows (lanes 0..31 and
             // 32..63); lane l collects the four words of row l and stores them side by side.
-            uint32_t wb[4] = {0u, 0u, 0u, 0u};
+            int wb[4] = {0, 0, 0, 0};
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -427,8 +439,11 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                             const float y = fmaf(dcol[j], acc[i][j][q * 4 + t], bcol[j] * sv[t]);
                             const bool bit = f0 + j * 32 + (lane & 31) < g.F && y >= tcol[j];
                             const unsigned long long mask = __ballot(bit);
-                            if (lane == r0) wb[j] = static_cast<uint32_t>(mask);
-                            if (lane == r0 + 4) wb[j] = static_cast<uint32_t>(mask >> 32);
+                            // the two halves of the (wavefront-uniform) mask go to lanes r0 and r0 + 4
+                            asm volatile("v_writelane_b32 %0, %1, %2"
+                                         : "+v"(wb[j]) : "s"(static_cast<uint32_t>(mask)), "n"(r0));
+                            asm volatile("v_writelane_b32 %0, %1, %2"
+                                         : "+v"(wb[j]) : "s"(static_cast<uint32_t>(mask >> 32)), "n"(r0 + 4));
                         }
                     }
                 }
@@ -438,31 +453,53 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             if (row < g.M) {
                 uint32_t* dst = out_bits + static_cast<size_t>(row) * Fw + ntile * 4;
                 if ((Fw & 3) == 0) {
-                    *reinterpret_cast<uint4*>(dst) = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                    *reinterpret_cast<int4*>(dst) = make_int4(wb[0], wb[1], wb[2], wb[3]);
                 } else {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        if (ntile * 4 + j < Fw) dst[j] = wb[j];
+                        if (ntile * 4 + j < Fw) dst[j] = static_cast<uint32_t>(wb[j]);
                 }
             }
             continue;
         }
         float* out = MODE == kOutSplit ? ws_s1 + static_cast<size_t>(ksplit_id) * g.M * g.F : Y;
+        if (interior) {
+            // no predicate anywhere: nothing orders one store behind another
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
+                for (int q = 0; q < 4; ++q) {
+                    const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int row = m_base + i * 32 + q * 8 + (lane >> 5) * 4 + t;
-                    const size_t o = static_cast<size_t>(row) * g.F + f0 + (lane & 31);
+                    for (int t = 0; t < 4; ++t) {
+                        const int row = m_base + i * 32 + q * 8 + (lane >> 5) * 4 + t;
+                        const size_t o = static_cast<size_t>(row) * g.F + f0 + (lane & 31);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float s1 = acc[i][j][q * 4 + t];
-                        if (interior || (row < g.M && f0 + j * 32 + (lane & 31) < g.F)) {
+                        for (int j = 0; j < 4; ++j) {
+                            const float s1 = acc[i][j][q * 4 + t];
                             out[o + j * 32] = MODE == kOutSplit ? s1 : fmaf(dcol[j], s1, bcol[j] * sv[t]);
                             if (MODE == kOutYDebug) dbg_s1[o + j * 32] = static_cast<int>(s1);
+                        }
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int row = m_base + i * 32 + q * 8 + (lane >> 5) * 4 + t;
+                        const size_t o = static_cast<size_t>(row) * g.F + f0 + (lane & 31);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float s1 = acc[i][j][q * 4 + t];
+                            if (row < g.M && f0 + j * 32 + (lane & 31) < g.F) {
+                                out[o + j * 32] = MODE == kOutSplit ? s1 : fmaf(dcol[j], s1, bcol[j] * sv[t]);
+                                if (MODE == kOutYDebug) dbg_s1[o + j * 32] = static_cast<int>(s1);
+                            }
                         }
                     }
                 }
