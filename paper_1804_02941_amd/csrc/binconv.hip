@@ -477,7 +477,9 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const float s1 = acc[i][j][q * 4 + t];
-                            out[o + j * 32] = MODE == kOutSplit ? s1 : fmaf(dcol[j], s1, bcol[j] * sv[t]);
+                            // written once and not read again by this kernel: streaming stores
+                            __builtin_nontemporal_store(MODE == kOutSplit ? s1 : fmaf(dcol[j], s1, bcol[j] * sv[t]),
+                                                        out + o + j * 32);
                             if (MODE == kOutYDebug) dbg_s1[o + j * 32] = static_cast<int>(s1);
                         }
                     }
