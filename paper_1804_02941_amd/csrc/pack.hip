@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float*
     if (t0 + kItemsPerWave <= n_items) {
         const float* px = X + static_cast<size_t>(t0) * 64 + lane;
 #pragma unroll
-        for (int u = 0; u < kItemsPerWave; ++u) x[u] = px[u * 64];
+        for (int u = 0; u < kItemsPerWave; ++u) x[u] = __builtin_nontemporal_load(px + u * 64);
     }
     for (; t0 + kItemsPerWave <= n_items; t0 += step) {
         float nx[kItemsPerWave];
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float*
         if (more) {
             const float* px = X + static_cast<size_t>(t0 + step) * 64 + lane;
 #pragma unroll
-            for (int u = 0; u < kItemsPerWave; ++u) nx[u] = px[u * 64];
+            for (int u = 0; u < kItemsPerWave; ++u) nx[u] = __builtin_nontemporal_load(px + u * 64);
         }
         uint32_t word = 0;
 #pragma unroll

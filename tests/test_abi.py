@@ -62,3 +62,14 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert lib.dab_estimate_workspace_bytes(4, 100) == 0
     assert lib.dab_binfc_workspace_bytes(4, 100, 4) > 0
     assert lib.dab_binfc_workspace_bytes(0, 100, 4) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus 2 exits with a message and a non-zero status before touching a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert p.returncode == 2
+    assert "one GPU" in p.stderr
