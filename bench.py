@@ -49,10 +49,13 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
     ap.add_argument("--cpu-batch", type=int, default=256, help="images of the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--side-streams", type=int, default=3,
+    ap.add_argument("--side-streams", type=int, default=2,
                     help="HIP streams for the weight side (estimation + weight packing) of the layers; 0 = one stream")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of one captured HIP graph per step")
+    ap.add_argument("--wait-all", action="store_true",
+                    help="let the first product wait for the weight sides of all layers (default: each product waits "
+                         "only for its own layer's weights, so later layers' weight sides run beside earlier products)")
     ap.add_argument("--no-fused", action="store_true", help="skip the fused-chain measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
@@ -120,15 +123,15 @@ class Schedule:
     """One step of all layers over HIP streams of equal (default) priority.
 
     The weight side of a layer (estimation, weight packing) depends on no activation, so the
-    weight sides of all layers run first, spread over side streams (they are latency-bound
-    one-workgroup-per-filter kernels that share the chip well), while the current stream packs
-    the first layer's activations.  The current stream then waits for all of them and runs,
-    layer by layer, activation packing and the binary product with the chip to itself.  A step
-    forks from and joins back into the current stream, so steps never overlap, and the whole
-    step can be captured into one HIP graph.
+    weight sides run on side streams (longest first, spread by sort work) while the current
+    stream goes layer by layer through activation packing and the binary product; a product
+    waits for its own layer's weights only (an event per layer), so the weight sides of later
+    layers run beside the products of earlier ones.  A step forks from and joins back into the
+    current stream, so steps never overlap, and the whole step can be captured into one HIP
+    graph.
     """
 
-    def __init__(self, states, n_side, torch):
+    def __init__(self, states, n_side, torch, per_layer=True):
         self.torch = torch
         self.states = states
         self.side = [torch.cuda.Stream() for _ in range(n_side)]
@@ -143,6 +146,8 @@ class Schedule:
             a.sort()
         self.fork = torch.cuda.Event()
         self.ready = [torch.cuda.Event() for _ in self.side]
+        self.layer_ready = [torch.cuda.Event() for _ in states]
+        self.per_layer = per_layer
 
     def step(self, dab, events=None):
         torch, states = self.torch, self.states
@@ -157,10 +162,14 @@ class Schedule:
             with torch.cuda.stream(q):
                 for i in idxs:
                     weight_side(states[i], dab)
+                    if self.per_layer:
+                        self.layer_ready[i].record(q)
             done.record(q)
         for i, s in enumerate(states):
             activation_side(s, dab)
-            if i == 0:
+            if self.per_layer:
+                main.wait_event(self.layer_ready[i])
+            elif i == 0:
                 for done in self.ready:
                     main.wait_event(done)
             if events is not None:
@@ -168,6 +177,9 @@ class Schedule:
             product(s, dab)
             if events is not None:
                 events[i][1].record()
+        if self.per_layer:
+            for done in self.ready:
+                main.wait_event(done)
 
     def capture(self, dab):
         """The step as one HIP graph (kernel launches and stream dependencies only)."""
@@ -209,12 +221,12 @@ class FusedChain:
             with torch.cuda.stream(q):
                 for i in idxs:
                     weight_side(states[i], dab)
+                    sched.layer_ready[i].record(q)
             done.record(q)
         activation_side(states[0], dab)
-        for done in sched.ready:
-            main.wait_event(done)
         A = states[0].A
         for i, s in enumerate(states):
+            main.wait_event(sched.layer_ready[i])
             if events is not None:
                 events[i][0].record()
             if s.desc is None:
@@ -229,6 +241,8 @@ class FusedChain:
                     A = pooled
             if events is not None:
                 events[i][1].record()
+        for done in sched.ready:
+            main.wait_event(done)
 
     def capture(self, dab):
         torch = self.torch
@@ -321,7 +335,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    sched = Schedule(states, args.side_streams, torch)
+    sched = Schedule(states, args.side_streams, torch, per_layer=not args.wait_all)
     for _ in range(args.warmup):
         sched.step(dab)
     torch.cuda.synchronize()

@@ -88,7 +88,7 @@ def test_config3_full_chain():
         check_full_layer(L, x_nchw, W, tau, g, count=64)
     # the benchmark's multi-stream step (weight side on side streams) reproduces every layer bit for bit
     want = [s.Y.clone() for s in states]
-    sched = bench.Schedule(states, 3, torch)
+    sched = bench.Schedule(states, 2, torch)
     graph = None
     for it in range(7):
         if it == 3:
