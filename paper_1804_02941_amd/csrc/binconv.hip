@@ -318,17 +318,17 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             if (i == (lane >> 5)) mypix = pix;                         // lane l owns row l of the 64 for the row sums
         }
         // sA of this lane's row: box sum of the per-pixel sums over the filter window (the first T
-        // entries of the k-step table are the window's pixel offsets, times 16).  Sixteen loads at a
-        // time; the result is needed only after the reduction loop.
+        // entries of the k-step table are the window's pixel offsets, times 16).  Thirty-two loads at a
+        // time (a 5x5 window is one round trip); the result is needed only after the reduction loop.
         float rowsum = 0.0f;
         if (MODE != kOutSplit) {
             int sum = 0;
-            for (int t0 = 0; t0 < g.T; t0 += 16) {
-                int v[16];
+            for (int t0 = 0; t0 < g.T; t0 += 32) {
+                int v[32];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) v[u] = pixsum[mypix + (ktab[min(t0 + u, g.T - 1)] >> 4)];
+                for (int u = 0; u < 32; ++u) v[u] = pixsum[mypix + (ktab[min(t0 + u, g.T - 1)] >> 4)];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) sum += t0 + u < g.T ? v[u] : 0;
+                for (int u = 0; u < 32; ++u) sum += t0 + u < g.T ? v[u] : 0;
             }
             rowsum = static_cast<float>(sum);
         }
@@ -522,7 +522,15 @@ __global__ __launch_bounds__(256) void binconv_finish_kernel(const float* __rest
     const int m = static_cast<int>(i / F);
     const int f = static_cast<int>(i - static_cast<size_t>(m) * F);
     float s1 = 0.f;                                 // integer-valued, exact in any order
-    for (int k = 0; k < ksplit; ++k) s1 += ws_s1[static_cast<size_t>(k) * total + i];
+    int k = 0;
+    for (; k + 8 <= ksplit; k += 8) {               // eight partials in flight
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = ws_s1[static_cast<size_t>(k + u) * total + i];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s1 += v[u];
+    }
+    for (; k < ksplit; ++k) s1 += ws_s1[static_cast<size_t>(k) * total + i];
     const float sA = ws_sA[m];
     const float al = alpha[f], be = beta[f];
     Y[i] = fmaf(al - be, s1, be * sA);
@@ -548,7 +556,16 @@ __global__ __launch_bounds__(256) void binconv_finish_bits_kernel(const float* _
     bool bit = false;
     if (f < F) {
         float s1 = 0.f;
-        for (int k = 0; k < ksplit; ++k) s1 += ws_s1[static_cast<size_t>(k) * total + static_cast<size_t>(m) * F + f];
+        const float* p = ws_s1 + static_cast<size_t>(m) * F + f;
+        int k = 0;
+        for (; k + 8 <= ksplit; k += 8) {           // eight partials in flight
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[static_cast<size_t>(k + u) * total];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s1 += v[u];
+        }
+        for (; k < ksplit; ++k) s1 += p[static_cast<size_t>(k) * total];
         const float al = alpha[f], be = beta[f];
         bit = fmaf(al - be, s1, be * ws_sA[m]) >= (tau_out ? tau_out[f] : 0.0f);
     }
