@@ -157,6 +157,9 @@ class Schedule:
             return
         main = torch.cuda.current_stream()
         self.fork.record(main)
+        # the main stream's first kernel is enqueued (and captured) before the side work, so that a
+        # graph launch starts the main chain at once instead of behind the longest weight side
+        activation_side(states[0], dab)
         for q, idxs, done in zip(self.side, self.assign, self.ready):
             q.wait_event(self.fork)
             with torch.cuda.stream(q):
@@ -166,7 +169,8 @@ class Schedule:
                         self.layer_ready[i].record(q)
             done.record(q)
         for i, s in enumerate(states):
-            activation_side(s, dab)
+            if i > 0:
+                activation_side(s, dab)
             if self.per_layer:
                 main.wait_event(self.layer_ready[i])
             elif i == 0:
@@ -216,6 +220,7 @@ class FusedChain:
         torch, states, sched = self.torch, self.states, self.sched
         main = torch.cuda.current_stream()
         sched.fork.record(main)
+        activation_side(states[0], dab)
         for q, idxs, done in zip(sched.side, sched.assign, sched.ready):
             q.wait_event(sched.fork)
             with torch.cuda.stream(q):
@@ -223,7 +228,6 @@ class FusedChain:
                     weight_side(states[i], dab)
                     sched.layer_ready[i].record(q)
             done.record(q)
-        activation_side(states[0], dab)
         A = states[0].A
         for i, s in enumerate(states):
             main.wait_event(sched.layer_ready[i])
