@@ -208,8 +208,9 @@ int dab_binfc_bits(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, 
  * dab_pool_bits - max-pooling between two binarized layers, on the packed signs.  The sign of a
  * window's maximum is +1 iff any element's sign is +1 (one threshold per channel), so
  * sign(maxpool(y) - tau) is the bitwise OR of the window's packed words.  Windows lie inside the
- * image (no padding): Ho = (H - kh)/stride_h + 1, Wo likewise.  Sketch-A-Net (Section 5.1) pools
- * 3x3 with stride 2 after its second and fifth convolutions.
+ * image (no padding): Ho = (H - kh)/stride_h + 1, Wo likewise.  The Sketch-A-Net architecture that
+ * Section 5.1 trains (the network of the work it cites) pools 3x3 with stride 2 between binarized
+ * layers.
  *
  *   A_packed   uint32 [B][H][W][ceil(C/32)];  A_pooled uint32 [B][Ho][Wo][ceil(C/32)] out
  * Errors: a window larger than the image -> DAB_ERR_SHAPE.

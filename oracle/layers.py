@@ -170,8 +170,8 @@ def popcount_terms_1d(a_pm1, e01):
 
 # --------------------------------------------------------------------------
 # Between two binarized layers (Section 4: the next layer's inputs are again
-# +1 / -1; Section 5.1: Sketch-A-Net max-pools 3x3 / stride 2 after its second
-# and fifth convolutions).  Written as the definition: pool the real-valued
+# +1 / -1; the Sketch-A-Net architecture that Section 5.1 trains, taken from the
+# work it cites, max-pools 3x3 / stride 2 between binarized layers).  Written as the definition: pool the real-valued
 # output, then take the sign.
 # --------------------------------------------------------------------------
 
