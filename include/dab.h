@@ -116,6 +116,23 @@ size_t dab_estimate_workspace_bytes(int32_t F, int32_t n);
 int32_t dab_estimate_max_n(void);
 
 /*
+ * dab_estimate_sign_split - the baseline the paper compares with, in the estimator's output form.
+ * Section 4.1 notes that XNOR-Net / binary-weight networks are the special case that ignores the
+ * weight distribution: e = [w >= 0], alpha = mean |w| over the filter, beta = -alpha.  The outputs
+ * can be passed to dab_pack_weights and to the layer calls unchanged, which gives the comparison
+ * axis of the paper's tables on the same kernels.
+ *
+ *   W, alpha, beta, thr_val, thr_idx, alpha_is_upper   as for dab_estimate_alpha_beta
+ *   K              [F] int32 out: number of non-negative weights, 0 <= K <= n
+ * The lower group is the negative weights: thr_val is the largest negative weight and thr_idx the
+ * last index holding it (thr_val = -inf and thr_idx = 0 for a filter without negative weights);
+ * alpha_is_upper is 1.  n >= 1; any row length is supported.
+ */
+int dab_estimate_sign_split(const float* W, int32_t F, int32_t n,
+                            float* alpha, float* beta, int32_t* K,
+                            float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* stream);
+
+/*
  * dab_pack_weights - the mask e of Corollary 1 as bits, plus per-tap counts.
  * e[f,i] = 1 iff weight i of filter f belongs to the alpha group, decided from
  * the split descriptor of dab_estimate_alpha_beta (so the mask is defined by

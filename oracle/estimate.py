@@ -229,6 +229,34 @@ def xnor_reconstruction(w: np.ndarray) -> np.ndarray:
     return np.mean(np.abs(w)) * np.where(w >= 0, 1.0, -1.0)
 
 
+def estimate_sign_split(W: np.ndarray) -> dict:
+    """The XNOR-Net / binary-weight special case for every filter (Section 4.1: the distribution-
+    agnostic choice e = [w >= 0], alpha = mean |w|, beta = -alpha), in the same output form as
+    estimate_alpha_beta so that the same packing and layer code consumes it.
+
+    The lower group is the negative weights; K counts the non-negative ones (0 <= K <= n).  The
+    descriptor names the largest negative value and the last index holding it; a filter without
+    negative weights has thr_val = -inf (nothing is below it).
+    """
+    W = np.asarray(W)
+    F = W.shape[0]
+    W2 = W.reshape(F, -1).astype(np.float64)
+    n = W2.shape[1]
+    alpha = np.abs(W2).mean(axis=1)
+    e = (W2 >= 0).astype(np.uint8)
+    K = e.sum(axis=1).astype(np.int64)
+    thr_val = np.full(F, -np.inf)
+    thr_idx = np.zeros(F, dtype=np.int64)
+    for f in range(F):
+        neg = np.flatnonzero(W2[f] < 0)
+        if neg.size:
+            v = W2[f, neg].max()
+            thr_val[f] = v
+            thr_idx[f] = np.flatnonzero(W2[f] == v).max()
+    return dict(alpha=alpha, beta=-alpha, K=K, e=e.reshape(W.shape), thr_val=thr_val, thr_idx=thr_idx,
+                alpha_is_upper=np.ones(F, dtype=np.uint8), n=n)
+
+
 def all_partitions_of_sorted(w):
     """Helper for tests: every (lower, upper) split of the stable sorted order."""
     order = stable_order(w)

@@ -47,6 +47,8 @@ _SIGNATURES = {
     "dab_last_hip_error": (c_int, []),
     "dab_estimate_alpha_beta": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "dab_estimate_sign_split": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_void_p, c_void_p]),
     "dab_estimate_workspace_bytes": (c_size_t, [c_int32, c_int32]),
     "dab_estimate_max_n": (c_int32, []),
     "dab_pack_weights": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
@@ -145,6 +147,17 @@ def dab_estimate_alpha_beta(W, out=None, ws=None):
         _ptr(W, torch.float32, "W"), F, n, out["alpha"].data_ptr(), out["beta"].data_ptr(), out["K"].data_ptr(),
         out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(), out["alpha_is_upper"].data_ptr(),
         ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return out
+
+
+def dab_estimate_sign_split(W, out=None):
+    """W [F, n] fp32 -> the same dict as dab_estimate_alpha_beta for e = [w >= 0], alpha = mean|w|, beta = -alpha."""
+    F, n = W.shape
+    if out is None:
+        out = estimate_outputs(F, W.device)
+    _check("dab_estimate_sign_split", lib().dab_estimate_sign_split(
+        _ptr(W, torch.float32, "W"), F, n, out["alpha"].data_ptr(), out["beta"].data_ptr(), out["K"].data_ptr(),
+        out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(), out["alpha_is_upper"].data_ptr(), _stream()))
     return out
 
 

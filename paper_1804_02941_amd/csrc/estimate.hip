@@ -219,6 +219,59 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     }
 }
 
+// ---------------------------------------------------------------- sign split (XNOR-Net / BWN)
+// The distribution-agnostic special case of Section 4.1: e = [w >= 0], alpha = mean |w|, beta = -alpha.
+// One workgroup per filter, plain reductions; the outputs have the form of the estimator's, so the
+// same weight packing and layer kernels consume them.
+__global__ __launch_bounds__(256) void sign_split_kernel(const float* __restrict__ Wt, int n, float* __restrict__ alpha,
+                                                         float* __restrict__ beta, int32_t* __restrict__ Kout,
+                                                         float* __restrict__ thr_val, int32_t* __restrict__ thr_idx,
+                                                         uint8_t* __restrict__ alpha_is_upper) {
+    __shared__ double s_abs[4];
+    __shared__ int s_cnt[4];
+    __shared__ float s_max[4];
+    __shared__ int s_idx[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* row = Wt + static_cast<size_t>(blockIdx.x) * n;
+    double a = 0.0;
+    int cnt = 0, idx = 0;
+    float vmax = -INFINITY;                                   // largest negative value and its last index
+    for (int i = tid; i < n; i += 256) {
+        const float w = row[i];
+        a += fabs(static_cast<double>(w));
+        if (w >= 0.0f) {
+            ++cnt;
+        } else if (w > vmax || (w == vmax && i > idx)) {
+            vmax = w;
+            idx = i;
+        }
+    }
+    for (int d = 32; d >= 1; d >>= 1) {
+        a += __shfl_xor(a, d, 64);
+        cnt += __shfl_xor(cnt, d, 64);
+        const float ov = __shfl_xor(vmax, d, 64);
+        const int oi = __shfl_xor(idx, d, 64);
+        if (ov > vmax || (ov == vmax && oi > idx)) { vmax = ov; idx = oi; }
+    }
+    if (lane == 0) { s_abs[wave] = a; s_cnt[wave] = cnt; s_max[wave] = vmax; s_idx[wave] = idx; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) {
+            a += s_abs[w];
+            cnt += s_cnt[w];
+            if (s_max[w] > vmax || (s_max[w] == vmax && s_idx[w] > idx)) { vmax = s_max[w]; idx = s_idx[w]; }
+        }
+        const int f = blockIdx.x;
+        const float al = static_cast<float>(a / static_cast<double>(n));
+        alpha[f] = al;
+        beta[f] = -al;
+        Kout[f] = cnt;
+        thr_val[f] = vmax;
+        thr_idx[f] = vmax == -INFINITY ? 0 : idx;
+        alpha_is_upper[f] = 1;
+    }
+}
+
 constexpr int kEstimateMaxN = 1024 * 13;
 
 template <int THREADS, int ITEMS>
@@ -265,6 +318,19 @@ int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n, float* alpha, 
     if (n <= 1024 * 11) DAB_EST(1024, 11);
     DAB_EST(1024, 13);
 #undef DAB_EST
+}
+
+int dab_estimate_sign_split(const float* W, int32_t F, int32_t n, float* alpha, float* beta, int32_t* K,
+                            float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* stream) {
+    using namespace dab;
+    if (!W || !alpha || !beta || !K || !thr_val || !thr_idx || !alpha_is_upper) return DAB_ERR_NULL;
+    if (F < 1 || n < 1) return DAB_ERR_SHAPE;
+    if (misaligned(W, 4) || misaligned(alpha, 4) || misaligned(beta, 4) || misaligned(K, 4) ||
+        misaligned(thr_val, 4) || misaligned(thr_idx, 4))
+        return DAB_ERR_ALIGN;
+    hipLaunchKernelGGL(sign_split_kernel, dim3(F), dim3(256), 0, static_cast<hipStream_t>(stream), W, n, alpha, beta, K,
+                       thr_val, thr_idx, alpha_is_upper);
+    return launch_status();
 }
 
 }  // extern "C"

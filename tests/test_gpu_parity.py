@@ -263,3 +263,44 @@ def test_error_codes():
     with pytest.raises(TypeError):
         dab.dab_pack_activations(torch.zeros((1, 4)))        # CPU tensor: no fallback
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ the sign-split baseline (XNOR-Net / BWN)
+@pytest.mark.parametrize("n", [1, 2, 63, 600, 1600, 20000])
+def test_sign_split_estimate_and_layer(n):
+    rng = np.random.default_rng(n)
+    F = 37
+    W = weight_rows(rng, F, n, "dupes" if n == 600 else "gauss")
+    if n >= 63:
+        W[0] = np.abs(W[0]) + 0.5          # no negative weight
+        W[1] = -np.abs(W[1]) - 0.5         # no non-negative weight
+        W[2, ::3] = 0.0
+        W[2, 1::3] = -0.0
+    out = dab.dab_estimate_sign_split(gu.to_gpu(W))
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    ref = oest.estimate_sign_split(W)
+    assert np.array_equal(got["K"], ref["K"])
+    assert np.array_equal(got["thr_val"].astype(np.float64), ref["thr_val"])
+    assert np.array_equal(got["thr_idx"], ref["thr_idx"])
+    assert np.all(got["alpha_is_upper"] == 1)
+    assert np.allclose(got["alpha"], ref["alpha"], rtol=gu.AB_RTOL, atol=0) and np.array_equal(got["beta"], -got["alpha"])
+    if n < 2:
+        return                             # the packer and the layers need two weights
+    # the same packing kernel turns the descriptor into the sign mask
+    E, ecnt = dab.dab_pack_weights(gu.to_gpu(W.reshape(F, n, 1, 1)), out["thr_val"], out["thr_idx"], out["alpha_is_upper"])
+    torch.cuda.synchronize()
+    E_ref, ecnt_ref = opk.pack_weights(ref["e"].reshape(F, n, 1, 1))
+    assert np.array_equal(gu.u32(E), E_ref) and np.array_equal(gu.u32(ecnt), ecnt_ref)
+    # a fully-connected layer on these weights: y = alpha * (2 * #agreements - n), XNOR-Net's form
+    B = 9
+    x = rng.standard_normal((B, n)).astype(np.float32)
+    A = dab.dab_pack_activations(gu.to_gpu(x), dab.DAB_LAYOUT_NHWC, None).reshape(B, -1)
+    Y, s1 = dab.dab_binfc(A, E, out["alpha"], out["beta"], n, want_s1=True)
+    torch.cuda.synchronize()
+    a = olay.binarize_activations(x)
+    b = np.where(W >= 0, 1, -1)
+    agree = (a[:, None, :] == b[None, :, :]).sum(axis=2)
+    y_ref = got["alpha"].astype(np.float64)[None, :] * (2 * agree - n)
+    tol = gu.Y_RTOL * np.maximum(np.abs(y_ref), got["alpha"].astype(np.float64)[None, :] * n)
+    assert np.all(np.abs(Y.cpu().numpy() - y_ref) <= tol)

@@ -233,3 +233,49 @@ def test_batched_layer_and_errors():
         assert out["K"][f] == r["K"] and out["alpha"][f] == r["alpha"] and out["beta"][f] == r["beta"]
     with pytest.raises(ValueError):
         est.estimate_filter(np.array([1.0], dtype=np.float32))
+
+
+# ------------------------------------------------------------------ the sign-split baseline
+def test_sign_split_is_the_best_scaled_sign_vector_by_brute_force():
+    """XNOR-Net's choice (the special case Section 4.1 names): among all alpha * b with b in {+1,-1}^n the
+    least-squares optimum is b = sign(w), alpha = mean |w|.  Checked over every b for small n."""
+    import itertools
+    rng = np.random.default_rng(12)
+    for n in (3, 6, 9):
+        w = rng.standard_normal(n)
+        r = est.estimate_sign_split(w[None, :])
+        mine = np.sum((w - est.reconstruct(r["e"][0], r["alpha"][0], r["beta"][0])) ** 2)
+        best = min(np.sum((w - (np.dot(w, b) / n) * np.array(b)) ** 2)
+                   for b in itertools.product((1.0, -1.0), repeat=n))
+        assert mine == pytest.approx(best, rel=1e-12)
+        # and alpha is the minimiser for that sign vector
+        b = np.where(w >= 0, 1.0, -1.0)
+        for da in (-1e-3, 1e-3):
+            assert np.sum((w - (r["alpha"][0] + da) * b) ** 2) > mine
+
+
+def test_sign_split_descriptor_rebuilds_the_mask():
+    rng = np.random.default_rng(13)
+    rows = [rng.standard_normal(40), np.abs(rng.standard_normal(40)), -np.abs(rng.standard_normal(40)) - 0.1,
+            np.array([0.0, -0.0, 1.0, -1.0, -1.0, 2.0, -3.0, -1.0]),            # zeros count as +, tied largest negative
+            np.round(rng.standard_normal(64) * 2) / 2]
+    for w in rows:
+        r = est.estimate_sign_split(w[None, :].astype(np.float32))
+        e = est.mask_from_descriptor(w.astype(np.float32), r["thr_val"][0], r["thr_idx"][0], r["alpha_is_upper"][0])
+        assert np.array_equal(e, (w >= 0).astype(np.uint8))
+        assert r["K"][0] == int((w >= 0).sum())
+        assert r["alpha"][0] == pytest.approx(np.abs(w.astype(np.float32).astype(np.float64)).mean(), rel=1e-15)
+        assert r["beta"][0] == -r["alpha"][0]
+
+
+def test_distribution_aware_error_never_exceeds_the_sign_split_error():
+    """Section 4.1: the optimal (alpha, beta, e) can only improve on the distribution-agnostic choice."""
+    rng = np.random.default_rng(14)
+    for _ in range(20):
+        w = (rng.standard_normal(200) * rng.uniform(0.01, 1) + rng.uniform(-0.5, 0.5)).astype(np.float32)
+        d = est.estimate_filter(w)
+        x = est.estimate_sign_split(w[None, :])
+        w64 = w.astype(np.float64)
+        e_dab = np.sum((w64 - est.reconstruct(d["e"], d["alpha"], d["beta"])) ** 2)
+        e_xnor = np.sum((w64 - est.reconstruct(x["e"][0], x["alpha"][0], x["beta"][0])) ** 2)
+        assert e_dab <= e_xnor * (1 + 1e-12)
