@@ -20,8 +20,6 @@ SOURCES = ("api.hip", "binconv.hip", "pack.hip", "estimate.hip")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fno-gpu-rdc", "-ffp-contract=off",
-    # the split-reduction path adds exact integer-valued partial sums with hardware fp32 atomics
-    "-munsafe-fp-atomics",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
