@@ -61,7 +61,8 @@ struct MfmaGeom {
     int T, npix, plane;            // taps, padded pixels, bytes of one 32-channel plane of A4
     int act_p, act_w, act_wt;      // prepare: pixels x words of a transpose tile (product 256), word tiles
     int sum_shift;                 // prepare: log2 of the lanes that share one pixel's row sum
-    FastDiv d_HoWo, d_Wo, d_Wp, d_HpWp, d_nk, d_mtiles, d_ksplit, d_T, d_kw, d_act_wt, d_Cw;
+    int n_fblocks;                 // 32-filter column blocks (small products)
+    FastDiv d_HoWo, d_Wo, d_Wp, d_HpWp, d_nk, d_mtiles, d_ksplit, d_T, d_kw, d_act_wt, d_Cw, d_fblocks;
     // block ranges of the prepare kernel
     unsigned blk_act, blk_wgt, blk_sum, blk_tab, blk_sa;
 };
@@ -510,6 +511,115 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
     }
 }
 
+// ---------------------------------------------------------------- small products
+// Layers with a few hundred 32x32 output blocks at most (conv6 and fc7 of the Sketch-A-Net trunk,
+// the late stages of a ResNet at small batch) are latency problems: the persistent kernel above
+// would run on a handful of compute units or need a split reduction with partial sums in memory.
+// Here one workgroup owns one 32-pixel x 32-filter block; its WAVES wavefronts take consecutive
+// shares of the reduction, each reading both fragments straight from global memory (L2) through
+// two eight-step register sets, and add their integer partial sums (exact in fp32) through LDS.
+// sA comes from the prepare kernel's per-pixel pass.
+constexpr int kSmallDepth = 8;
+
+template <int MODE, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
+    const MfmaGeom g, const char* __restrict__ A4, const uint4* __restrict__ E4, const float* __restrict__ alpha,
+    const float* __restrict__ beta, float* __restrict__ Y, int32_t* __restrict__ dbg_s1, const float* __restrict__ sA,
+    const int32_t* __restrict__ ktab, const float* __restrict__ tau_out, uint32_t* __restrict__ out_bits) {
+    __shared__ float red[WAVES][16][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int mb = fdiv(blockIdx.x, g.d_fblocks);
+    const int fb = blockIdx.x - mb * g.n_fblocks;                   // neighbouring workgroups share the pixel rows
+    const uint4* Eb = E4 + static_cast<size_t>(fb >> 2) * g.nk * 256 + (fb & 3) * 64 + lane;
+    const __amdgpu_buffer_rsrc_t a4rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(A4), 0, 2 * g.KB * g.plane, 0x00020000);
+    int pixoff;
+    {
+        const int m = min(mb * 32 + (lane & 31), g.M - 1);
+        const int b = fdiv(m, g.d_HoWo);
+        const int r = m - b * g.HoWo;
+        const int oy = fdiv(r, g.d_Wo);
+        const int ox = r - oy * g.Wo;
+        pixoff = ((b * g.Hp + oy * g.sh) * g.Wp + ox * g.sw) * 16 + (lane >> 5) * g.plane;
+    }
+    // column constants of this thread's outputs (every element it finishes has column lane % 32)
+    const int f = min(fb * 32 + (lane & 31), g.F - 1);
+    const float al = alpha[f], be = beta[f];
+    const float tcol = (MODE == kOutBits && tau_out) ? tau_out[f] : 0.0f;
+
+    auto load_a = [&](int poff) -> v4i {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(a4rsrc, pixoff, poff, 0);
+        return v4i{static_cast<int>(v[0]), static_cast<int>(v[1]), static_cast<int>(v[2]), static_cast<int>(v[3])};
+    };
+    v16f acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    // This wavefront's steps [k0, k1), taken in groups of kSmallDepth with two register sets: the
+    // loads of the next group are issued back to back before the products of the current one.
+    // Consecutive steps are neighbouring taps, i.e. neighbouring 16-byte pieces of the same cache
+    // lines, so a burst finds the lines its first load brought in (issued one per step instead,
+    // the eight wavefronts evict each other's lines and nearly every load goes to L2).  Fetches
+    // past k1 repeat its last step.
+    const int per = (g.nk + WAVES - 1) / WAVES;
+    const int k0 = min(wave * per, g.nk), k1 = min(k0 + per, g.nk);
+    const int klast = max(k1 - 1, 0);
+    v4i aq[2][kSmallDepth];
+    uint4 bq[2][kSmallDepth];
+    auto fetch = [&](int set, int first) {
+#pragma unroll
+        for (int d = 0; d < kSmallDepth; ++d) aq[set][d] = load_a(ktab[min(first + d, klast)]);
+#pragma unroll
+        for (int d = 0; d < kSmallDepth; ++d) bq[set][d] = Eb[static_cast<size_t>(min(first + d, klast)) * 256];
+    };
+    auto multiply = [&](int set, int first) {
+#pragma unroll
+        for (int d = 0; d < kSmallDepth; ++d) {
+            if (first + d < k1) {
+                const uint4 bu = bq[set][d];
+                const v4i bv = {static_cast<int>(bu.x), static_cast<int>(bu.y), static_cast<int>(bu.z),
+                                static_cast<int>(bu.w)};
+                acc = mfma_fp4(aq[set][d], bv, acc);
+            }
+        }
+    };
+    fetch(0, k0);
+    for (int st = k0; st < k1; st += 2 * kSmallDepth) {
+        fetch(1, st + kSmallDepth);
+        multiply(0, st);
+        fetch(0, st + 2 * kSmallDepth);
+        multiply(1, st + kSmallDepth);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
+    __syncthreads();
+
+    // register v of lane l is row (v/4)*8 + (l/32)*4 + v%4 of the block, column l%32; wavefront w
+    // finishes registers w, w + WAVES, ...
+    const bool fvalid = fb * 32 + (lane & 31) < g.F;
+    const float dcol = al - be;
+    const int Fw = (g.F + 31) >> 5;
+#pragma unroll
+    for (int v = wave; v < 16; v += WAVES) {
+        const int rl = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        const int row = mb * 32 + rl;
+        const float sv = sA[min(row, g.M - 1)];
+        float s1 = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) s1 += red[w][v][lane];
+        const float y = fmaf(dcol, s1, be * sv);
+        if (MODE == kOutBits) {
+            const unsigned long long mask = __ballot(fvalid && y >= tcol);
+            const uint32_t word = static_cast<uint32_t>(lane < 32 ? mask : mask >> 32);
+            if ((lane & 31) == 0 && row < g.M) out_bits[static_cast<size_t>(row) * Fw + fb] = word;
+        } else if (row < g.M && fvalid) {
+            const size_t o = static_cast<size_t>(row) * g.F + fb * 32 + (lane & 31);
+            Y[o] = y;
+            if (MODE == kOutYDebug) dbg_s1[o] = static_cast<int>(s1);
+        }
+    }
+}
+
 // ---------------------------------------------------------------- finish (split launches)
 __global__ __launch_bounds__(256) void binconv_finish_kernel(const float* __restrict__ ws_s1,
                                                              const float* __restrict__ ws_sA,
@@ -580,7 +690,7 @@ __global__ __launch_bounds__(256) void binconv_finish_bits_kernel(const float* _
 struct MfmaPlan {
     MfmaGeom g;
     int waves;
-    bool split;
+    bool split, small;
     size_t a4_bytes, e4_bytes, sa_bytes, s1_bytes, ws_bytes, lds_bytes;
     unsigned grid;
 };
@@ -625,6 +735,16 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     g.ksplit = ceil_div(g.nk, g.split_steps);
     pl->split = g.ksplit > 1;
     if (pl->split) pl->waves = 4;
+    // A layer that would need the split and has at most 512 output blocks of 32 x 32 runs one
+    // workgroup per block over the whole reduction instead (no partial sums in memory, no finish kernel).
+    g.n_fblocks = ceil_div(d.F, 32);
+    g.d_fblocks = make_fastdiv(g.n_fblocks);
+    pl->small = tiles256 * 2 <= kNumCU && 1ll * ceil_div(g.M, 32) * g.n_fblocks <= 512;
+    if (pl->small) {
+        pl->split = false;
+        g.ksplit = 1;
+        g.split_steps = g.nk;
+    }
     const int span = pl->split ? g.split_steps : g.nk;
     const int nchunks = ceil_div(span, kMaxChunk);
     g.kchunk = ceil_div(ceil_div(span, nchunks), kPrefetch) * kPrefetch;
@@ -660,7 +780,7 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     g.blk_wgt = static_cast<unsigned>((1ll * g.n_ntiles * g.nk * 256 + 255) / 256);
     g.blk_sum = static_cast<unsigned>((1ll * g.npix * (1 << g.sum_shift) + 255) / 256);
     g.blk_tab = static_cast<unsigned>((g.nk + kTabPad + 255) / 256);
-    g.blk_sa = pl->split ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
+    g.blk_sa = (pl->split || pl->small) ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
     return DAB_OK;
 }
 
@@ -699,6 +819,24 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
                        st, g, A, E, reinterpret_cast<uint4*>(a4), e4, pixsum, ktab, sa);
     if (int rc = launch_status()) return rc;
 
+    if (pl.small) {
+        const unsigned blocks = static_cast<unsigned>(ceil_div(g.M, 32) * g.n_fblocks);
+        auto launch = [&](auto kernel, int waves) {
+            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64 * waves), 0, st, g, a4, e4, alpha, beta, Y, dbg_s1, sa, ktab,
+                               tau_out, out_bits);
+        };
+        // enough wavefronts per block that each keeps a few steps of the reduction
+        if (g.nk >= 32) {
+            if (!Y) launch(binconv_small_kernel<kOutBits, 8>, 8);
+            else if (dbg_s1) launch(binconv_small_kernel<kOutYDebug, 8>, 8);
+            else launch(binconv_small_kernel<kOutY, 8>, 8);
+        } else {
+            if (!Y) launch(binconv_small_kernel<kOutBits, 2>, 2);
+            else if (dbg_s1) launch(binconv_small_kernel<kOutYDebug, 2>, 2);
+            else launch(binconv_small_kernel<kOutY, 2>, 2);
+        }
+        return launch_status();
+    }
     if (pl.split) {
         if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)) return rc;
         const size_t total = static_cast<size_t>(g.M) * d.F;
