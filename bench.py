@@ -124,14 +124,14 @@ class Schedule:
 
     The weight side of a layer (estimation, weight packing) depends on no activation, so the
     weight sides run on side streams (longest first, spread by sort work) while the current
-    stream goes layer by layer through activation packing and the binary product; a product
-    waits for its own layer's weights only (an event per layer), so the weight sides of later
-    layers run beside the products of earlier ones.  A step forks from and joins back into the
+    stream packs the activations of all layers and then goes layer by layer through the binary
+    products; a product waits for its own layer's weights only (an event per layer), so the
+    weight sides of later layers run beside the products of earlier ones.  A step forks from and joins back into the
     current stream, so steps never overlap, and the whole step can be captured into one HIP
     graph.
     """
 
-    def __init__(self, states, n_side, torch, per_layer=True):
+    def __init__(self, states, n_side, torch, per_layer=True, acts_first=True):
         self.torch = torch
         self.states = states
         self.side = [torch.cuda.Stream() for _ in range(n_side)]
@@ -148,6 +148,7 @@ class Schedule:
         self.ready = [torch.cuda.Event() for _ in self.side]
         self.layer_ready = [torch.cuda.Event() for _ in states]
         self.per_layer = per_layer
+        self.acts_first = acts_first
 
     def step(self, dab, events=None):
         torch, states = self.torch, self.states
@@ -160,6 +161,7 @@ class Schedule:
         # the main stream's first kernel is enqueued (and captured) before the side work, so that a
         # graph launch starts the main chain at once instead of behind the longest weight side
         activation_side(states[0], dab)
+        first = 1 if self.acts_first else len(states)
         for q, idxs, done in zip(self.side, self.assign, self.ready):
             q.wait_event(self.fork)
             with torch.cuda.stream(q):
@@ -168,8 +170,13 @@ class Schedule:
                     if self.per_layer:
                         self.layer_ready[i].record(q)
             done.record(q)
+        # every layer's input is resident when the step starts, so all activations are packed while
+        # the weight sides are still estimating (memory-bound work beside LDS-bound work); the
+        # products then follow each other without a packing kernel between them
+        for s in states[first:]:
+            activation_side(s, dab)
         for i, s in enumerate(states):
-            if i > 0:
+            if 0 < i < first:
                 activation_side(s, dab)
             if self.per_layer:
                 main.wait_event(self.layer_ready[i])
