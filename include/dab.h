@@ -235,6 +235,57 @@ int dab_binfc_bits(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, 
 int dab_pool_bits(const uint32_t* A_packed, int32_t B, int32_t C, int32_t H, int32_t W, int32_t kh, int32_t kw,
                   int32_t stride_h, int32_t stride_w, uint32_t* A_pooled, void* stream);
 
+/*
+ * Weight-side steps of one training iteration (Algorithm 2).  The real weights are mean-centred
+ * and clamped, every filter is binarized (dab_estimate_alpha_beta on the result), W~ is formed for
+ * the forward and backward pass, and the gradient with respect to W~ is turned into the gradient
+ * applied to the real weights (Theorem 4).  All buffers are device memory; W is [F][C][kh][kw]
+ * fp32, seen as F rows of n = C*kh*kw.
+ */
+typedef enum {
+    DAB_CENTER_FILTER = 0,   /* subtract the mean of the filter's n weights                    */
+    DAB_CENTER_CHANNEL = 1   /* subtract, per filter and tap, the mean over the C channels     */
+} dab_center_axis;
+
+/*
+ * dab_mean_center_clamp - MeanCenter, then Clamp(lo, hi) (Algorithm 2 lists them in this order
+ * and does not name the axis of the mean; both conventions above are provided).  The mean is
+ * accumulated in double, the centred value is rounded once to fp32.
+ *
+ *   W      [F][C][T] fp32 in (T = kh*kw);  W_out the same shape, may be W itself (in place)
+ * Errors: lo > hi or a non-positive size -> DAB_ERR_SHAPE; another axis -> DAB_ERR_UNSUPPORTED.
+ */
+int dab_mean_center_clamp(const float* W, int32_t F, int32_t C, int32_t T, int32_t axis, float lo, float hi,
+                          float* W_out, void* stream);
+
+/*
+ * dab_binarized_weights - W~ = alpha e + beta (1 - e) as fp32 (the last line of Algorithm 2's
+ * binarization loop), with e taken from the split descriptor exactly as dab_pack_weights takes it.
+ *
+ *   W, alpha, beta, thr_val, thr_idx, alpha_is_upper   as for dab_estimate_alpha_beta
+ *   W_tilde  [F][n] fp32 out, every element alpha[f] or beta[f]; must not overlap W
+ */
+int dab_binarized_weights(const float* W, int32_t F, int32_t n, const float* alpha, const float* beta,
+                          const float* thr_val, const int32_t* thr_idx, const uint8_t* alpha_is_upper,
+                          float* W_tilde, void* stream);
+
+/*
+ * dab_weight_gradient - Theorem 4 (derived in the appendix): G~ = G~1 + G~2, element-wise.  With e
+ * the mask of the split descriptor, K its number of ones, T_k = W o e and R = W - T_k,
+ *     G~_i = e_i/K + (||T_k||_1 / K) T_k^i [|W_i| <= 1] + (1-e_i)/(n-K) + (||R||_1 / (n-K)) R^i [|W_i| <= 1]
+ * (the theorem's sgn(T_k) and sgn(W - T_k) are the masks e and 1 - e, as its derivation
+ * substitutes them; STE passes the value where |W_i| <= 1).  With an upstream gradient dC/dW~ the
+ * output is its element-wise product with G~, the gradient applied to the real weights.
+ *
+ *   W         [F][n] fp32, the mean-centred, clamped weights that were binarized (n >= 2)
+ *   upstream  [F][n] fp32 or NULL
+ *   G_out     [F][n] fp32 out; must not overlap W
+ * K and the two l1 norms are recomputed from W and the descriptor (double accumulation).  A
+ * descriptor whose mask is empty or full is outside the theorem; that group's terms are 0.
+ */
+int dab_weight_gradient(const float* W, int32_t F, int32_t n, const float* thr_val, const int32_t* thr_idx,
+                        const uint8_t* alpha_is_upper, const float* upstream, float* G_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,7 +11,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import c_char_p, c_int, c_int32, c_size_t, c_void_p
+from ctypes import c_char_p, c_float, c_int, c_int32, c_size_t, c_void_p
 
 import torch
 
@@ -19,6 +19,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libdab_hip.so")
 
 DAB_OK = 0
+DAB_ERR_NULL, DAB_ERR_SHAPE, DAB_ERR_ALIGN, DAB_ERR_WORKSPACE, DAB_ERR_UNSUPPORTED, DAB_ERR_HIP = 1, 2, 3, 4, 5, 6
 DAB_LAYOUT_NHWC = 0
 DAB_LAYOUT_NCHW = 1
 
@@ -67,6 +68,12 @@ _SIGNATURES = {
                                c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_pool_bits": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32,
                               c_void_p, c_void_p]),
+    "dab_mean_center_clamp": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_float, c_float, c_void_p,
+                                      c_void_p]),
+    "dab_binarized_weights": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_void_p, c_void_p]),
+    "dab_weight_gradient": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                    c_void_p]),
 }
 
 _lib = None
@@ -268,3 +275,39 @@ def dab_pool_bits(A_packed, C, kh, kw, stride_h, stride_w, out=None):
         _ptr(A_packed, torch.int32, "A_packed"), B, C, H, W, kh, kw, stride_h, stride_w,
         _ptr(A_pooled, torch.int32, "A_pooled"), _stream()))
     return A_pooled
+
+
+DAB_CENTER_FILTER, DAB_CENTER_CHANNEL = 0, 1
+
+
+def dab_mean_center_clamp(W, axis=DAB_CENTER_FILTER, lo=-1.0, hi=1.0, out=None):
+    """MeanCenter + Clamp of W[F,C,kh,kw] (fp32); out may be W itself."""
+    F, C = W.shape[0], W.shape[1]
+    T = W.shape[2] * W.shape[3]
+    W_out = out if out is not None else torch.empty_like(W)
+    _check("dab_mean_center_clamp", lib().dab_mean_center_clamp(
+        _ptr(W, torch.float32, "W"), F, C, T, axis, lo, hi, _ptr(W_out, torch.float32, "W_out"), _stream()))
+    return W_out
+
+
+def dab_binarized_weights(W, alpha, beta, thr_val, thr_idx, alpha_is_upper, out=None):
+    """W~ = alpha e + beta (1 - e) as fp32 [F,n] from W[F,n] and the estimator's outputs."""
+    F, n = W.shape
+    Wt = out if out is not None else torch.empty_like(W)
+    _check("dab_binarized_weights", lib().dab_binarized_weights(
+        _ptr(W, torch.float32, "W"), F, n, _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"),
+        _ptr(thr_val, torch.float32, "thr_val"), _ptr(thr_idx, torch.int32, "thr_idx"),
+        _ptr(alpha_is_upper, torch.uint8, "alpha_is_upper"), _ptr(Wt, torch.float32, "W_tilde"), _stream()))
+    return Wt
+
+
+def dab_weight_gradient(W, thr_val, thr_idx, alpha_is_upper, upstream=None, out=None):
+    """Theorem 4's element-wise factor G~ for W[F,n] (times `upstream` when given)."""
+    F, n = W.shape
+    G = out if out is not None else torch.empty_like(W)
+    up = None if upstream is None else _ptr(upstream, torch.float32, "upstream")
+    _check("dab_weight_gradient", lib().dab_weight_gradient(
+        _ptr(W, torch.float32, "W"), F, n, _ptr(thr_val, torch.float32, "thr_val"),
+        _ptr(thr_idx, torch.int32, "thr_idx"), _ptr(alpha_is_upper, torch.uint8, "alpha_is_upper"), up,
+        _ptr(G, torch.float32, "G_out"), _stream()))
+    return G
