@@ -31,6 +31,9 @@ the design notes of the repository):
   index), not by sgn() of the kept values, which would drop kept zeros.
 * T, the sum of all weights, is taken as the last prefix sum P_n, so that
   T - P_n is exactly zero.
+* The restricted search (``estimate_filter_bounded``): Section 5 only remarks
+  that K should change by slight amounts between iterations; the window is
+  taken on the split position (see ``split_window``).
 """
 from __future__ import annotations
 
@@ -86,11 +89,40 @@ def estimate_filter(w: np.ndarray) -> dict:
     thr_idx         original index of that element: i is in the lower group iff
                     w_i < thr_val or (w_i == thr_val and i <= thr_idx)
     """
+    return _estimate_in_window(w, 1, np.asarray(w).size - 1)
+
+
+def split_window(n: int, K_prev: int, alpha_is_upper_prev: int, max_change: int):
+    """Splits allowed when the previous iteration's split may move by at most max_change.
+
+    Section 5 remarks that for natural images K must be kept from changing by
+    more than slight amounts, and gives no rule.  Reading taken here: the
+    partition may move by at most max_change elements, i.e. the size i of the
+    lower group stays within max_change of its previous value (i_prev = K_prev
+    if the alpha group was the lower one, n - K_prev otherwise), inside 1 .. n-1.
+    K itself then changes by at most max_change as long as the same group stays
+    the alpha group.
+    """
+    i_prev = n - int(K_prev) if alpha_is_upper_prev else int(K_prev)
+    i_prev = min(max(i_prev, 1), n - 1)
+    d = min(max(int(max_change), 0), n)
+    return max(1, i_prev - d), min(n - 1, i_prev + d)
+
+
+def estimate_filter_bounded(w: np.ndarray, K_prev: int, alpha_is_upper_prev: int, max_change: int) -> dict:
+    """``estimate_filter`` with the split restricted to ``split_window``: the best D inside the
+    window (ties towards the larger i, as everywhere), labelled by magnitude as usual."""
+    n = np.asarray(w).size
+    lo, hi = split_window(n, K_prev, alpha_is_upper_prev, max_change)
+    return _estimate_in_window(w, lo, hi)
+
+
+def _estimate_in_window(w: np.ndarray, i_lo: int, i_hi: int) -> dict:
     w = np.asarray(w, dtype=np.float64).ravel()
     n = w.size
     order, P, D = split_scores(w)
-    maxD = D.max()
-    i_star = int(np.flatnonzero(D == maxD)[-1]) + 1
+    maxD = D[i_lo - 1:i_hi].max()
+    i_star = int(np.flatnonzero(D[i_lo - 1:i_hi] == maxD)[-1]) + i_lo
     T = P[n - 1]
     mu_lower = P[i_star - 1] / i_star
     mu_upper = (T - P[i_star - 1]) / (n - i_star)

@@ -279,3 +279,65 @@ def test_distribution_aware_error_never_exceeds_the_sign_split_error():
         e_dab = np.sum((w64 - est.reconstruct(d["e"], d["alpha"], d["beta"])) ** 2)
         e_xnor = np.sum((w64 - est.reconstruct(x["e"][0], x["alpha"][0], x["beta"][0])) ** 2)
         assert e_dab <= e_xnor * (1 + 1e-12)
+
+
+# ------------------------------------------------------------------ restricted search (bounded change of K)
+def _error_of_split(w, i):
+    """||W - W~||^2 of the split 'i smallest | rest' with the two group means, from the definition."""
+    ws = np.sort(np.asarray(w, dtype=np.float64), kind="stable")
+    lo, hi = ws[:i], ws[i:]
+    return float(((lo - lo.mean()) ** 2).sum() + ((hi - hi.mean()) ** 2).sum())
+
+
+def test_bounded_search_with_a_wide_window_is_the_plain_estimate():
+    rng = np.random.default_rng(31)
+    for n in (2, 3, 17, 200):
+        w = rng.standard_normal(n)
+        full = est.estimate_filter(w)
+        for kp, up in ((1, 0), (n - 1, 1), (n // 2 + 1, 0)):
+            got = est.estimate_filter_bounded(w, min(kp, n - 1), up, n)
+            assert got["i_star"] == full["i_star"] and got["alpha"] == full["alpha"] and got["K"] == full["K"]
+            assert np.array_equal(got["e"], full["e"])
+
+
+def test_bounded_search_minimises_the_error_inside_the_window():
+    rng = np.random.default_rng(32)
+    for trial in range(30):
+        n = int(rng.integers(5, 80))
+        w = rng.standard_normal(n) + (rng.random(n) < 0.3) * 2.0
+        K_prev = int(rng.integers(1, n))
+        up = int(rng.integers(0, 2))
+        d = int(rng.integers(0, 6))
+        i_prev = n - K_prev if up else K_prev
+        lo, hi = max(1, i_prev - d), min(n - 1, i_prev + d)
+        assert est.split_window(n, K_prev, up, d) == (lo, hi)
+        errs = {i: _error_of_split(w, i) for i in range(lo, hi + 1)}
+        best = min(errs, key=lambda i: (errs[i], -i))
+        got = est.estimate_filter_bounded(w, K_prev, up, d)
+        assert lo <= got["i_star"] <= hi
+        assert errs[got["i_star"]] <= errs[best] * (1 + 1e-12) + 1e-15
+        # no split inside the window does better; one outside may
+        full = est.estimate_filter(w)
+        assert _error_of_split(w, full["i_star"]) <= errs[got["i_star"]] + 1e-12
+        # means and labelling follow the chosen partition
+        a, b = est.group_means(w, got["e"].astype(np.float64))
+        assert got["alpha"] == pytest.approx(a, rel=1e-13) and got["beta"] == pytest.approx(b, rel=1e-13)
+        assert abs(got["alpha"]) >= abs(got["beta"])
+        assert got["K"] == int(got["e"].sum())
+
+
+def test_bounded_search_with_no_room_keeps_the_previous_partition():
+    rng = np.random.default_rng(33)
+    w = rng.standard_normal(40)
+    for K_prev, up in ((7, 0), (7, 1), (39, 0), (1, 1)):
+        got = est.estimate_filter_bounded(w, K_prev, up, 0)
+        i_prev = 40 - K_prev if up else K_prev
+        assert got["i_star"] == i_prev
+        order = np.argsort(w, kind="stable")
+        low = np.zeros(40, dtype=bool)
+        low[order[:i_prev]] = True
+        assert np.array_equal(est.lower_group_from_descriptor(w, got["thr_val"], got["thr_idx"]), low)
+    # a previous K outside 1 .. n-1 is pulled back inside
+    assert est.split_window(40, 0, 0, 3) == (1, 4)
+    assert est.split_window(40, 55, 0, 3) == (36, 39)
+    assert est.split_window(40, 5, 1, 10 ** 9) == (1, 39)
