@@ -116,6 +116,25 @@ size_t dab_estimate_workspace_bytes(int32_t F, int32_t n);
 int32_t dab_estimate_max_n(void);
 
 /*
+ * dab_estimate_alpha_beta_bounded - the same estimate with the split kept near the previous
+ * iteration's.  Section 5 remarks that on natural images the algorithm needs K restricted to
+ * change by slight amounts only and gives no rule; here the partition may move by at most
+ * max_change elements: with i_prev the previous size of the lower group (K_prev if the alpha group
+ * was the lower one, n - K_prev otherwise, pulled into 1 .. n-1), the best split is searched over
+ * max(1, i_prev - max_change) .. min(n-1, i_prev + max_change) only.  Ties, labelling and outputs
+ * are as above; max_change >= n gives dab_estimate_alpha_beta's result, max_change = 0 keeps the
+ * previous partition sizes and refreshes alpha, beta and the descriptor for the new weights.
+ *
+ *   K_prev              [F] int32, alpha_is_upper_prev [F] uint8: the previous call's outputs; they
+ *                       may be the very buffers passed as K and alpha_is_upper
+ * Errors as above; max_change < 0 -> DAB_ERR_SHAPE.
+ */
+int dab_estimate_alpha_beta_bounded(const float* W, int32_t F, int32_t n, const int32_t* K_prev,
+                                    const uint8_t* alpha_is_upper_prev, int32_t max_change, float* alpha,
+                                    float* beta, int32_t* K, float* thr_val, int32_t* thr_idx,
+                                    uint8_t* alpha_is_upper, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * dab_estimate_sign_split - the baseline the paper compares with, in the estimator's output form.
  * Section 4.1 notes that XNOR-Net / binary-weight networks are the special case that ignores the
  * weight distribution: e = [w >= 0], alpha = mean |w| over the filter, beta = -alpha.  The outputs

@@ -56,9 +56,10 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b) {   // a be
 template <int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restrict__ Wt, int n,
                                                            float* __restrict__ alpha, float* __restrict__ beta,
-                                                           int32_t* __restrict__ Kout, float* __restrict__ thr_val,
-                                                           int32_t* __restrict__ thr_idx,
-                                                           uint8_t* __restrict__ alpha_is_upper) {
+                                                           int32_t* Kout, float* __restrict__ thr_val,
+                                                           int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
+                                                           const int32_t* K_prev, const uint8_t* upper_prev,
+                                                           int max_change) {
     static_assert(ITEMS >= 1 && ITEMS <= 15, "a digit counter has 4 bits");
     constexpr int NW = THREADS / 64;
     constexpr int N = THREADS * ITEMS;
@@ -149,14 +150,24 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     __syncthreads();
     const double T = total_s;
 
-    // ---- D_i over this thread's positions; split i = position + 1, i in 1 .. n-1
+    // ---- D_i over this thread's positions; split i = position + 1, i in 1 .. n-1, or in the
+    // window around the previous split when one is given (read before any output is written, so
+    // the previous outputs may be the buffers this call overwrites)
+    int wlo = 1, whi = n - 1;
+    if (K_prev) {
+        int ip = upper_prev[blockIdx.x] ? n - K_prev[blockIdx.x] : K_prev[blockIdx.x];
+        ip = min(max(ip, 1), n - 1);
+        const int d = min(max(max_change, 0), n);
+        wlo = max(1, ip - d);
+        whi = min(n - 1, ip + d);
+    }
     Best best{-1.0, 1.0, 0.0, 0};
     double P = base;
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         P += x[j];
         const int i = lo + j + 1;
-        if (lo + j < hi && i < n) {
+        if (lo + j < hi && i >= wlo && i <= whi) {
             const double rest = T - P;
             const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
             const Best cand{P * P * fr + rest * rest * fi, fi * fr, P, i};
@@ -276,10 +287,34 @@ constexpr int kEstimateMaxN = 1024 * 13;
 
 template <int THREADS, int ITEMS>
 static int launch_estimate(const float* W, int F, int n, float* alpha, float* beta, int32_t* K, float* thr_val,
-                           int32_t* thr_idx, uint8_t* aiu, hipStream_t st) {
+                           int32_t* thr_idx, uint8_t* aiu, const int32_t* K_prev, const uint8_t* upper_prev,
+                           int max_change, hipStream_t st) {
     hipLaunchKernelGGL((estimate_kernel<THREADS, ITEMS>), dim3(F), dim3(THREADS), 0, st, W, n, alpha, beta, K,
-                       thr_val, thr_idx, aiu);
+                       thr_val, thr_idx, aiu, K_prev, upper_prev, max_change);
     return launch_status();
+}
+
+// Smallest padded size that holds the row; odd item counts keep the per-thread key runs off each
+// other's LDS banks.
+static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* beta, int32_t* K, float* thr_val,
+                             int32_t* thr_idx, uint8_t* aiu, const int32_t* K_prev, const uint8_t* upper_prev,
+                             int max_change, hipStream_t st) {
+#define DAB_EST(T, I) \
+    return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, st)
+    if (n <= 64 * 3) DAB_EST(64, 3);
+    if (n <= 256 * 3) DAB_EST(256, 3);
+    if (n <= 256 * 5) DAB_EST(256, 5);
+    if (n <= 256 * 7) DAB_EST(256, 7);
+    if (n <= 256 * 9) DAB_EST(256, 9);
+    if (n <= 256 * 11) DAB_EST(256, 11);
+    if (n <= 512 * 7) DAB_EST(512, 7);
+    if (n <= 512 * 9) DAB_EST(512, 9);
+    if (n <= 512 * 11) DAB_EST(512, 11);
+    if (n <= 1024 * 7) DAB_EST(1024, 7);
+    if (n <= 1024 * 9) DAB_EST(1024, 9);
+    if (n <= 1024 * 11) DAB_EST(1024, 11);
+    DAB_EST(1024, 13);
+#undef DAB_EST
 }
 
 }  // namespace dab
@@ -300,24 +335,25 @@ int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n, float* alpha, 
         misaligned(thr_val, 4) || misaligned(thr_idx, 4))
         return DAB_ERR_ALIGN;
     if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-#define DAB_EST(T, I) return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, st)
-    // smallest padded size that holds the row; odd item counts keep the per-thread key runs off
-    // each other's LDS banks
-    if (n <= 64 * 3) DAB_EST(64, 3);
-    if (n <= 256 * 3) DAB_EST(256, 3);
-    if (n <= 256 * 5) DAB_EST(256, 5);
-    if (n <= 256 * 7) DAB_EST(256, 7);
-    if (n <= 256 * 9) DAB_EST(256, 9);
-    if (n <= 256 * 11) DAB_EST(256, 11);
-    if (n <= 512 * 7) DAB_EST(512, 7);
-    if (n <= 512 * 9) DAB_EST(512, 9);
-    if (n <= 512 * 11) DAB_EST(512, 11);
-    if (n <= 1024 * 7) DAB_EST(1024, 7);
-    if (n <= 1024 * 9) DAB_EST(1024, 9);
-    if (n <= 1024 * 11) DAB_EST(1024, 11);
-    DAB_EST(1024, 13);
-#undef DAB_EST
+    return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, nullptr, nullptr, 0,
+                             static_cast<hipStream_t>(stream));
+}
+
+int dab_estimate_alpha_beta_bounded(const float* W, int32_t F, int32_t n, const int32_t* K_prev,
+                                    const uint8_t* alpha_is_upper_prev, int32_t max_change, float* alpha, float* beta,
+                                    int32_t* K, float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* ws,
+                                    size_t ws_bytes, void* stream) {
+    using namespace dab;
+    (void)ws; (void)ws_bytes;
+    if (!W || !K_prev || !alpha_is_upper_prev || !alpha || !beta || !K || !thr_val || !thr_idx || !alpha_is_upper)
+        return DAB_ERR_NULL;
+    if (F < 1 || n < 2 || max_change < 0) return DAB_ERR_SHAPE;
+    if (misaligned(W, 4) || misaligned(K_prev, 4) || misaligned(alpha, 4) || misaligned(beta, 4) || misaligned(K, 4) ||
+        misaligned(thr_val, 4) || misaligned(thr_idx, 4))
+        return DAB_ERR_ALIGN;
+    if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
+    return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, K_prev, alpha_is_upper_prev,
+                             max_change, static_cast<hipStream_t>(stream));
 }
 
 int dab_estimate_sign_split(const float* W, int32_t F, int32_t n, float* alpha, float* beta, int32_t* K,

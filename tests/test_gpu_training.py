@@ -121,3 +121,62 @@ def test_sign_split_descriptor_and_errors():
     assert lib.dab_mean_center_clamp(None, 6, 130, 1, 0, -1.0, 1.0, p, None) == dab.DAB_ERR_NULL
     assert lib.dab_weight_gradient(p, 6, 1, p, p, p, None, p, None) == dab.DAB_ERR_SHAPE
     assert lib.dab_binarized_weights(p, 0, 130, p, p, p, p, p, p, None) == dab.DAB_ERR_SHAPE
+
+
+# ------------------------------------------------------------------ bounded change of the split
+def check_bounded(w, got, K_prev, up_prev, d):
+    F, n = w.shape
+    for f in range(F):
+        r = oest.estimate_filter_bounded(w[f], int(K_prev[f]), int(up_prev[f]), d)
+        lo, hi = oest.split_window(n, int(K_prev[f]), int(up_prev[f]), d)
+        upper, K = int(got["alpha_is_upper"][f]), int(got["K"][f])
+        i_gpu = n - K if upper else K
+        assert lo <= i_gpu <= hi, f"filter {f}: split {i_gpu} outside the window {lo}..{hi}"
+        if i_gpu != r["i_star"]:                                      # only a near-tie of D may differ
+            assert oest.score_of_split(w[f], i_gpu) >= r["maxD"] * (1 - gu.D_RTOL)
+        low = oest.lower_group_from_descriptor(w[f], float(got["thr_val"][f]), int(got["thr_idx"][f]))
+        order = oest.stable_order(w[f])
+        ref_low = np.zeros(n, bool)
+        ref_low[order[:i_gpu]] = True
+        assert np.array_equal(low, ref_low), f"filter {f}: descriptor"
+        w64 = w[f].astype(np.float64)
+        mu_l, mu_u = w64[low].mean(), w64[~low].mean()
+        a_ref, b_ref = (mu_u, mu_l) if upper else (mu_l, mu_u)
+        if abs(abs(mu_u) - abs(mu_l)) > 1e-12 * max(abs(mu_u), abs(mu_l)):
+            assert upper == (1 if abs(mu_u) >= abs(mu_l) else 0), f"filter {f}: labelling"
+        assert abs(got["alpha"][f] - a_ref) <= gu.AB_RTOL * abs(a_ref) + 1e-30
+        assert abs(got["beta"][f] - b_ref) <= gu.AB_RTOL * abs(b_ref) + 1e-30
+
+
+@pytest.mark.parametrize("F,n", [(9, 18), (40, 1600), (6, 45), (5, 12544), (17, 900)])
+def test_bounded_estimate(F, n):
+    rng = np.random.default_rng(50 + n)
+    w0 = wl.skewed_mixture_weights(rng, np.random.default_rng(51 + n), F, n, n)
+    t0 = gu.to_gpu(w0)
+    prev = dab.dab_estimate_alpha_beta(t0)
+    # the weights after an update: a small step
+    w1 = (w0 + 0.05 * np.float32(np.sqrt(2.0 / n)) * rng.standard_normal((F, n))).astype(np.float32)
+    t1 = gu.to_gpu(w1)
+    Kp, up = prev["K"].cpu().numpy(), prev["alpha_is_upper"].cpu().numpy()
+    for d in (0, 1, max(2, n // 50), n, 2 ** 31 - 1):
+        got = dab.dab_estimate_alpha_beta_bounded(t1, prev["K"], prev["alpha_is_upper"], d)
+        torch.cuda.synchronize()
+        check_bounded(w1, {k: v.cpu().numpy() for k, v in got.items()}, Kp, up, d)
+    # a window that covers everything is the plain estimate, bit for bit
+    full = dab.dab_estimate_alpha_beta(t1)
+    for k in full:
+        assert torch.equal(full[k], got[k]), k
+    # previous outputs and new outputs in the same buffers
+    state = {k: v.clone() for k, v in prev.items()}
+    dab.dab_estimate_alpha_beta_bounded(t1, state["K"], state["alpha_is_upper"], 3, out=state)
+    sep = dab.dab_estimate_alpha_beta_bounded(t1, prev["K"], prev["alpha_is_upper"], 3)
+    torch.cuda.synchronize()
+    for k in sep:
+        assert torch.equal(sep[k], state[k]), k
+    # previous values outside 1 .. n-1 are pulled inside
+    odd = torch.tensor([0, n, 5 * n] + [1] * (F - 3), dtype=torch.int32, device=t1.device)
+    got = dab.dab_estimate_alpha_beta_bounded(t1, odd, prev["alpha_is_upper"], 2)
+    torch.cuda.synchronize()
+    check_bounded(w1, {k: v.cpu().numpy() for k, v in got.items()}, odd.cpu().numpy(), up, 2)
+    assert dab.lib().dab_estimate_alpha_beta_bounded(t1.data_ptr(), F, n, odd.data_ptr(), up.ctypes.data, -1, 1, 1, 1, 1, 1,
+                                                     1, None, 0, None) == dab.DAB_ERR_SHAPE
