@@ -56,7 +56,7 @@ def parse():
     ap.add_argument("--wait-all", action="store_true",
                     help="let the first product wait for the weight sides of all layers (default: each product waits "
                          "only for its own layer's weights, so later layers' weight sides run beside earlier products)")
-    ap.add_argument("--no-fused", action="store_true", help="skip the fused-chain measurement")
+    ap.add_argument("--no-fused", action="store_true", help="skip the fused-chain and training-side measurements")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
                          "HBM byte counters of a rocprofv3 --pmc run)")
@@ -287,6 +287,56 @@ def build_states(batch, dab, torch, wl):
     return states
 
 
+def training_weight_side(states, dab, torch, args):
+    """The weight side of one training iteration (Algorithm 2, Theorem 4) for the six layers, measured
+    beside the headline: MeanCenter + Clamp, estimation inside a window around the previous split,
+    weight packing, W~, and the gradient factor applied to an upstream gradient.  One stream, one
+    HIP graph.  Algorithmic bytes: nine passes over arrays of the size of W (the raw weights read once,
+    the centred weights read by four kernels, the upstream gradient read once; centred weights, W~ and
+    the gradient written) plus the packed bits."""
+    bufs = []
+    for s in states:
+        bufs.append({"Wc": torch.empty_like(s.W), "Wt": torch.empty_like(s.W2), "G": torch.empty_like(s.W2),
+                     "up": torch.randn_like(s.W2), "prev": {k: v.clone() for k, v in s.est.items()}})
+
+    def step():
+        for s, b in zip(states, bufs):
+            dab.dab_mean_center_clamp(s.W, dab.DAB_CENTER_FILTER, -1.0, 1.0, out=b["Wc"])
+            W2 = b["Wc"].view(s.L.F, -1)
+            est = dab.dab_estimate_alpha_beta_bounded(W2, b["prev"]["K"], b["prev"]["alpha_is_upper"],
+                                                      max(1, W2.shape[1] // 64), out=b["prev"])
+            dab.dab_pack_weights(b["Wc"], est["thr_val"], est["thr_idx"], est["alpha_is_upper"], out=s.EW)
+            dab.dab_binarized_weights(W2, est["alpha"], est["beta"], est["thr_val"], est["thr_idx"],
+                                      est["alpha_is_upper"], out=b["Wt"])
+            dab.dab_weight_gradient(W2, est["thr_val"], est["thr_idx"], est["alpha_is_upper"], upstream=b["up"],
+                                    out=b["G"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        step()
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    weights = sum(s.W.numel() for s in states)
+    nbytes = weights * 4 * 9 + sum(s.EW[0].numel() * 4 for s in states)
+    # leave the plain step's packed weights as they were
+    for s in states:
+        weight_side(s, dab)
+    torch.cuda.synchronize()
+    return {"what": "MeanCenter + Clamp, windowed estimate, pack weights, W~, Theorem 4 gradient for the six layers; "
+                    "one stream, one HIP graph",
+            "ms_per_step": round(1e3 * dt / args.steps, 4), "weights": weights, "algorithmic_bytes": nbytes,
+            "gb_per_s": round(nbytes / (dt / args.steps) / 1e9, 1)}
+
+
 def cpu_oracle_baseline(batch, wl):
     """The float64 CPU oracle, as it stands, on a small slice of the same workload."""
     import numpy as np
@@ -456,6 +506,7 @@ def main():
                                                               for k in range(args.steps)) / args.steps, 4)
                                           for i, s in enumerate(states)}}
 
+    training = None if args.no_fused else training_weight_side(states, dab, torch, args)
     cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
     line = {
         "metric": "effective binary MACs/s on Sketch-A-Net binarized layers",
@@ -470,6 +521,7 @@ def main():
                    "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
                    "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "rebinarized_chain": fused,
+        "training_weight_side": training,
     }
     print(json.dumps(line))
 
