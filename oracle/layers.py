@@ -19,6 +19,9 @@ Readings taken where the text is silent:
 * The layer is a cross-correlation (no kernel flip), no bias, no activation
   scaling factor: y = sum_i a_i * w~_i.
 
+* WBin (Section 5.1: only the weights binarized): the same layer applied to the
+  real-valued input, nothing else changed (``weights_only_layer``).
+
 Layouts: activations are NCHW here (the conventional statement of the
 problem); outputs are returned as [B, Ho, Wo, F].
 """
@@ -195,3 +198,22 @@ def next_layer_input(y: np.ndarray, tau=None, pool=None) -> np.ndarray:
     if pool is not None:
         y = max_pool(y, *pool)
     return binarize_activations(np.transpose(np.asarray(y), (0, 3, 1, 2)), tau)
+
+
+def weights_only_layer(x, e, alpha, beta, pad=(0, 0), stride=(1, 1)) -> np.ndarray:
+    """The WBin variant of Section 5.1: only the weights are binarized, the input keeps its real values.
+
+    y = x (*) W~ with W~ = alpha e + beta (1-e) (Section 4.1, 4.3.2), zero padding, no bias.
+    x is [B,C,H,W] (or [B,K] with e [F,K]); returns [B,Ho,Wo,F] (or [B,F]) in float64.
+    """
+    Wt = two_valued_filters(e, alpha, beta)
+    x = np.asarray(x, dtype=np.float64)
+    if x.ndim == 2:
+        return fc(x, Wt)
+    return conv2d(x, Wt, pad, stride)
+
+
+def weights_only_magnitude(x, e, alpha, beta, pad=(0, 0), stride=(1, 1)) -> np.ndarray:
+    """sum_i |x_i| |w~_i| per output: the scale a floating-point evaluation of the layer is accurate to."""
+    return weights_only_layer(np.abs(np.asarray(x, dtype=np.float64)), e, np.abs(np.asarray(alpha, dtype=np.float64)),
+                              np.abs(np.asarray(beta, dtype=np.float64)), pad, stride)

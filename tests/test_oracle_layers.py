@@ -167,3 +167,39 @@ def test_packed_words_reproduce_integer_terms():
                 m += C
         assert 2 * p1 - c1 == s1[b, oy, ox, f]
         assert 2 * pA - m == sA[b, oy, ox]
+
+
+# ------------------------------------------------------------------ WBin (weights-only binarized layer)
+def test_weights_only_layer_against_library_and_two_term_form():
+    """Section 5.1's WBin: real input, two-valued filters.  Checked against a library cross-correlation
+    and against beta * sum(x) + (alpha - beta) * sum over the mask, brute force, on a small case."""
+    rng = np.random.default_rng(61)
+    B, C, H, W, F, kh, kw = 2, 5, 7, 6, 4, 3, 2
+    x = rng.standard_normal((B, C, H, W))
+    e = (rng.random((F, C, kh, kw)) < 0.4).astype(np.uint8)
+    alpha, beta = rng.standard_normal(F), rng.standard_normal(F) * 0.3
+    for pad, stride in (((0, 0), (1, 1)), ((1, 1), (1, 1)), ((2, 1), (2, 1))):
+        got = lay.weights_only_layer(x, e, alpha, beta, pad, stride)
+        Wt = np.where(e == 1, alpha[:, None, None, None], beta[:, None, None, None])
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(Wt), padding=pad, stride=stride)
+        assert np.allclose(got, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+        xp = np.pad(x, ((0, 0), (0, 0), (pad[0], pad[0]), (pad[1], pad[1])))
+        Bo, Ho, Wo, _ = got.shape
+        for b in range(B):
+            for oy in range(Ho):
+                for ox in range(Wo):
+                    win = xp[b, :, oy * stride[0]:oy * stride[0] + kh, ox * stride[1]:ox * stride[1] + kw]
+                    for f in range(F):
+                        two = beta[f] * win.sum() + (alpha[f] - beta[f]) * win[e[f] == 1].sum()
+                        assert got[b, oy, ox, f] == pytest.approx(two, rel=1e-11, abs=1e-12)
+        mag = lay.weights_only_magnitude(x, e, alpha, beta, pad, stride)
+        assert np.all(mag >= np.abs(got) - 1e-12)
+    # fully connected form, and +1/-1 inputs reduce to the binarized layer
+    xf = rng.standard_normal((3, 11))
+    ef = (rng.random((4, 11)) < 0.5).astype(np.uint8)
+    assert np.allclose(lay.weights_only_layer(xf, ef, alpha, beta),
+                       xf @ np.where(ef == 1, alpha[:, None], beta[:, None]).T, rtol=1e-13)
+    a = np.where(x >= 0, 1, -1).astype(np.int8)
+    s1, sA = lay.integer_terms(a, e, (1, 1), (1, 1))
+    assert np.allclose(lay.weights_only_layer(a, e, alpha, beta, (1, 1), (1, 1)),
+                       lay.layer_from_integer_terms(s1, sA, alpha, beta), rtol=1e-12, atol=1e-12)
