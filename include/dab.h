@@ -255,6 +255,32 @@ int dab_pool_bits(const uint32_t* A_packed, int32_t B, int32_t C, int32_t H, int
                   int32_t stride_h, int32_t stride_w, uint32_t* A_pooled, void* stream);
 
 /*
+ * dab_wbin_conv2d / dab_wbin_fc - the weights-only binarized layer (Section 5.1's WBin: the
+ * convolutional weights binarized, the inputs left real): y = x (*) W~ with
+ * W~ = alpha e + beta (1 - e) (Sections 4.1, 4.3.2), evaluated as
+ *     y[p][f] = beta[f] * sum_i x_i + (alpha[f] - beta[f]) * sum_i x_i e_i
+ * over the taps inside the image (zero padding, cross-correlation, no bias).  The second sum is a
+ * dense contraction and runs on the matrix cores: each fp32 input is split exactly into three bf16
+ * pieces, the mask is bf16 0 / 1, so every product is exact and only the fp32 accumulation rounds.
+ *
+ *   X          fp32 NHWC [B][H][W][C] (dab_wbin_fc: [B][Kin]), finite, 16-byte aligned
+ *   E_packed, alpha, beta   as for dab_binconv2d (the outputs of dab_pack_weights / the estimator)
+ *   Y          fp32 NHWC [B][Ho][Wo][F] out (dab_wbin_fc: [B][F])
+ *   ws         workspace of dab_wbin_conv2d_workspace_bytes(d) bytes (dab_wbin_fc_workspace_bytes),
+ *              256-byte aligned: the bf16 pieces (6 bytes per input element, with the padding
+ *              halo), the expanded masks, per-pixel input sums
+ * Accuracy: fp32 accumulation of exact terms; the error is bounded by about (3*n/16 + T) * 2^-24
+ * times sum_i |x_i| |w~_i| (n = C*kh*kw, T = kh*kw) and is typically a few 1e-7 of that scale.
+ * Errors as for dab_binconv2d.
+ */
+size_t dab_wbin_conv2d_workspace_bytes(const dab_conv_desc* d /* host */);
+size_t dab_wbin_fc_workspace_bytes(int32_t B, int32_t Kin, int32_t F);
+int dab_wbin_conv2d(const dab_conv_desc* d /* host */, const float* X, const uint32_t* E_packed, const float* alpha,
+                    const float* beta, float* Y, void* ws, size_t ws_bytes, void* stream);
+int dab_wbin_fc(int32_t B, int32_t Kin, int32_t F, const float* X, const uint32_t* E_packed, const float* alpha,
+                const float* beta, float* Y, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Weight-side steps of one training iteration (Algorithm 2).  The real weights are mean-centred
  * and clamped, every filter is binarized (dab_estimate_alpha_beta on the result), W~ is formed for
  * the forward and backward pass, and the gradient with respect to W~ is turned into the gradient

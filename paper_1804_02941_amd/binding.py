@@ -71,6 +71,12 @@ _SIGNATURES = {
                                c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_pool_bits": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32,
                               c_void_p, c_void_p]),
+    "dab_wbin_conv2d_workspace_bytes": (c_size_t, [ctypes.POINTER(dab_conv_desc)]),
+    "dab_wbin_fc_workspace_bytes": (c_size_t, [c_int32, c_int32, c_int32]),
+    "dab_wbin_conv2d": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                c_void_p, c_size_t, c_void_p]),
+    "dab_wbin_fc": (c_int, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                            c_size_t, c_void_p]),
     "dab_mean_center_clamp": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_float, c_float, c_void_p,
                                       c_void_p]),
     "dab_binarized_weights": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -328,3 +334,31 @@ def dab_estimate_alpha_beta_bounded(W, K_prev, alpha_is_upper_prev, max_change, 
         _ptr(o["thr_val"], torch.float32, "thr_val"), _ptr(o["thr_idx"], torch.int32, "thr_idx"),
         _ptr(o["alpha_is_upper"], torch.uint8, "alpha_is_upper"), None, 0, _stream()))
     return o
+
+
+def dab_wbin_conv2d(desc, X, E_packed, alpha, beta, out=None, ws=None):
+    """Weights-only binarized convolution: X fp32 NHWC [B,H,W,C] -> Y fp32 [B,Ho,Wo,F]."""
+    dev = X.device
+    Y = out if out is not None else torch.empty((desc.B, desc.Ho, desc.Wo, desc.F), dtype=torch.float32, device=dev)
+    nbytes = lib().dab_wbin_conv2d_workspace_bytes(ctypes.byref(desc))
+    ws = _workspace(nbytes, dev, ws)
+    _check("dab_wbin_conv2d", lib().dab_wbin_conv2d(
+        ctypes.byref(desc), _ptr(X, torch.float32, "X"), _ptr(E_packed, torch.int32, "E_packed"),
+        _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"), _ptr(Y, torch.float32, "Y"),
+        ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return Y
+
+
+def dab_wbin_fc(X, E_packed, alpha, beta, out=None, ws=None):
+    """Weights-only binarized fully-connected layer: X fp32 [B,Kin] -> Y fp32 [B,F]."""
+    dev = X.device
+    B, Kin = X.shape
+    F = alpha.shape[0]
+    Y = out if out is not None else torch.empty((B, F), dtype=torch.float32, device=dev)
+    nbytes = lib().dab_wbin_fc_workspace_bytes(B, Kin, F)
+    ws = _workspace(nbytes, dev, ws)
+    _check("dab_wbin_fc", lib().dab_wbin_fc(
+        B, Kin, F, _ptr(X, torch.float32, "X"), _ptr(E_packed, torch.int32, "E_packed"),
+        _ptr(alpha, torch.float32, "alpha"), _ptr(beta, torch.float32, "beta"), _ptr(Y, torch.float32, "Y"),
+        ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return Y

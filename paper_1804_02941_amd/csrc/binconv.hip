@@ -62,7 +62,8 @@ struct MfmaGeom {
     int act_p, act_w, act_wt;      // prepare: pixels x words of a transpose tile (product 256), word tiles
     int sum_shift;                 // prepare: log2 of the lanes that share one pixel's row sum
     int n_fblocks;                 // 32-filter column blocks (small products)
-    FastDiv d_HoWo, d_Wo, d_Wp, d_HpWp, d_nk, d_mtiles, d_ksplit, d_T, d_kw, d_act_wt, d_Cw, d_fblocks;
+    int wbin, C16, nb;             // weights-only layer: flag, 16-channel groups per tap, B steps per filter tile (fp4: nb = nk)
+    FastDiv d_HoWo, d_Wo, d_Wp, d_HpWp, d_nk, d_mtiles, d_ksplit, d_T, d_kw, d_act_wt, d_Cw, d_fblocks, d_3;
     // block ranges of the prepare kernel
     unsigned blk_act, blk_wgt, blk_sum, blk_tab, blk_sa;
 };
@@ -215,6 +216,141 @@ __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, 
     }
 }
 
+// ---------------------------------------------------------------- prepare (weights-only layer)
+// fp32 -> bf16 with round-to-nearest-even (finite inputs).
+__device__ __forceinline__ uint32_t bf16_bits(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float bf16_value(uint32_t b) { return __uint_as_float(b << 16); }
+
+// The weights-only layer keeps the real inputs: x is split into three bf16 pieces, x = p0 + p1 + p2
+// exactly (each remainder is computed exactly in fp32 and has at most 16, then 8 significant bits),
+// the masks become bf16 0 / 1, and every product p * e is exact, so the fp32 accumulators of the
+// MFMAs see exactly the terms x_i e_i, eight bits at a time.  Layout of the pieces: planes
+// [(16-channel group * 3 + piece) * 2 + half][padded pixel][8 bf16], zero halo, zero past C;
+// weights: fragments [128-filter tile][16-channel group * T + tap][4][2][32][8 bf16].
+__global__ __launch_bounds__(256) void wbin_prepare_kernel(const MfmaGeom g, const float* __restrict__ X,
+                                                           const uint32_t* __restrict__ E, uint4* __restrict__ A16,
+                                                           uint4* __restrict__ E16, float* __restrict__ pixsum,
+                                                           int32_t* __restrict__ ktab, float* __restrict__ sA) {
+    DAB_RESERVE_VGPRS();
+    unsigned blk = blockIdx.x;
+    if (blk < g.blk_act) {
+        const long long i = 1ll * blk * 256 + threadIdx.x;
+        if (i >= 1ll * g.npix * 2 * g.C16) return;
+        const int g8 = static_cast<int>(i / g.npix);                // 8-channel group
+        const int pp = static_cast<int>(i - 1ll * g8 * g.npix);     // padded pixel (fastest: coalesced stores)
+        const int b = fdiv(pp, g.d_HpWp);
+        const int r = pp - b * g.Hp * g.Wp;
+        const int yp = fdiv(r, g.d_Wp);
+        const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
+        float v[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] = 0.0f;
+        if (y >= 0 && y < g.H && x >= 0 && x < g.W) {
+            const float* src = X + ((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.C + g8 * 8;
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                if (g8 * 8 + c < g.C) v[c] = src[c];
+        }
+        uint32_t piece[3][8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float rest = v[c];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                piece[p][c] = bf16_bits(rest);
+                rest -= bf16_value(piece[p][c]);                     // exact
+            }
+        }
+        const int c16 = g8 >> 1, half = g8 & 1;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const size_t q = static_cast<size_t>((c16 * 3 + p) * 2 + half);
+            A16[q * g.npix + pp] = make_uint4(piece[p][0] | (piece[p][1] << 16), piece[p][2] | (piece[p][3] << 16),
+                                              piece[p][4] | (piece[p][5] << 16), piece[p][6] | (piece[p][7] << 16));
+        }
+        return;
+    }
+    blk -= g.blk_act;
+    if (blk < g.blk_wgt) {
+        const long long i = 1ll * blk * 256 + threadIdx.x;
+        if (i >= 1ll * g.n_ntiles * g.nb * 256) return;
+        const int e = static_cast<int>(i & 255);
+        const int tk = static_cast<int>(i >> 8);                    // filter tile * nb + B step
+        const int nt = tk / g.nb;
+        const int bs = tk - nt * g.nb;
+        const int c16 = fdiv(bs, g.d_T);
+        const int tap = bs - c16 * g.T;
+        const int j = e >> 6, half = (e >> 5) & 1, f = nt * kNTile + j * 32 + (e & 31);
+        uint32_t bits = 0;
+        if (f < g.Fp) bits = (E[(static_cast<size_t>(tap) * g.Cw + (c16 >> 1)) * g.Fp + f] >> ((c16 & 1) * 16 + half * 8)) & 0xFFu;
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            w[k] = ((bits >> (2 * k)) & 1u ? 0x3F80u : 0u) | ((bits >> (2 * k + 1)) & 1u ? 0x3F800000u : 0u);
+        E16[i] = make_uint4(w[0], w[1], w[2], w[3]);
+        return;
+    }
+    blk -= g.blk_wgt;
+    if (blk < g.blk_sum) {
+        // sum of the real inputs of every padded pixel (0 in the halo), double accumulation;
+        // 2^sum_shift neighbouring lanes share a pixel (about sixteen channels each)
+        const unsigned t = blk * 256 + threadIdx.x;
+        const int pp = static_cast<int>(t >> g.sum_shift);
+        const int sub = static_cast<int>(t & ((1u << g.sum_shift) - 1));
+        const int ppc = min(pp, g.npix - 1);                       // every lane stays in the shuffles
+        const int b = fdiv(ppc, g.d_HpWp);
+        const int r = ppc - b * g.Hp * g.Wp;
+        const int yp = fdiv(r, g.d_Wp);
+        const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
+        double sum = 0.0;
+        if (y >= 0 && y < g.H && x >= 0 && x < g.W) {
+            const float* src = X + ((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.C;
+            for (int c = sub; c < g.C; c += 1 << g.sum_shift) sum += static_cast<double>(src[c]);
+        }
+        for (int d = 1; d < (1 << g.sum_shift); d <<= 1) sum += __shfl_xor(sum, d, 64);
+        if (pp < g.npix && sub == 0) pixsum[pp] = static_cast<float>(sum);
+        return;
+    }
+    blk -= g.blk_sum;
+    if (blk < g.blk_tab) {
+        // byte offset of every k-step: steps run (16-channel group, piece) slowest, taps fastest
+        const int i = static_cast<int>(blk * 256 + threadIdx.x);
+        if (i >= g.nk + kTabPad) return;
+        const int ks = min(i, g.nk - 1);
+        const int kb = fdiv(ks, g.d_T);
+        const int tap = ks - kb * g.T;
+        const int ky = fdiv(tap, g.d_kw);
+        const int kx = tap - ky * g.kw;
+        ktab[i] = kb * 2 * g.plane + (ky * g.Wp + kx) * 16;
+        return;
+    }
+    blk -= g.blk_tab;
+    {
+        // small layers only: the window sum of every output pixel, one wavefront per pixel, lanes
+        // along the channels of a tap
+        const int m = static_cast<int>(blk * 4 + (threadIdx.x >> 6));
+        if (m >= g.M) return;
+        const int lane = threadIdx.x & 63;
+        const int b = fdiv(m, g.d_HoWo);
+        const int r = m - b * g.HoWo;
+        const int oy = fdiv(r, g.d_Wo);
+        const int ox = r - oy * g.Wo;
+        double acc = 0.0;
+        for (int tap = 0; tap < g.T; ++tap) {
+            const int ky = fdiv(tap, g.d_kw);
+            const int y = oy * g.sh - g.ph + ky, x = ox * g.sw - g.pw + (tap - ky * g.kw);
+            if (y < 0 || y >= g.H || x < 0 || x >= g.W) continue;
+            const float* src = X + ((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.C;
+            for (int c = lane; c < g.C; c += 64) acc += static_cast<double>(src[c]);
+        }
+        for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+        if (lane == 0) sA[m] = static_cast<float>(acc);
+    }
+}
+
 // ---------------------------------------------------------------- main
 __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
     const v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0};
@@ -224,6 +360,21 @@ __device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
 }
 
 enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2, kOutBits = 3 };
+// Operand kinds of the main kernel: bits expanded to fp4 (the binarized layer), or bf16 (the
+// weights-only layer: fp32 inputs split into three bf16 pieces, masks as 0 / 1).
+enum { kFp4 = 0, kBf16 = 1 };
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+template <int KIND>
+__device__ __forceinline__ v16f mfma_step(v4i a, v4i b, v16f c) {
+    if constexpr (KIND == kFp4) {
+        return mfma_fp4(a, b, c);
+    } else {
+        // 32x32x16: lane l holds row (column) l % 32 and the eight k of half l / 32
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+    }
+}
 
 
 // One group of the k-step schedule: an MFMA, then at most one LDS read or one buffer load in its shadow.
@@ -231,7 +382,7 @@ enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2, kOutBits = 3 };
 #define DAB_SLOT_VMEM() do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); } while (0)
 #define DAB_SLOT_NONE() do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); } while (0)
 
-template <int WAVES, int MODE>
+template <int WAVES, int MODE, int KIND = kFp4>
 __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom g, const char* __restrict__ A4,
                                                                   const uint4* __restrict__ E4,
                                                                   const float* __restrict__ alpha,
@@ -267,7 +418,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         kend = g.nk;
     }
     const int f0 = ntile * kNTile;
-    const uint4* Epanel = E4 + static_cast<size_t>(ntile) * g.nk * 256;
+    const uint4* Epanel = E4 + static_cast<size_t>(ntile) * g.nb * 256;
     const int nchunks = (kend - kbeg + g.kchunk - 1) / g.kchunk;
     // A4 as a buffer resource: the per-lane pixel offset rides in a VGPR, the k-step offset in an SGPR
     const __amdgpu_buffer_rsrc_t a4rsrc =
@@ -290,12 +441,18 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
     // (it is rounded up to the prefetch depth) hold zeros.
     auto stage_panel = [&](int ks0, int ks1, int steps) {
         const int nkb = (ks1 - ks0) * 4;                           // 1 KB pieces: 64 groups of 16 bytes
-        const uint4* src = Epanel + static_cast<size_t>(ks0) * 256;
         const int rot = blockIdx.x % nkb;
         for (int i = wave; i < nkb; i += WAVES) {
             int kb = i + rot;
             kb = kb >= nkb ? kb - nkb : kb;
-            __builtin_amdgcn_global_load_lds(src + kb * 64 + lane, panel + kb * 64, 16, 0, 0);
+            int bs = ks0 + (kb >> 2);                              // B step of this k-step
+            if (KIND == kBf16) {
+                // k-steps run (16-channel group, piece, tap); the three pieces share the group's fragments
+                const int kbp = fdiv(bs, g.d_T);
+                bs = fdiv(kbp, g.d_3) * g.T + (bs - kbp * g.T);
+            }
+            __builtin_amdgcn_global_load_lds(Epanel + static_cast<size_t>(bs) * 256 + (kb & 3) * 64 + lane,
+                                             panel + kb * 64, 16, 0, 0);
         }
         for (int e = nkb * 64 + tid; e < steps * 256; e += THREADS) panel[e] = make_uint4(0, 0, 0, 0);
     };
@@ -322,7 +479,17 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         // entries of the k-step table are the window's pixel offsets, times 16).  Thirty-two loads at a
         // time (a 5x5 window is one round trip); the result is needed only after the reduction loop.
         float rowsum = 0.0f;
-        if (MODE != kOutSplit) {
+        if (KIND == kBf16) {
+            // weights-only layer: the per-pixel sums are fp32 sums of the real inputs
+            const float* psum = reinterpret_cast<const float*>(pixsum);
+            for (int t0 = 0; t0 < g.T; t0 += 32) {
+                float v[32];
+#pragma unroll
+                for (int u = 0; u < 32; ++u) v[u] = psum[mypix + (ktab[min(t0 + u, g.T - 1)] >> 4)];
+#pragma unroll
+                for (int u = 0; u < 32; ++u) rowsum += t0 + u < g.T ? v[u] : 0.0f;
+            }
+        } else if (MODE != kOutSplit) {
             int sum = 0;
             for (int t0 = 0; t0 < g.T; t0 += 32) {
                 int v[32];
@@ -396,8 +563,8 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                         const uint4 bu = bq[d & 1][j];
                         const v4i bv = {static_cast<int>(bu.x), static_cast<int>(bu.y), static_cast<int>(bu.z),
                                         static_cast<int>(bu.w)};
-                        acc[0][j] = mfma_fp4(abuf[d][0], bv, acc[0][j]);
-                        acc[1][j] = mfma_fp4(abuf[d][1], bv, acc[1][j]);
+                        acc[0][j] = mfma_step<KIND>(abuf[d][0], bv, acc[0][j]);
+                        acc[1][j] = mfma_step<KIND>(abuf[d][1], bv, acc[1][j]);
                     }
                     // issue order of this k-step: every memory instruction in the shadow of an MFMA
                     DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS();
@@ -521,7 +688,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
 // sA comes from the prepare kernel's per-pixel pass.
 constexpr int kSmallDepth = 8;
 
-template <int MODE, int WAVES>
+template <int MODE, int WAVES, int KIND = kFp4>
 __global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
     const MfmaGeom g, const char* __restrict__ A4, const uint4* __restrict__ E4, const float* __restrict__ alpha,
     const float* __restrict__ beta, float* __restrict__ Y, int32_t* __restrict__ dbg_s1, const float* __restrict__ sA,
@@ -531,7 +698,14 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int mb = fdiv(blockIdx.x, g.d_fblocks);
     const int fb = blockIdx.x - mb * g.n_fblocks;                   // neighbouring workgroups share the pixel rows
-    const uint4* Eb = E4 + static_cast<size_t>(fb >> 2) * g.nk * 256 + (fb & 3) * 64 + lane;
+    const uint4* Eb = E4 + static_cast<size_t>(fb >> 2) * g.nb * 256 + (fb & 3) * 64 + lane;
+    // B step of a k-step: the same index, or (weights-only layer) the 16-channel group's fragment
+    // shared by its three pieces
+    auto b_step = [&](int ks) -> int {
+        if (KIND == kFp4) return ks;
+        const int kbp = fdiv(ks, g.d_T);
+        return fdiv(kbp, g.d_3) * g.T + (ks - kbp * g.T);
+    };
     const __amdgpu_buffer_rsrc_t a4rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(A4), 0, 2 * g.KB * g.plane, 0x00020000);
     int pixoff;
@@ -570,7 +744,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
 #pragma unroll
         for (int d = 0; d < kSmallDepth; ++d) aq[set][d] = load_a(ktab[min(first + d, klast)]);
 #pragma unroll
-        for (int d = 0; d < kSmallDepth; ++d) bq[set][d] = Eb[static_cast<size_t>(min(first + d, klast)) * 256];
+        for (int d = 0; d < kSmallDepth; ++d) bq[set][d] = Eb[static_cast<size_t>(b_step(min(first + d, klast))) * 256];
     };
     auto multiply = [&](int set, int first) {
 #pragma unroll
@@ -579,7 +753,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
                 const uint4 bu = bq[set][d];
                 const v4i bv = {static_cast<int>(bu.x), static_cast<int>(bu.y), static_cast<int>(bu.z),
                                 static_cast<int>(bu.w)};
-                acc = mfma_fp4(aq[set][d], bv, acc);
+                acc = mfma_step<KIND>(aq[set][d], bv, acc);
             }
         }
     };
@@ -697,12 +871,15 @@ struct MfmaPlan {
 
 static size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
-static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
+static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl, bool wbin = false) {
     MfmaGeom& g = pl->g;
     g = MfmaGeom{};
     g.B = d.B; g.H = d.H; g.W = d.W; g.F = d.F; g.kh = d.kh; g.kw = d.kw;
     g.ph = d.pad_h; g.pw = d.pad_w; g.sh = d.stride_h; g.sw = d.stride_w;
-    g.C = d.C; g.Cw = ceil_div(d.C, 32); g.KB = ceil_div(d.C, 64);
+    g.C = d.C; g.Cw = ceil_div(d.C, 32);
+    // k-blocks per tap: 64 channels of fp4, or (weights-only layer) 16 channels of bf16 times three pieces
+    g.wbin = wbin ? 1 : 0; g.C16 = ceil_div(d.C, 16);
+    g.KB = wbin ? 3 * g.C16 : ceil_div(d.C, 64);
     g.Ho = (d.H + 2 * d.pad_h - d.kh) / d.stride_h + 1;
     g.Wo = (d.W + 2 * d.pad_w - d.kw) / d.stride_w + 1;
     g.HoWo = g.Ho * g.Wo;
@@ -712,9 +889,10 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     const long long a4 = 1ll * d.B * g.Hp * g.Wp * g.KB * 32;
     const long long nk = 1ll * d.kh * d.kw * g.KB;
     if (M >= (1ll << 30) || a4 >= (1ll << 31) || nk >= (1 << 20) || 1ll * M * d.F >= (1ll << 40)) return DAB_ERR_UNSUPPORTED;
-    if (1ll * d.C * d.kh * d.kw >= (1ll << 24)) return DAB_ERR_UNSUPPORTED;   // |s1| must stay exact in fp32
+    if (!wbin && 1ll * d.C * d.kh * d.kw >= (1ll << 24)) return DAB_ERR_UNSUPPORTED;   // |s1| must stay exact in fp32
     g.M = static_cast<int>(M);
     g.nk = static_cast<int>(nk);
+    g.nb = wbin ? d.kh * d.kw * g.C16 : g.nk;
     g.n_ntiles = ceil_div(d.F, kNTile);
     if (1ll * g.n_ntiles * g.nk >= (1ll << 22)) return DAB_ERR_UNSUPPORTED;
 
@@ -725,7 +903,7 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     const int tiles256 = ceil_div(g.M, 256) * g.n_ntiles;
     pl->waves = 1ll * ceil_div(g.M, 512) * g.n_ntiles >= kNumCU * 3 / 4 ? 8 : 4;
     g.ksplit = 1;
-    if (tiles256 * 2 <= kNumCU) {
+    if (!wbin && tiles256 * 2 <= kNumCU) {                       // (the weights-only layer runs unsplit)
         g.ksplit = kNumCU / tiles256;
         const int max_split = g.nk / (2 * kPrefetch);              // at least two prefetch groups per split
         if (g.ksplit > max_split) g.ksplit = max_split;
@@ -759,10 +937,11 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     g.d_HoWo = make_fastdiv(g.HoWo); g.d_Wo = make_fastdiv(g.Wo);
     g.d_Wp = make_fastdiv(g.Wp); g.d_HpWp = make_fastdiv(g.Hp * g.Wp);
     g.d_T = make_fastdiv(g.T); g.d_kw = make_fastdiv(g.kw); g.d_Cw = make_fastdiv(g.Cw);
+    g.d_3 = make_fastdiv(3);
     g.d_nk = make_fastdiv(g.nk); g.d_mtiles = make_fastdiv(g.n_mtiles); g.d_ksplit = make_fastdiv(g.ksplit);
 
     pl->a4_bytes = round256(static_cast<size_t>(a4));
-    pl->e4_bytes = static_cast<size_t>(g.n_ntiles) * g.nk * 4096;
+    pl->e4_bytes = static_cast<size_t>(g.n_ntiles) * g.nb * 4096;
     pl->sa_bytes = round256(static_cast<size_t>(g.M) * 4) + round256(static_cast<size_t>(g.npix) * 4) +
                    round256(static_cast<size_t>(g.nk + kTabPad) * 4);
     pl->s1_bytes = pl->split ? round256(static_cast<size_t>(g.ksplit) * g.M * d.F * 4) : 0;
@@ -781,21 +960,32 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl) {
     g.blk_sum = static_cast<unsigned>((1ll * g.npix * (1 << g.sum_shift) + 255) / 256);
     g.blk_tab = static_cast<unsigned>((g.nk + kTabPad + 255) / 256);
     g.blk_sa = (pl->split || pl->small) ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
+    if (wbin) {
+        // block ranges of wbin_prepare_kernel: one thread per (8-channel group, padded pixel), per
+        // 16-byte weight fragment, per padded pixel, per table entry
+        g.blk_act = static_cast<unsigned>((1ll * g.npix * 2 * g.C16 + 255) / 256);
+        g.blk_wgt = static_cast<unsigned>((1ll * g.n_ntiles * g.nb * 256 + 255) / 256);
+        g.sum_shift = 0;
+        while (g.sum_shift < 6 && (16 << g.sum_shift) < d.C) ++g.sum_shift;
+        // the small kernel takes the window sums of the sA pass, not the per-pixel sums
+        g.blk_sum = pl->small ? 0u : static_cast<unsigned>((1ll * g.npix * (1 << g.sum_shift) + 255) / 256);
+        g.blk_sa = pl->small ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
+    }
     return DAB_OK;
 }
 
-template <int WAVES, int MODE>
+template <int WAVES, int MODE, int KIND = kFp4>
 static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const uint4* e4, float* sa,
                        const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, float* ws_s1,
                        const int32_t* pixsum, const int32_t* ktab, const float* tau_out, uint32_t* out_bits) {
     static thread_local size_t granted = 0;
     if (pl.lds_bytes > 48 * 1024 && pl.lds_bytes > granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE, KIND>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pl.lds_bytes));
         if (e != hipSuccess) return hip_failed(e);
         granted = pl.lds_bytes;
     }
-    hipLaunchKernelGGL((binconv_mfma_kernel<WAVES, MODE>), dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4,
+    hipLaunchKernelGGL((binconv_mfma_kernel<WAVES, MODE, KIND>), dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4,
                        e4, alpha, beta, Y, dbg_s1, ws_s1, sa, pixsum, ktab, tau_out, out_bits);
     return launch_status();
 }
@@ -860,6 +1050,38 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
                   : launch_main<4, kOutY>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits);
 }
 
+// The weights-only layer: same main kernel on bf16 operands, fp32 output only.
+static int run_wbin(const dab_conv_desc& d, const float* X, const uint32_t* E, const float* alpha, const float* beta,
+                    float* Y, void* ws, size_t ws_bytes, hipStream_t st) {
+    MfmaPlan pl;
+    if (int rc = plan_binconv(d, &pl, true)) return rc;
+    if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
+    char* a16 = static_cast<char*>(ws);
+    uint4* e16 = reinterpret_cast<uint4*>(a16 + pl.a4_bytes);
+    float* sa = reinterpret_cast<float*>(a16 + pl.a4_bytes + pl.e4_bytes);
+    const MfmaGeom& g = pl.g;
+    float* pixsum = reinterpret_cast<float*>(reinterpret_cast<char*>(sa) + round256(static_cast<size_t>(g.M) * 4));
+    int32_t* ktab = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pixsum) + round256(static_cast<size_t>(g.npix) * 4));
+    hipLaunchKernelGGL(wbin_prepare_kernel, dim3(g.blk_act + g.blk_wgt + g.blk_sum + g.blk_tab + g.blk_sa), dim3(256), 0, st,
+                       g, X, E, reinterpret_cast<uint4*>(a16), e16, pixsum, ktab, sa);
+    if (int rc = launch_status()) return rc;
+    if (pl.small) {
+        const unsigned blocks = static_cast<unsigned>(ceil_div(g.M, 32) * g.n_fblocks);
+        if (g.nk >= 32)
+            hipLaunchKernelGGL((binconv_small_kernel<kOutY, 8, kBf16>), dim3(blocks), dim3(512), 0, st, g, a16, e16, alpha,
+                               beta, Y, nullptr, sa, ktab, nullptr, nullptr);
+        else
+            hipLaunchKernelGGL((binconv_small_kernel<kOutY, 2, kBf16>), dim3(blocks), dim3(128), 0, st, g, a16, e16, alpha,
+                               beta, Y, nullptr, sa, ktab, nullptr, nullptr);
+        return launch_status();
+    }
+    const int32_t* psum = reinterpret_cast<const int32_t*>(pixsum);
+    return pl.waves == 8 ? launch_main<8, kOutY, kBf16>(pl, st, a16, e16, sa, alpha, beta, Y, nullptr, nullptr, psum, ktab,
+                                                        nullptr, nullptr)
+                         : launch_main<4, kOutY, kBf16>(pl, st, a16, e16, sa, alpha, beta, Y, nullptr, nullptr, psum, ktab,
+                                                        nullptr, nullptr);
+}
+
 static int check_common(const void* A, const void* E, const void* alpha, const void* beta, const void* Y,
                         const void* dbg) {
     if (!A || !E || !alpha || !beta || !Y) return DAB_ERR_NULL;
@@ -913,6 +1135,34 @@ int dab_binfc(int32_t B, int32_t Kin, int32_t F, const uint32_t* A_packed, const
     const dab_conv_desc d{B, Kin, 1, 1, F, 1, 1, 0, 0, 1, 1};
     return dab::run_binconv(d, A_packed, E_packed, alpha, beta, Y, dbg_s1, nullptr, nullptr, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
+}
+
+size_t dab_wbin_conv2d_workspace_bytes(const dab_conv_desc* d) {
+    dab::MfmaPlan pl;
+    if (!d || dab::check_desc(d) != DAB_OK || dab::plan_binconv(*d, &pl, true) != DAB_OK) return 0;
+    return pl.ws_bytes;
+}
+
+size_t dab_wbin_fc_workspace_bytes(int32_t B, int32_t Kin, int32_t F) {
+    if (B < 1 || Kin < 2 || F < 1) return 0;
+    const dab_conv_desc d{B, Kin, 1, 1, F, 1, 1, 0, 0, 1, 1};
+    return dab_wbin_conv2d_workspace_bytes(&d);
+}
+
+int dab_wbin_conv2d(const dab_conv_desc* d, const float* X, const uint32_t* E_packed, const float* alpha,
+                    const float* beta, float* Y, void* ws, size_t ws_bytes, void* stream) {
+    if (!d) return DAB_ERR_NULL;
+    if (int rc = dab::check_common(X, E_packed, alpha, beta, Y, nullptr)) return rc;
+    if (int rc = dab::check_desc(d)) return rc;
+    return dab::run_wbin(*d, X, E_packed, alpha, beta, Y, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int dab_wbin_fc(int32_t B, int32_t Kin, int32_t F, const float* X, const uint32_t* E_packed, const float* alpha,
+                const float* beta, float* Y, void* ws, size_t ws_bytes, void* stream) {
+    if (int rc = dab::check_common(X, E_packed, alpha, beta, Y, nullptr)) return rc;
+    if (B < 1 || Kin < 2 || F < 1) return DAB_ERR_SHAPE;
+    const dab_conv_desc d{B, Kin, 1, 1, F, 1, 1, 0, 0, 1, 1};
+    return dab::run_wbin(d, X, E_packed, alpha, beta, Y, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int dab_binconv2d_bits(const dab_conv_desc* d, const uint32_t* A_packed, const uint32_t* E_packed,
