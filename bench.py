@@ -35,6 +35,7 @@ if ROOT not in sys.path:
 #   one AND + one BCNT per 32 binary MACs of a lane, i.e. at most 6.29e14 binary MAC/s.
 #   HBM: 8 TB/s; a layer writes 4 bytes per output and reads its packed/expanded operands.
 MFMA_FP4_FLOPS = 10.1e15
+MFMA_BF16_FLOPS = 2.5e15
 VALU_PAIR_MACS = 256 * 64 * 2.4e9 * 16
 HBM_BYTES_PER_S = 8.0e12
 # HBM bytes of one conv2 call at batch 256 (prepare + main kernel), from the FETCH_SIZE and WRITE_SIZE
@@ -56,7 +57,7 @@ def parse():
     ap.add_argument("--wait-all", action="store_true",
                     help="let the first product wait for the weight sides of all layers (default: each product waits "
                          "only for its own layer's weights, so later layers' weight sides run beside earlier products)")
-    ap.add_argument("--no-fused", action="store_true", help="skip the fused-chain and training-side measurements")
+    ap.add_argument("--no-fused", action="store_true", help="skip the measurements beside the headline (fused chain, training side, weights-only layers)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
                          "HBM byte counters of a rocprofv3 --pmc run)")
@@ -337,6 +338,47 @@ def training_weight_side(states, dab, torch, args):
             "gb_per_s": round(nbytes / (dt / args.steps) / 1e9, 1)}
 
 
+def weights_only_products(states, dab, torch, args):
+    """The six layers as weights-only binarized layers (WBin of Section 5.1) on their real-valued inputs,
+    one call after the other on one stream: HIP events around each dab_wbin_conv2d / dab_wbin_fc.
+    Each input element becomes three bf16 pieces, so a binary MAC costs three bf16 MACs (6 FLOP)."""
+    import ctypes as ct
+    out = {}
+    total_ms, total_macs = 0.0, 0
+    for s in states:
+        L = s.L
+        nbytes = (dab.lib().dab_wbin_fc_workspace_bytes(s.B, L.C, L.F) if L.is_fc
+                  else dab.lib().dab_wbin_conv2d_workspace_bytes(ct.byref(s.desc)))
+        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=s.X.device)
+        Y = torch.empty_like(s.Y)
+
+        def run():
+            if L.is_fc:
+                dab.dab_wbin_fc(s.X.view(s.B, -1), s.EW[0], s.est["alpha"], s.est["beta"], out=Y, ws=ws)
+            else:
+                dab.dab_wbin_conv2d(s.desc, s.X, s.EW[0], s.est["alpha"], s.est["beta"], out=Y, ws=ws)
+
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(1, min(args.steps, 20))
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        total_ms += ms
+        total_macs += s.macs
+        out[L.name] = {"ms": round(ms, 4), "bf16_tflops": round(6 * s.macs / (ms * 1e-3) / 1e12, 1),
+                       "frac_of_mfma_bf16_peak": round(6 * s.macs / (ms * 1e-3) / MFMA_BF16_FLOPS, 4)}
+        del ws, Y
+    return {"what": "dab_wbin_conv2d / dab_wbin_fc (prepare + product) per layer, fp32 inputs as three bf16 pieces, "
+                    "one stream",
+            "ms_per_step": round(total_ms, 4), "macs_per_s": total_macs / (total_ms * 1e-3), "per_layer": out}
+
+
 def cpu_oracle_baseline(batch, wl):
     """The float64 CPU oracle, as it stands, on a small slice of the same workload."""
     import numpy as np
@@ -507,6 +549,7 @@ def main():
                                           for i, s in enumerate(states)}}
 
     training = None if args.no_fused else training_weight_side(states, dab, torch, args)
+    wbin = None if args.no_fused else weights_only_products(states, dab, torch, args)
     cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
     line = {
         "metric": "effective binary MACs/s on Sketch-A-Net binarized layers",
@@ -521,7 +564,7 @@ def main():
                    "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
                    "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "rebinarized_chain": fused,
-        "training_weight_side": training,
+        "training_weight_side": training, "weights_only_layers": wbin,
     }
     print(json.dumps(line))
 
