@@ -34,6 +34,13 @@
 //             Layers too small to fill the chip are also split along the reduction and write
 //             their exact partial sums to the workspace;
 //   finish    (split launches only) adds the partials, y = (alpha-beta)*s1 + beta*sA.
+// Layers with at most 512 output blocks of 32 x 32 skip main and finish for the small-product
+// kernel further down (one workgroup per block, no partial sums in memory).
+//
+// The weights-only layer (Section 5.1's WBin: real inputs, binarized weights) runs through the
+// same main and small kernels with bf16 operands: wbin_prepare_kernel splits every fp32 input
+// exactly into three bf16 pieces laid out like the fp4 planes, the masks become bf16 0 / 1, and
+// v_mfma_f32_32x32x16_bf16 takes the place of the fp4 instruction (products exact, fp32 sums).
 #include "dab_internal.h"
 
 namespace dab {
