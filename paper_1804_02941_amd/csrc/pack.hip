@@ -66,16 +66,22 @@ __global__ __launch_bounds__(256) void pack_act_nhwc_kernel(const float* __restr
 // Fast path: C a multiple of 64 whose 64-channel groups divide sixteen.  Item t then starts at
 // float 64*t of X and at word 2*t of A, so a batch of sixteen items is one base address plus
 // immediate offsets, and the thresholds of the batch stay in registers.
+// CW64 (the 64-channel groups per pixel: 1, 2, 4, 8 or 16) is a template parameter so that only
+// CW64 thresholds are held beside the two batches of sixteen values (45-48 VGPRs up to 256 channels).
+template <int CW64>
 __global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float* __restrict__ X,
                                                                     const float* __restrict__ tau,
-                                                                    uint32_t* __restrict__ A, int n_items, int Cw64) {
-    DAB_RESERVE_VGPRS();
+                                                                    uint32_t* __restrict__ A, int n_items) {
+    if (CW64 >= 8) DAB_RESERVE_VGPRS();                     // these would land on 64 registers
     const int lane = threadIdx.x & 63;
     const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int n_waves = gridDim.x * (blockDim.x >> 6);
+    float thc[CW64];
+#pragma unroll
+    for (int u = 0; u < CW64; ++u) thc[u] = tau ? tau[u * 64 + lane] : 0.0f;
     float th[kItemsPerWave];
 #pragma unroll
-    for (int u = 0; u < kItemsPerWave; ++u) th[u] = tau ? tau[(u & (Cw64 - 1)) * 64 + lane] : 0.0f;
+    for (int u = 0; u < kItemsPerWave; ++u) th[u] = thc[u & (CW64 - 1)];
 
     // full batches: the loads of the next batch are issued before the current one is balloted
     const int step = n_waves * kItemsPerWave;
@@ -279,10 +285,19 @@ int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, i
         // sixteen consecutive items start at a multiple of sixteen, so the channel group of item u
         // of a batch is u mod Cw64 whenever Cw64 divides sixteen
         const bool periodic = Cw64 <= kItemsPerWave && (Cw64 & (Cw64 - 1)) == 0;
-        if (periodic && C % 64 == 0)
-            hipLaunchKernelGGL(pack_act_nhwc_aligned_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
-                               X, tau, A_packed, static_cast<int>(n_items), Cw64);
-        else if (periodic)
+        if (periodic && C % 64 == 0) {
+#define DAB_PACK_ALIGNED(N)                                                                                       \
+    hipLaunchKernelGGL(pack_act_nhwc_aligned_kernel<N>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, X, tau, \
+                       A_packed, static_cast<int>(n_items))
+            switch (Cw64) {
+                case 1: DAB_PACK_ALIGNED(1); break;
+                case 2: DAB_PACK_ALIGNED(2); break;
+                case 4: DAB_PACK_ALIGNED(4); break;
+                case 8: DAB_PACK_ALIGNED(8); break;
+                default: DAB_PACK_ALIGNED(16); break;
+            }
+#undef DAB_PACK_ALIGNED
+        } else if (periodic)
             hipLaunchKernelGGL(pack_act_nhwc_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
                                X, tau, A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
         else
