@@ -9,8 +9,8 @@ packing, activation bit packing and the binary convolution / fully-connected pro
 fp32 inputs of all layers and the fp32 weights are resident in HBM before the timed region.
 
 A step is launched as one captured HIP graph: the weight sides of all layers (they depend on
-no activation) run first on side streams, then each layer packs its activations and runs its
-product on the main stream.  The timed region is K graph launches.
+no activation) run on side streams while the main stream packs the activations of all layers;
+the products follow, alternating over two streams.  The timed region is K graph launches.
 
 Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
 call (the binary product of the largest layer) from HIP-event timings of an eager pass over
@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
     ap.add_argument("--cpu-batch", type=int, default=256, help="images of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--product-streams", type=int, default=2,
+                    help="streams the binary products alternate over (1 = all on the main stream)")
     ap.add_argument("--side-streams", type=int, default=2,
                     help="HIP streams for the weight side (estimation + weight packing) of the layers; 0 = one stream")
     ap.add_argument("--no-graph", action="store_true",
@@ -125,17 +127,21 @@ class Schedule:
 
     The weight side of a layer (estimation, weight packing) depends on no activation, so the
     weight sides run on side streams (longest first, spread by sort work) while the current
-    stream packs the activations of all layers and then goes layer by layer through the binary
-    products; a product waits for its own layer's weights only (an event per layer), so the
-    weight sides of later layers run beside the products of earlier ones.  A step forks from and joins back into the
-    current stream, so steps never overlap, and the whole step can be captured into one HIP
-    graph.
+    stream packs the activations of all layers (every input is resident when the step starts;
+    memory-bound work beside the LDS-bound estimation).  The binary products then alternate
+    between the current stream and one more: a product waits for its own layer's weights only
+    (an event per layer), so the weight sides of later layers run beside the products of earlier
+    ones, and with two product streams the prepare kernel of the next layer runs beside the
+    main kernel of this one, whose last workgroups hand their compute units straight to the next
+    main kernel.  A step forks from and joins back into the current stream, so steps never
+    overlap, and the whole step can be captured into one HIP graph.
     """
 
-    def __init__(self, states, n_side, torch, per_layer=True, acts_first=True):
+    def __init__(self, states, n_side, torch, per_layer=True, n_product=2):
         self.torch = torch
         self.states = states
         self.side = [torch.cuda.Stream() for _ in range(n_side)]
+        self.extra = [torch.cuda.Stream() for _ in range(max(n_product, 1) - 1)] if n_side > 0 else []
         # longest-processing-time assignment by sort work F * n; layer order kept inside a stream
         load = [0.0] * max(n_side, 1)
         self.assign = [[] for _ in range(max(n_side, 1))]
@@ -146,23 +152,23 @@ class Schedule:
         for a in self.assign:
             a.sort()
         self.fork = torch.cuda.Event()
+        self.packed = torch.cuda.Event()
         self.ready = [torch.cuda.Event() for _ in self.side]
+        self.joined = [torch.cuda.Event() for _ in self.extra]
         self.layer_ready = [torch.cuda.Event() for _ in states]
         self.per_layer = per_layer
-        self.acts_first = acts_first
 
-    def step(self, dab, events=None):
+    def step(self, dab):
         torch, states = self.torch, self.states
         if not self.side:
-            for i, s in enumerate(states):
-                run_layer(s, dab, None if events is None else events[i])
+            for s in states:
+                run_layer(s, dab)
             return
         main = torch.cuda.current_stream()
         self.fork.record(main)
         # the main stream's first kernel is enqueued (and captured) before the side work, so that a
         # graph launch starts the main chain at once instead of behind the longest weight side
         activation_side(states[0], dab)
-        first = 1 if self.acts_first else len(states)
         for q, idxs, done in zip(self.side, self.assign, self.ready):
             q.wait_event(self.fork)
             with torch.cuda.stream(q):
@@ -171,27 +177,27 @@ class Schedule:
                     if self.per_layer:
                         self.layer_ready[i].record(q)
             done.record(q)
-        # every layer's input is resident when the step starts, so all activations are packed while
-        # the weight sides are still estimating (memory-bound work beside LDS-bound work); the
-        # products then follow each other without a packing kernel between them
-        for s in states[first:]:
+        for s in states[1:]:
             activation_side(s, dab)
-        for i, s in enumerate(states):
-            if 0 < i < first:
-                activation_side(s, dab)
-            if self.per_layer:
-                main.wait_event(self.layer_ready[i])
-            elif i == 0:
+        self.packed.record(main)
+        streams = [main] + self.extra
+        for q in self.extra:
+            q.wait_event(self.packed)
+        if not self.per_layer:
+            for q in streams:
                 for done in self.ready:
-                    main.wait_event(done)
-            if events is not None:
-                events[i][0].record()
-            product(s, dab)
-            if events is not None:
-                events[i][1].record()
-        if self.per_layer:
-            for done in self.ready:
-                main.wait_event(done)
+                    q.wait_event(done)
+        for i, s in enumerate(states):
+            q = streams[i % len(streams)]
+            if self.per_layer:
+                q.wait_event(self.layer_ready[i])
+            with torch.cuda.stream(q):
+                product(s, dab)
+        for q, done in zip(self.extra, self.joined):
+            done.record(q)
+            main.wait_event(done)
+        for done in self.ready:
+            main.wait_event(done)
 
     def capture(self, dab):
         """The step as one HIP graph (kernel launches and stream dependencies only)."""
@@ -438,7 +444,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    sched = Schedule(states, args.side_streams, torch, per_layer=not args.wait_all)
+    sched = Schedule(states, args.side_streams, torch, per_layer=not args.wait_all, n_product=args.product_streams)
     for _ in range(args.warmup):
         sched.step(dab)
     torch.cuda.synchronize()
@@ -559,7 +565,7 @@ def main():
         "config": {"workload": "config 3: Sketch-A-Net binarized trunk (conv2-conv6, fc7), batch %d, "
                                "estimate + pack weights + pack activations + binary product per layer" % args.batch,
                    "batch": args.batch, "binary_macs_per_step": total_macs,
-                   "streams": 1 + args.side_streams,
+                   "streams": 1 + args.side_streams + (max(args.product_streams, 1) - 1 if args.side_streams else 0),
                    "launch": "eager" if args.no_graph else "one captured HIP graph per step",
                    "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
                    "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
