@@ -164,14 +164,20 @@ __global__ __launch_bounds__(256) void pack_act_nchw_kernel(const float* __restr
 // of up to 24K weights, so most layers need one pass.
 constexpr int kWeightSlabFloats = 24 * 1024;   // 96 KB
 
-__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ Wt, const float* __restrict__ thr_val,
+__global__ __launch_bounds__(1024) void pack_weights_kernel(const float* __restrict__ Wt, const float* __restrict__ thr_val,
                                                            const int32_t* __restrict__ thr_idx,
                                                            const uint8_t* __restrict__ alpha_is_upper,
                                                            uint32_t* __restrict__ E, uint32_t* __restrict__ ecnt,
                                                            int F, int C, int T, int Cw, int Fp, int slab_c) {
     extern __shared__ __align__(16) float slab[];
     __shared__ uint32_t cnt[128];            // per-tap counts, T <= 128 taps (checked on the host)
-    const int f = blockIdx.x;
+    // Workgroups go round-robin over the eight XCDs, and a column of E is one 4-byte word per
+    // row: neighbouring filters share cache lines.  Filters are dealt out so that an XCD owns a
+    // contiguous range of them, and the partial lines merge in that XCD's L2 instead of reaching
+    // memory as 4-byte writes from eight L2s.
+    const int per_xcd = (Fp + kNumXCD - 1) / kNumXCD;
+    const int f = static_cast<int>(blockIdx.x % kNumXCD) * per_xcd + static_cast<int>(blockIdx.x / kNumXCD);
+    if (blockIdx.x / kNumXCD >= static_cast<unsigned>(per_xcd) || f >= Fp) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
     const int R = T * Cw;
     if (f >= F) {                            // padding column: all zero
@@ -196,8 +202,21 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
         float* sl = slab + mis;
         __syncthreads();
         if (tid < head) sl[tid] = src[tid];
-        for (int q = tid; q < body4; q += blockDim.x)
-            *reinterpret_cast<float4*>(sl + head + 4 * q) = *reinterpret_cast<const float4*>(src + head + 4 * q);
+        // eight loads in flight per thread (a plain copy loop waits for every load in turn, and a
+        // 12544-weight filter is 13 round trips per thread)
+        for (int q0 = tid; q0 < body4; q0 += 8 * blockDim.x) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = min(q0 + u * static_cast<int>(blockDim.x), body4 - 1);   // the tail re-reads the last piece
+                v[u] = *reinterpret_cast<const float4*>(src + head + 4 * q);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * blockDim.x;
+                if (q < body4) *reinterpret_cast<float4*>(sl + head + 4 * q) = v[u];
+            }
+        }
         for (int i = head + 4 * body4 + tid; i < count; i += blockDim.x) sl[i] = src[i];
         __syncthreads();
         const int groups = (nc + 63) >> 6;                 // 64-channel groups in this slab
@@ -336,7 +355,10 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
         if (e != hipSuccess) return hip_failed(e);
         granted = lds;
     }
-    hipLaunchKernelGGL(pack_weights_kernel, dim3(Fp), dim3(256), lds, static_cast<hipStream_t>(stream),
+    // the (tap, 64-channel group) items of a filter are spread over the wavefronts of its workgroup:
+    // long filters get sixteen of them
+    const int threads = 1ll * C * T >= 8192 ? 1024 : 256;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(kNumXCD * ceil_div(Fp, kNumXCD)), dim3(threads), lds, static_cast<hipStream_t>(stream),
                        W, thr_val, thr_idx, alpha_is_upper, E_packed, ecnt, F, C, T, Cw, Fp, slab_c);
     return launch_status();
 }
