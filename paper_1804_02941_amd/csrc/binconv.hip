@@ -242,29 +242,39 @@ __global__ __launch_bounds__(256) void wbin_prepare_kernel(const MfmaGeom g, con
                                                            uint4* __restrict__ E16, float* __restrict__ pixsum,
                                                            int32_t* __restrict__ ktab, float* __restrict__ sA) {
     DAB_RESERVE_VGPRS();
+    __shared__ float xt[32][65];                                   // 32 pixels x 64 channels, padded rows
     unsigned blk = blockIdx.x;
     if (blk < g.blk_act) {
-        const long long i = 1ll * blk * 256 + threadIdx.x;
-        if (i >= 1ll * g.npix * 2 * g.C16) return;
-        const int g8 = static_cast<int>(i / g.npix);                // 8-channel group
-        const int pp = static_cast<int>(i - 1ll * g8 * g.npix);     // padded pixel (fastest: coalesced stores)
-        const int b = fdiv(pp, g.d_HpWp);
-        const int r = pp - b * g.Hp * g.Wp;
-        const int yp = fdiv(r, g.d_Wp);
-        const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
-        float v[8];
+        // A block takes 32 padded pixels x 64 channels.  Its threads read the fp32 values along the
+        // channels (256 contiguous bytes per pixel), turn the tile through LDS, and write the bf16
+        // pieces along the pixels (512 contiguous bytes per plane and half-wavefront).
+        const int n_ct = (g.C16 + 3) >> 2;                          // 64-channel tiles
+        const int pt = static_cast<int>(blk) / n_ct;
+        const int ct = static_cast<int>(blk) - pt * n_ct;
+        const int tid = threadIdx.x;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] = 0.0f;
-        if (y >= 0 && y < g.H && x >= 0 && x < g.W) {
-            const float* src = X + ((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.C + g8 * 8;
-#pragma unroll
-            for (int c = 0; c < 8; ++c)
-                if (g8 * 8 + c < g.C) v[c] = src[c];
+        for (int k = 0; k < 8; ++k) {
+            const int e = tid + k * 256;                            // element of the tile: pixel e / 64, channel e % 64
+            const int pl = e >> 6, cl = e & 63;
+            const int pp = pt * 32 + pl, c = ct * 64 + cl;
+            float v = 0.0f;
+            if (pp < g.npix && c < g.C) {
+                const int b = fdiv(pp, g.d_HpWp);
+                const int r = pp - b * g.Hp * g.Wp;
+                const int yp = fdiv(r, g.d_Wp);
+                const int y = yp - g.ph, x = r - yp * g.Wp - g.pw;
+                if (y >= 0 && y < g.H && x >= 0 && x < g.W) v = X[((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.C + c];
+            }
+            xt[pl][cl] = v;
         }
+        __syncthreads();
+        const int pl = tid & 31, gl = tid >> 5;                     // pixel of the tile, 8-channel group of the tile
+        const int pp = pt * 32 + pl, g8 = ct * 8 + gl;
+        if (pp >= g.npix || g8 >= 2 * g.C16) return;
         uint32_t piece[3][8];
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            float rest = v[c];
+            float rest = xt[pl][gl * 8 + c];
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
                 piece[p][c] = bf16_bits(rest);
@@ -336,25 +346,34 @@ __global__ __launch_bounds__(256) void wbin_prepare_kernel(const MfmaGeom g, con
     }
     blk -= g.blk_tab;
     {
-        // small layers only: the window sum of every output pixel, one wavefront per pixel, lanes
-        // along the channels of a tap
-        const int m = static_cast<int>(blk * 4 + (threadIdx.x >> 6));
-        if (m >= g.M) return;
-        const int lane = threadIdx.x & 63;
+        // small layers only: the window sum of every output pixel, one workgroup per pixel; a row of
+        // the window is kw*C contiguous values, read four batches deep
+        __shared__ double part[4];
+        const int m = static_cast<int>(blk);
+        const int tid = threadIdx.x;
         const int b = fdiv(m, g.d_HoWo);
         const int r = m - b * g.HoWo;
         const int oy = fdiv(r, g.d_Wo);
         const int ox = r - oy * g.Wo;
+        const int x0 = max(ox * g.sw - g.pw, 0), x1 = min(ox * g.sw - g.pw + g.kw, g.W);
+        const int len = (x1 - x0) * g.C;
         double acc = 0.0;
-        for (int tap = 0; tap < g.T; ++tap) {
-            const int ky = fdiv(tap, g.d_kw);
-            const int y = oy * g.sh - g.ph + ky, x = ox * g.sw - g.pw + (tap - ky * g.kw);
-            if (y < 0 || y >= g.H || x < 0 || x >= g.W) continue;
-            const float* src = X + ((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.C;
-            for (int c = lane; c < g.C; c += 64) acc += static_cast<double>(src[c]);
+        for (int ky = 0; ky < g.kh; ++ky) {
+            const int y = oy * g.sh - g.ph + ky;
+            if (y < 0 || y >= g.H) continue;
+            const float* src = X + ((static_cast<size_t>(b) * g.H + y) * g.W + x0) * g.C;
+            for (int i0 = tid; i0 < len; i0 += 4 * 256) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = src[min(i0 + u * 256, len - 1)];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc += i0 + u * 256 < len ? static_cast<double>(v[u]) : 0.0;
+            }
         }
         for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
-        if (lane == 0) sA[m] = static_cast<float>(acc);
+        if ((tid & 63) == 0) part[tid >> 6] = acc;
+        __syncthreads();
+        if (tid == 0) sA[m] = static_cast<float>((part[0] + part[1]) + (part[2] + part[3]));
     }
 }
 
@@ -524,13 +543,6 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             if (nchunks > 1) {
                 __syncthreads();                                   // previous users of the panel are done
                 stage_panel(ks0, ks1, steps);
-                __builtin_amdgcn_s_waitcnt(0);                     // every counter to zero: the copies have landed
-                __syncthreads();
-            } else if (!staged) {
-                // the copies were issued before the first tile's address work and row sums
-                __builtin_amdgcn_s_waitcnt(0);
-                __syncthreads();
-                staged = true;
             }
             // A fragments: a queue of kPrefetch k-steps per row block, refilled as it drains.  The
             // byte offset of a k-step comes from the table the prepare kernel wrote (four per
@@ -541,7 +553,8 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             };
             // Slot d of the queue holds the fragments of step st + d; the slot emptied by the previous
             // step is refilled during this one (kPrefetch - 1 steps ahead), so a register is never
-            // live as both a pending load and an operand and the loop carries no copies.
+            // live as both a pending load and an operand and the loop carries no copies.  The first
+            // fragments are requested before the wait for the panel, so both latencies overlap.
             const int* kt = ktab + ks0;
             v4i abuf[kPrefetch][2];
 #pragma unroll
@@ -549,6 +562,15 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                 const int p = kt[d];
 #pragma unroll
                 for (int i = 0; i < 2; ++i) abuf[d][i] = load_a(i, p);
+            }
+            if (nchunks > 1) {
+                __builtin_amdgcn_s_waitcnt(0);                     // every counter to zero: the copies have landed
+                __syncthreads();
+            } else if (!staged) {
+                // the copies were issued before the first tile's address work and row sums
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+                staged = true;
             }
             const uint4* bp = panel + lane;
             uint4 bq[2][4];
@@ -968,15 +990,15 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl, bool wbin = false)
     g.blk_tab = static_cast<unsigned>((g.nk + kTabPad + 255) / 256);
     g.blk_sa = (pl->split || pl->small) ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
     if (wbin) {
-        // block ranges of wbin_prepare_kernel: one thread per (8-channel group, padded pixel), per
-        // 16-byte weight fragment, per padded pixel, per table entry
-        g.blk_act = static_cast<unsigned>((1ll * g.npix * 2 * g.C16 + 255) / 256);
+        // block ranges of wbin_prepare_kernel: a block per 32 pixels x 64 channels, a thread per 16-byte
+        // weight fragment, lanes per padded pixel, a thread per table entry, a block per output pixel
+        g.blk_act = static_cast<unsigned>(ceil_div(g.npix, 32)) * static_cast<unsigned>(ceil_div(g.C16, 4));
         g.blk_wgt = static_cast<unsigned>((1ll * g.n_ntiles * g.nb * 256 + 255) / 256);
         g.sum_shift = 0;
         while (g.sum_shift < 6 && (16 << g.sum_shift) < d.C) ++g.sum_shift;
         // the small kernel takes the window sums of the sA pass, not the per-pixel sums
         g.blk_sum = pl->small ? 0u : static_cast<unsigned>((1ll * g.npix * (1 << g.sum_shift) + 255) / 256);
-        g.blk_sa = pl->small ? static_cast<unsigned>((g.M + 3) / 4) : 0u;
+        g.blk_sa = pl->small ? static_cast<unsigned>(g.M) : 0u;
     }
     return DAB_OK;
 }
