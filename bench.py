@@ -40,7 +40,7 @@ VALU_PAIR_MACS = 256 * 64 * 2.4e9 * 16
 HBM_BYTES_PER_S = 8.0e12
 # HBM bytes of one conv2 call at batch 256 (prepare + main kernel), from the FETCH_SIZE and WRITE_SIZE
 # counter runs summarised in profiles/bench_config3_hbm_counters.md
-CONV2_CALL_HBM_BYTES = 157115504
+CONV2_CALL_HBM_BYTES = 157136400
 
 
 def parse():
