@@ -333,15 +333,24 @@ __global__ __launch_bounds__(256) void wbin_prepare_kernel(const MfmaGeom g, con
     }
     blk -= g.blk_sum;
     if (blk < g.blk_tab) {
-        // byte offset of every k-step: steps run (16-channel group, piece) slowest, taps fastest
+        // byte offset of every k-step: steps run (16-channel group, tap, piece), pieces fastest, so
+        // three consecutive steps share one B fragment; then the window's pixel offsets (times 16)
         const int i = static_cast<int>(blk * 256 + threadIdx.x);
-        if (i >= g.nk + kTabPad) return;
+        if (i >= g.nk + kTabPad + g.T) return;
+        if (i >= g.nk + kTabPad) {
+            const int tap = i - (g.nk + kTabPad);
+            const int ky = fdiv(tap, g.d_kw);
+            ktab[i] = (ky * g.Wp + (tap - ky * g.kw)) * 16;
+            return;
+        }
         const int ks = min(i, g.nk - 1);
-        const int kb = fdiv(ks, g.d_T);
-        const int tap = ks - kb * g.T;
+        const int bs = fdiv(ks, g.d_3);
+        const int piece = ks - 3 * bs;
+        const int c16 = fdiv(bs, g.d_T);
+        const int tap = bs - c16 * g.T;
         const int ky = fdiv(tap, g.d_kw);
         const int kx = tap - ky * g.kw;
-        ktab[i] = kb * 2 * g.plane + (ky * g.Wp + kx) * 16;
+        ktab[i] = (c16 * 3 + piece) * 2 * g.plane + (ky * g.Wp + kx) * 16;
         return;
     }
     blk -= g.blk_tab;
@@ -421,6 +430,11 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
                                                                   uint32_t* __restrict__ out_bits) {
     constexpr int THREADS = 64 * WAVES;
     constexpr int MTILE = 64 * WAVES;
+    // k-steps per B step: the three bf16 pieces of an input share the fragments of their 16-channel
+    // group and tap, so a panel entry serves three consecutive k-steps; depth of the A queue
+    constexpr int PIECES = KIND == kBf16 ? 3 : 1;
+    constexpr int QD = KIND == kBf16 ? 6 : kPrefetch;
+    constexpr int EPQ = QD / PIECES;                               // panel entries per queue round
     extern __shared__ __align__(16) uint4 panel[];                 // [kchunk][4][64 lanes] 16-byte groups
     __shared__ __align__(16) float sA_lds[WAVES][64];              // row sums of each wavefront's 64 pixels
 
@@ -441,7 +455,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         mt_first = blockIdx.x - ntile * g.wg_per_ntile;
         mt_step = g.wg_per_ntile;
         kbeg = 0;
-        kend = g.nk;
+        kend = g.nb;                                               // chunks are counted in B steps (fp4: nb = nk)
     }
     const int f0 = ntile * kNTile;
     const uint4* Epanel = E4 + static_cast<size_t>(ntile) * g.nb * 256;
@@ -471,22 +485,15 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         for (int i = wave; i < nkb; i += WAVES) {
             int kb = i + rot;
             kb = kb >= nkb ? kb - nkb : kb;
-            int bs = ks0 + (kb >> 2);                              // B step of this k-step
-            if (KIND == kBf16) {
-                // k-steps run (16-channel group, piece, tap); the three pieces share the group's fragments
-                const int kbp = fdiv(bs, g.d_T);
-                bs = fdiv(kbp, g.d_3) * g.T + (bs - kbp * g.T);
-            }
-            __builtin_amdgcn_global_load_lds(Epanel + static_cast<size_t>(bs) * 256 + (kb & 3) * 64 + lane,
-                                             panel + kb * 64, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(Epanel + static_cast<size_t>(ks0) * 256 + kb * 64 + lane, panel + kb * 64, 16,
+                                             0, 0);
         }
         for (int e = nkb * 64 + tid; e < steps * 256; e += THREADS) panel[e] = make_uint4(0, 0, 0, 0);
     };
     // A reduction that fits in LDS is staged once, and its copies are issued first of all so that
     // they fly while the first tile's addresses and row sums are worked out.
     bool staged = false;
-    if (nchunks == 1 && mt_first < g.n_mtiles)
-        stage_panel(kbeg, kend, (kend - kbeg + kPrefetch - 1) / kPrefetch * kPrefetch);
+    if (nchunks == 1 && mt_first < g.n_mtiles) stage_panel(kbeg, kend, (kend - kbeg + EPQ - 1) / EPQ * EPQ);
     for (int mt = mt_first; mt < g.n_mtiles; mt += mt_step) {
         const int m_base = mt * MTILE + wave * 64;
         int pixoff[2], mypix = 0;
@@ -508,10 +515,11 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         if (KIND == kBf16) {
             // weights-only layer: the per-pixel sums are fp32 sums of the real inputs
             const float* psum = reinterpret_cast<const float*>(pixsum);
+            const int32_t* wtab = ktab + g.nk + kTabPad;            // the window's pixel offsets, times 16
             for (int t0 = 0; t0 < g.T; t0 += 32) {
                 float v[32];
 #pragma unroll
-                for (int u = 0; u < 32; ++u) v[u] = psum[mypix + (ktab[min(t0 + u, g.T - 1)] >> 4)];
+                for (int u = 0; u < 32; ++u) v[u] = psum[mypix + (wtab[min(t0 + u, g.T - 1)] >> 4)];
 #pragma unroll
                 for (int u = 0; u < 32; ++u) rowsum += t0 + u < g.T ? v[u] : 0.0f;
             }
@@ -537,28 +545,29 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
         for (int chunk = 0; chunk < nchunks; ++chunk) {
             const int ks0 = kbeg + chunk * g.kchunk;
             const int ks1 = min(kend, ks0 + g.kchunk);
-            // k-steps of this chunk rounded up to the prefetch depth; the extra steps multiply
-            // zero B fragments (and re-read the last valid A fragment), so the loop has no tail
-            const int steps = (ks1 - ks0 + kPrefetch - 1) / kPrefetch * kPrefetch;
+            // panel entries of this chunk rounded up to a queue round; the extra k-steps multiply
+            // zero B fragments (and read some valid A fragment), so the loop has no tail
+            const int ent = (ks1 - ks0 + EPQ - 1) / EPQ * EPQ;
+            const int steps = ent * PIECES;
             if (nchunks > 1) {
                 __syncthreads();                                   // previous users of the panel are done
-                stage_panel(ks0, ks1, steps);
+                stage_panel(ks0, ks1, ent);
             }
-            // A fragments: a queue of kPrefetch k-steps per row block, refilled as it drains.  The
-            // byte offset of a k-step comes from the table the prepare kernel wrote (four per
-            // scalar load); steps past the end re-read the last fragment against zero B fragments.
+            // A fragments: a queue of QD k-steps per row block, refilled as it drains.  The byte
+            // offset of a k-step comes from the table the prepare kernel wrote (four per scalar
+            // load); steps past the end read a valid fragment against zero B fragments.
             auto load_a = [&](int i, int poff) -> v4i {
                 const auto v = __builtin_amdgcn_raw_buffer_load_b128(a4rsrc, pixoff[i], poff, 0);
                 return v4i{static_cast<int>(v[0]), static_cast<int>(v[1]), static_cast<int>(v[2]), static_cast<int>(v[3])};
             };
             // Slot d of the queue holds the fragments of step st + d; the slot emptied by the previous
-            // step is refilled during this one (kPrefetch - 1 steps ahead), so a register is never
-            // live as both a pending load and an operand and the loop carries no copies.  The first
+            // step is refilled during this one (QD - 1 steps ahead), so a register is never live as
+            // both a pending load and an operand and the loop carries no copies.  The first
             // fragments are requested before the wait for the panel, so both latencies overlap.
-            const int* kt = ktab + ks0;
-            v4i abuf[kPrefetch][2];
+            const int* kt = ktab + ks0 * PIECES;
+            v4i abuf[QD][2];
 #pragma unroll
-            for (int d = 0; d < kPrefetch - 1; ++d) {
+            for (int d = 0; d < QD - 1; ++d) {
                 const int p = kt[d];
 #pragma unroll
                 for (int i = 0; i < 2; ++i) abuf[d][i] = load_a(i, p);
@@ -576,27 +585,35 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_mfma_kernel(const MfmaGeom
             uint4 bq[2][4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) bq[0][j] = bp[j * 64];
-            for (int st = 0; st < steps; st += kPrefetch) {
+            int e0 = 0;                                            // panel entry of step st
+            for (int st = 0; st < steps; st += QD, e0 += EPQ) {
 #pragma unroll
-                for (int d = 0; d < kPrefetch; ++d) {
-                    // B fragments of the next step are read while this step multiplies
-                    const uint4* bn = bp + static_cast<size_t>(min(st + d + 1, steps - 1)) * 256;
+                for (int d = 0; d < QD; ++d) {
+                    constexpr int kAhead = QD - 1;
+                    const int eb = d / PIECES;                     // entry of this step within the round
+                    if (d % PIECES == 0) {
+                        // B fragments of the next entry are read while this one multiplies
+                        const uint4* bn = bp + static_cast<size_t>(min(e0 + eb + 1, ent - 1)) * 256;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) bq[(d + 1) & 1][j] = bn[j * 64];
-                    constexpr int kAhead = kPrefetch - 1;
+                        for (int j = 0; j < 4; ++j) bq[(eb + 1) & 1][j] = bn[j * 64];
+                    }
                     const int p = kt[st + d + kAhead];
-                    abuf[(d + kAhead) % kPrefetch][0] = load_a(0, p);
-                    abuf[(d + kAhead) % kPrefetch][1] = load_a(1, p);
+                    abuf[(d + kAhead) % QD][0] = load_a(0, p);
+                    abuf[(d + kAhead) % QD][1] = load_a(1, p);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint4 bu = bq[d & 1][j];
+                        const uint4 bu = bq[eb & 1][j];
                         const v4i bv = {static_cast<int>(bu.x), static_cast<int>(bu.y), static_cast<int>(bu.z),
                                         static_cast<int>(bu.w)};
                         acc[0][j] = mfma_step<KIND>(abuf[d][0], bv, acc[0][j]);
                         acc[1][j] = mfma_step<KIND>(abuf[d][1], bv, acc[1][j]);
                     }
                     // issue order of this k-step: every memory instruction in the shadow of an MFMA
-                    DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS();
+                    if (d % PIECES == 0) {
+                        DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS(); DAB_SLOT_DS();
+                    } else {
+                        DAB_SLOT_NONE(); DAB_SLOT_NONE(); DAB_SLOT_NONE(); DAB_SLOT_NONE();
+                    }
                     DAB_SLOT_VMEM(); DAB_SLOT_NONE(); DAB_SLOT_VMEM(); DAB_SLOT_NONE();
                 }
             }
@@ -728,12 +745,20 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
     const int mb = fdiv(blockIdx.x, g.d_fblocks);
     const int fb = blockIdx.x - mb * g.n_fblocks;                   // neighbouring workgroups share the pixel rows
     const uint4* Eb = E4 + static_cast<size_t>(fb >> 2) * g.nb * 256 + (fb & 3) * 64 + lane;
-    // B step of a k-step: the same index, or (weights-only layer) the 16-channel group's fragment
-    // shared by its three pieces
-    auto b_step = [&](int ks) -> int {
-        if (KIND == kFp4) return ks;
-        const int kbp = fdiv(ks, g.d_T);
-        return fdiv(kbp, g.d_3) * g.T + (ks - kbp * g.T);
+    // This kernel walks the reduction with the taps of one plane fastest (neighbouring taps share
+    // cache lines).  For fp4 that is the order of the offset table; the weights-only layer's table
+    // runs (16-channel group, tap, piece), so its step s = (group * 3 + piece) * T + tap is mapped
+    // to the table entry and to the B fragment the three pieces share.
+    auto table_step = [&](int s) -> int {
+        if (KIND == kFp4) return s;
+        const int kbp = fdiv(s, g.d_T);
+        const int c16 = fdiv(kbp, g.d_3);
+        return (c16 * g.T + (s - kbp * g.T)) * 3 + (kbp - 3 * c16);
+    };
+    auto b_step = [&](int s) -> int {
+        if (KIND == kFp4) return s;
+        const int kbp = fdiv(s, g.d_T);
+        return fdiv(kbp, g.d_3) * g.T + (s - kbp * g.T);
     };
     const __amdgpu_buffer_rsrc_t a4rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(A4), 0, 2 * g.KB * g.plane, 0x00020000);
@@ -771,7 +796,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_small_kernel(
     uint4 bq[2][kSmallDepth];
     auto fetch = [&](int set, int first) {
 #pragma unroll
-        for (int d = 0; d < kSmallDepth; ++d) aq[set][d] = load_a(ktab[min(first + d, klast)]);
+        for (int d = 0; d < kSmallDepth; ++d) aq[set][d] = load_a(ktab[table_step(min(first + d, klast))]);
 #pragma unroll
         for (int d = 0; d < kSmallDepth; ++d) bq[set][d] = Eb[static_cast<size_t>(b_step(min(first + d, klast))) * 256];
     };
@@ -952,9 +977,11 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl, bool wbin = false)
         g.ksplit = 1;
         g.split_steps = g.nk;
     }
-    const int span = pl->split ? g.split_steps : g.nk;
+    // chunks of the LDS panel, in B steps (the weights-only layer has a third as many as k-steps)
+    const int span = pl->split ? g.split_steps : g.nb;
     const int nchunks = ceil_div(span, kMaxChunk);
-    g.kchunk = ceil_div(ceil_div(span, nchunks), kPrefetch) * kPrefetch;
+    const int round = wbin ? 2 : kPrefetch;                        // panel entries per round of the A queue
+    g.kchunk = ceil_div(ceil_div(span, nchunks), round) * round;
     g.n_mtiles = ceil_div(g.M, 64 * pl->waves);
     g.wg_per_ntile = kNumCU / g.n_ntiles;
     if (g.wg_per_ntile < 1) g.wg_per_ntile = 1;
@@ -972,7 +999,7 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl, bool wbin = false)
     pl->a4_bytes = round256(static_cast<size_t>(a4));
     pl->e4_bytes = static_cast<size_t>(g.n_ntiles) * g.nb * 4096;
     pl->sa_bytes = round256(static_cast<size_t>(g.M) * 4) + round256(static_cast<size_t>(g.npix) * 4) +
-                   round256(static_cast<size_t>(g.nk + kTabPad) * 4);
+                   round256(static_cast<size_t>(g.nk + kTabPad + g.T) * 4);
     pl->s1_bytes = pl->split ? round256(static_cast<size_t>(g.ksplit) * g.M * d.F * 4) : 0;
     pl->ws_bytes = pl->a4_bytes + pl->e4_bytes + pl->sa_bytes + pl->s1_bytes;
     pl->lds_bytes = static_cast<size_t>(g.kchunk) * 4096;
@@ -997,6 +1024,7 @@ static int plan_binconv(const dab_conv_desc& d, MfmaPlan* pl, bool wbin = false)
         g.sum_shift = 0;
         while (g.sum_shift < 6 && (16 << g.sum_shift) < d.C) ++g.sum_shift;
         // the small kernel takes the window sums of the sA pass, not the per-pixel sums
+        g.blk_tab = static_cast<unsigned>((g.nk + kTabPad + g.T + 255) / 256);
         g.blk_sum = pl->small ? 0u : static_cast<unsigned>((1ll * g.npix * (1 << g.sum_shift) + 255) / 256);
         g.blk_sa = pl->small ? static_cast<unsigned>(g.M) : 0u;
     }
