@@ -33,13 +33,36 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
     return __uint_as_float(k ^ ((k >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
-template <typename T>
-__device__ __forceinline__ T wave_inclusive_scan(T v, int lane) {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const T o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
-    }
+// The scans over a wavefront sit on the critical path between two barriers (the 32-bit one once
+// per sort pass), so they use data-parallel-primitive moves (register to register, no LDS crossbar round trips): shifts
+// by 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add 0), then lane 15 of row 0
+// and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t v) {
+    return v + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+    return v + __hiloint2double(hi, lo);                   // lanes without a source add +0.0
+}
+__device__ __forceinline__ double wave_inclusive_scan_f64(double v) {
+    v = dpp_add<0x111, 0xf>(v);
+    v = dpp_add<0x112, 0xf>(v);
+    v = dpp_add<0x114, 0xf>(v);
+    v = dpp_add<0x118, 0xf>(v);
+    v = dpp_add<0x142, 0xa>(v);
+    v = dpp_add<0x143, 0xc>(v);
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
+    v = dpp_add<0x111, 0xf>(v);   // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);   // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);   // row_shr:8
+    v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
@@ -107,7 +130,7 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
         uint32_t run = 0;
 #pragma unroll
         for (int w = 0; w < 8; ++w) { const uint32_t t = c[w]; c[w] = run; run += t; }
-        const uint32_t inc = wave_inclusive_scan(run, lane);
+        const uint32_t inc = wave_inclusive_scan_u32(run);
         if (lane == 63) wave_tot[wave] = inc;
         __syncthreads();
         uint32_t base = inc - run, all = 0;
@@ -141,7 +164,7 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
         x[j] = lo + j < hi ? static_cast<double>(key_to_float(keys[lo + j])) : 0.0;
         local += x[j];
     }
-    const double inc = wave_inclusive_scan(local, lane);
+    const double inc = wave_inclusive_scan_f64(local);
     if (lane == 63) wave_sum[wave] = inc;
     __syncthreads();
     double base = inc - local;
@@ -214,7 +237,7 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     const uint32_t r = static_cast<uint32_t>(r_s);
     uint32_t cnt = 0;
     for (int i = lo; i < hi; ++i) cnt += (row[i] == tv) ? 1u : 0u;
-    const uint32_t cinc = wave_inclusive_scan(cnt, lane);
+    const uint32_t cinc = wave_inclusive_scan_u32(cnt);
     if (lane == 63) wave_tot[wave] = cinc;
     __syncthreads();
     uint32_t cbase = cinc - cnt;
