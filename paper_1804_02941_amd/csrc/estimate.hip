@@ -140,16 +140,18 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
             if (w < wave) base += t;
             all += t;
         }
+        // keys with digits 0..7 precede digits 8..15: their total goes into the high halves here,
+        // so the scatter only picks a half
+        base += (all & 0xFFFFu) << 16;
         *reinterpret_cast<uint4*>(&counters[tid * 8]) = make_uint4(c[0] + base, c[1] + base, c[2] + base, c[3] + base);
         *reinterpret_cast<uint4*>(&counters[tid * 8 + 4]) = make_uint4(c[4] + base, c[5] + base, c[6] + base, c[7] + base);
         __syncthreads();
-        const uint32_t low_total = all & 0xFFFFu;                  // keys with digits 0..7 precede digits 8..15
         // every thread holds its keys in registers, so the buffer can be overwritten in place
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             const uint32_t d = (k[j] >> shift) & 15u;
             const uint32_t word = counters[(d & 7u) * THREADS + tid];
-            const uint32_t off = d < 8u ? (word & 0xFFFFu) : (word >> 16) + low_total;
+            const uint32_t off = (word >> ((d & 8u) * 2u)) & 0xFFFFu;
             keys[off + static_cast<uint32_t>((pfx >> (4 * j)) & 15ull)] = k[j];
         }
         __syncthreads();
