@@ -311,7 +311,7 @@ def training_weight_side(states, dab, torch, args):
             dab.dab_mean_center_clamp(s.W, dab.DAB_CENTER_FILTER, -1.0, 1.0, out=b["Wc"])
             W2 = b["Wc"].view(s.L.F, -1)
             est = dab.dab_estimate_alpha_beta_bounded(W2, b["prev"]["K"], b["prev"]["alpha_is_upper"],
-                                                      max(1, W2.shape[1] // 64), out=b["prev"])
+                                                      max(1, W2.shape[1] // 64), out=b["prev"], ws=s.est_ws)
             dab.dab_pack_weights(b["Wc"], est["thr_val"], est["thr_idx"], est["alpha_is_upper"], out=s.EW)
             dab.dab_binarized_weights(W2, est["alpha"], est["beta"], est["thr_val"], est["thr_idx"],
                                       est["alpha_is_upper"], out=b["Wt"])

@@ -322,17 +322,20 @@ def dab_weight_gradient(W, thr_val, thr_idx, alpha_is_upper, upstream=None, out=
     return G
 
 
-def dab_estimate_alpha_beta_bounded(W, K_prev, alpha_is_upper_prev, max_change, out=None):
+def dab_estimate_alpha_beta_bounded(W, K_prev, alpha_is_upper_prev, max_change, out=None, ws=None):
     """dab_estimate_alpha_beta with the split at most `max_change` elements from the previous one
     (K_prev int32 [F], alpha_is_upper_prev uint8 [F]: the previous call's outputs; `out` may hold them)."""
     F, n = W.shape
     o = out if out is not None else estimate_outputs(F, W.device)
+    nbytes = lib().dab_estimate_workspace_bytes(F, n)
+    ws = _workspace(nbytes, W.device, ws)
     _check("dab_estimate_alpha_beta_bounded", lib().dab_estimate_alpha_beta_bounded(
         _ptr(W, torch.float32, "W"), F, n, _ptr(K_prev, torch.int32, "K_prev"),
         _ptr(alpha_is_upper_prev, torch.uint8, "alpha_is_upper_prev"), max_change,
         _ptr(o["alpha"], torch.float32, "alpha"), _ptr(o["beta"], torch.float32, "beta"), _ptr(o["K"], torch.int32, "K"),
         _ptr(o["thr_val"], torch.float32, "thr_val"), _ptr(o["thr_idx"], torch.int32, "thr_idx"),
-        _ptr(o["alpha_is_upper"], torch.uint8, "alpha_is_upper"), None, 0, _stream()))
+        _ptr(o["alpha_is_upper"], torch.uint8, "alpha_is_upper"), ws.data_ptr() if ws is not None else None, nbytes,
+        _stream()))
     return o
 
 

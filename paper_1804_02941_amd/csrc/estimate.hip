@@ -82,8 +82,9 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
                                                            int32_t* Kout, float* __restrict__ thr_val,
                                                            int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
                                                            const int32_t* K_prev, const uint8_t* upper_prev,
-                                                           int max_change) {
+                                                           int max_change, const uint8_t* __restrict__ only) {
     static_assert(ITEMS >= 1 && ITEMS <= 15, "a digit counter has 4 bits");
+    if (only && !only[blockIdx.x]) return;      // the bucket kernel below has finished this row
     constexpr int NW = THREADS / 64;
     constexpr int N = THREADS * ITEMS;
     __shared__ uint32_t keys[N];
@@ -255,6 +256,369 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     }
 }
 
+// ---------------------------------------------------------------- estimation without the full sort
+// The arg-max of D needs the sorted order only near the optimum.  One pass of LDS atomics puts the
+// row into 4096 value buckets (count and exact fixed-point sum each), a scan gives, for every
+// bucket, the number and sum of all smaller elements, and with them D at the last element of every
+// bucket exactly and an upper bound of D at the positions inside it: there P_i lies between
+// S_b + j*lo_b and S_b + j*hi_b (and the same from the bucket's other end), and D is convex in P,
+// so the larger of the two ends bounds it.  Only buckets whose bound reaches the best bucket-end
+// value can hold the arg-max; their elements (a few dozen for the weight distributions of a
+// network) are ranked exactly, with exact prefix sums, and the split is chosen among them by the
+// same comparison as in the sort kernel.  A row whose candidates exceed the list (many equal
+// values, a constant row) is flagged and left to the sort kernel, which is launched behind this
+// one and returns at once for rows that are not flagged.
+//
+// Sums are integers: with 2^e > max |w| the values are scaled by 2^(48 - e) and rounded to int64,
+// which is exact for every element within 2^-24 of the row's largest magnitude (smaller ones are
+// rounded at 2^-49 of it), and integer atomics make the result independent of their order.
+constexpr int kFastBuckets = 4096;
+constexpr int kFastCap = 1024;          // candidate elements ranked exactly
+constexpr int kFastBigBucket = 64;      // buckets above this size are candidates without a bound
+
+__device__ __forceinline__ double d_score(double P, double T, double i, double n) {
+    const double rest = T - P;
+    return P * P / i + rest * rest / (n - i);
+}
+
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* __restrict__ Wt, int n,
+                                                                  float* __restrict__ alpha, float* __restrict__ beta,
+                                                                  int32_t* Kout, float* __restrict__ thr_val,
+                                                                  int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
+                                                                  const int32_t* K_prev, const uint8_t* upper_prev,
+                                                                  int max_change, uint8_t* __restrict__ fallback) {
+    constexpr int NW = THREADS / 64;
+    constexpr int BPT = kFastBuckets / THREADS;                  // buckets per thread
+    __shared__ uint32_t cnt[kFastBuckets + 1];                     // counts, then the exclusive prefix N_b (N_4096 = n)
+    __shared__ unsigned long long sum[kFastBuckets + 1];           // fixed-point sums, then the exclusive prefix S_b
+    __shared__ uint8_t cand[kFastBuckets];
+    __shared__ uint32_t lkey[kFastCap];
+    __shared__ long long lq[kFastCap];
+    __shared__ uint16_t lb[kFastCap];
+    __shared__ float w_min[NW], w_max[NW];
+    __shared__ uint32_t w_cnt[NW], w_cnt2[NW];
+    __shared__ long long w_sum[NW];
+    __shared__ double w_d[NW];
+    __shared__ Best wave_best[NW];
+    __shared__ uint32_t nlist_s, r_s;
+    __shared__ float thr_s;
+    __shared__ uint16_t w_hits[NW][ITEMS];
+
+    DAB_RESERVE_VGPRS();
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int f = blockIdx.x;
+    const float* row = Wt + static_cast<size_t>(f) * n;
+
+    // ---- the row, once, into registers (element j of thread t is row[t + j*THREADS])
+    float v[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) v[j] = row[min(tid + j * THREADS, n - 1)];
+    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        mn = fminf(mn, v[j]);                                      // (the clamped repeats change nothing)
+        mx = fmaxf(mx, v[j]);
+    }
+    for (int d = 32; d >= 1; d >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, d, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+    }
+    if (lane == 0) { w_min[wave] = mn; w_max[wave] = mx; }
+    for (int b = tid; b < kFastBuckets; b += THREADS) { cnt[b] = 0u; sum[b] = 0ull; cand[b] = 0; }
+    if (tid == 0) nlist_s = 0u;
+    __syncthreads();
+    for (int w = 0; w < NW; ++w) { mn = fminf(mn, w_min[w]); mx = fmaxf(mx, w_max[w]); }
+    if (!(mx > mn) || !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY)) {   // constant row (or not finite)
+        if (tid == 0) fallback[f] = 1;
+        return;
+    }
+    const float M = fmaxf(fabsf(mn), fabsf(mx));
+    const int ex = static_cast<int>((__float_as_uint(M) >> 23) & 0xFFu) - 126;     // M < 2^ex
+    const double scale = ldexp(1.0, 48 - ex);
+    const double vmin = static_cast<double>(mn);
+    // bucket of a value: fp32 arithmetic, monotone in the value (subtraction, multiplication by a
+    // positive constant and truncation all are); the rounding moves a value by less than 1e-3 of
+    // a bucket, which the bounds below allow for
+    const float bscalef = static_cast<float>(kFastBuckets * (1.0 - 1.0 / 4096.0) / (static_cast<double>(mx) - vmin));
+    const double bwidth = 1.0 / static_cast<double>(bscalef);     // value units per bucket
+
+    // ---- histogram: count and exact sum per bucket
+    int bk[ITEMS];
+    // x * 2^(48 - ex) as an integer, from the bits of x: the 24-bit significand shifted by the
+    // exponent difference (to the right, rounding half up, only for elements below 2^-24 of the
+    // row's largest magnitude)
+    auto fixed_of = [&](float x) -> long long {
+        const uint32_t u = __float_as_uint(x);
+        const int e = static_cast<int>((u >> 23) & 0xFFu);
+        const long long m = e ? static_cast<long long>((u & 0x7FFFFFu) | 0x800000u) : static_cast<long long>(u & 0x7FFFFFu);
+        const int sh = (e ? e : 1) - 150 + 48 - ex;                 // value = m * 2^(e - 150); sh <= 24
+        const long long q = sh >= 0 ? m << sh : (sh > -63 ? (m + (1ll << (-sh - 1))) >> -sh : 0ll);
+        return (u >> 31) ? -q : q;
+    };
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        bk[j] = max(min(static_cast<int>((v[j] - mn) * bscalef), kFastBuckets - 1), 0);
+        if (tid + j * THREADS < n) {
+            atomicAdd(&cnt[bk[j]], 1u);
+            atomicAdd(&sum[bk[j]], static_cast<unsigned long long>(fixed_of(v[j])));
+        }
+    }
+    __syncthreads();
+
+    // ---- exclusive prefixes over the buckets (thread t scans buckets t*BPT ..)
+    {
+        uint32_t c[BPT], crun = 0;
+        long long sv[BPT], srun = 0;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            c[k] = cnt[tid * BPT + k];
+            sv[k] = static_cast<long long>(sum[tid * BPT + k]);
+        }
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            const uint32_t tc = c[k];
+            const long long ts = sv[k];
+            c[k] = crun;
+            sv[k] = srun;
+            crun += tc;
+            srun += ts;
+        }
+        const uint32_t cinc = wave_inclusive_scan_u32(crun);
+        long long sinc = srun;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const long long o = __shfl_up(sinc, d, 64);
+            if (lane >= d) sinc += o;
+        }
+        if (lane == 63) { w_cnt[wave] = cinc; w_sum[wave] = sinc; }
+        __syncthreads();
+        uint32_t cbase = cinc - crun;
+        long long sbase = sinc - srun, total = 0;
+        for (int w = 0; w < NW; ++w) {
+            if (w < wave) { cbase += w_cnt[w]; sbase += w_sum[w]; }
+            total += w_sum[w];
+        }
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            cnt[tid * BPT + k] = c[k] + cbase;
+            sum[tid * BPT + k] = static_cast<unsigned long long>(sv[k] + sbase);
+        }
+        if (tid == 0) {
+            cnt[kFastBuckets] = static_cast<uint32_t>(n);
+            sum[kFastBuckets] = static_cast<unsigned long long>(total);
+        }
+    }
+    __syncthreads();
+    const double T = static_cast<double>(static_cast<long long>(sum[kFastBuckets])), dn = static_cast<double>(n);
+
+    // ---- allowed splits: 1 .. n-1, or the window around the previous split
+    int wlo = 1, whi = n - 1;
+    if (K_prev) {
+        int ip = upper_prev[f] ? n - K_prev[f] : K_prev[f];
+        ip = min(max(ip, 1), n - 1);
+        const int d = min(max(max_change, 0), n);
+        wlo = max(1, ip - d);
+        whi = min(n - 1, ip + d);
+    }
+
+    // ---- D at the end of every bucket (the hardware reciprocal is accurate far beyond the margin
+    // used below).  Buckets are dealt out round robin: the populated ones are neighbours.
+    auto score = [&](double P, double ri, double rr) -> double {
+        const double rest = T - P;
+        return P * P * ri + rest * rest * rr;
+    };
+    double dend = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < BPT; ++k) {
+        const int b = tid + k * THREADS;
+        const int i0 = static_cast<int>(cnt[b]), iend = static_cast<int>(cnt[b + 1]);
+        if (iend > i0 && iend >= wlo && iend <= whi)
+            dend = fmax(dend, score(static_cast<double>(static_cast<long long>(sum[b + 1])),
+                                    __builtin_amdgcn_rcp(static_cast<double>(iend)),
+                                    __builtin_amdgcn_rcp(static_cast<double>(n - iend))));
+    }
+    for (int d = 32; d >= 1; d >>= 1) dend = fmax(dend, __shfl_xor(dend, d, 64));
+    if (lane == 0) w_d[wave] = dend;
+    __syncthreads();
+    for (int w = 0; w < NW; ++w) dend = fmax(dend, w_d[w]);
+    const double need = dend - 1e-6 * fabs(dend);
+
+    // ---- candidates: buckets that can hold a split reaching `need`.  Inside a bucket P_i lies in
+    // [S_b + j lo, S_b + j hi] and in [S_e - (c-j) hi, S_e - (c-j) lo] (j elements of the bucket are
+    // below the split); D is convex in P and in i separately, so over a box of (i, P) it is largest
+    // at a corner.  First the box of the whole bucket, then, only where that is not enough to rule
+    // the bucket out, position by position.
+    uint32_t ncand = 0;
+#pragma unroll
+    for (int k = 0; k < BPT; ++k) {
+        const int b = tid + k * THREADS;
+        const int i0 = static_cast<int>(cnt[b]), iend = static_cast<int>(cnt[b + 1]);
+        const int c = iend - i0;
+        if (c == 0) continue;
+        const double Sb = static_cast<double>(static_cast<long long>(sum[b]));
+        const double Se = static_cast<double>(static_cast<long long>(sum[b + 1]));
+        bool is_cand = false;
+        if (iend >= wlo && iend <= whi)
+            is_cand = score(Se, __builtin_amdgcn_rcp(static_cast<double>(iend)),
+                            __builtin_amdgcn_rcp(static_cast<double>(n - iend))) >= need;
+        const int jlo = max(1, wlo - i0), jhi = min(c - 1, whi - i0);
+        if (!is_cand && jlo <= jhi) {
+            if (c > kFastBigBucket) {
+                is_cand = true;
+            } else {
+                // value range of the bucket in fixed-point units, widened against rounding
+                const double lo = (vmin + (static_cast<double>(b) - 2e-3) * bwidth) * scale - 1.0;
+                const double hi = (vmin + (static_cast<double>(b) + 1.0 + 2e-3) * bwidth) * scale + 1.0;
+                const double ja = static_cast<double>(jlo), jb = static_cast<double>(jhi);
+                const double ra = static_cast<double>(c - jlo), rb = static_cast<double>(c - jhi);
+                const double Pl = fmax(fmin(Sb + ja * lo, Sb + jb * lo), fmin(Se - ra * hi, Se - rb * hi));
+                const double Ph = fmin(fmax(Sb + ja * hi, Sb + jb * hi), fmax(Se - ra * lo, Se - rb * lo));
+                const double ri0 = __builtin_amdgcn_rcp(static_cast<double>(i0 + jlo));
+                const double rr0 = __builtin_amdgcn_rcp(static_cast<double>(n - i0 - jlo));
+                const double ri1 = __builtin_amdgcn_rcp(static_cast<double>(i0 + jhi));
+                const double rr1 = __builtin_amdgcn_rcp(static_cast<double>(n - i0 - jhi));
+                const double box = fmax(fmax(score(Pl, ri0, rr0), score(Ph, ri0, rr0)),
+                                        fmax(score(Pl, ri1, rr1), score(Ph, ri1, rr1)));
+                if (box >= need) {
+                    for (int j = jlo; j <= jhi && !is_cand; ++j) {
+                        const double dj = static_cast<double>(j), dr = static_cast<double>(c - j);
+                        const double pl = fmax(Sb + dj * lo, Se - dr * hi), ph = fmin(Sb + dj * hi, Se - dr * lo);
+                        const double ri = __builtin_amdgcn_rcp(static_cast<double>(i0 + j));
+                        const double rr = __builtin_amdgcn_rcp(static_cast<double>(n - i0 - j));
+                        is_cand = fmax(score(pl, ri, rr), score(ph, ri, rr)) >= need;
+                    }
+                }
+            }
+        }
+        if (is_cand) {
+            cand[b] = 1;
+            ncand += static_cast<uint32_t>(c);
+        }
+    }
+    const uint32_t ninc = wave_inclusive_scan_u32(ncand);
+    if (lane == 63) w_cnt2[wave] = ninc;
+    __syncthreads();
+    uint32_t nc = 0;
+    for (int w = 0; w < NW; ++w) nc += w_cnt2[w];
+    if (nc > kFastCap || nc == 0) {
+        if (tid == 0) fallback[f] = 1;
+        return;
+    }
+
+    // ---- the candidates' elements
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        if (tid + j * THREADS < n && cand[bk[j]]) {
+            const uint32_t slot = atomicAdd(&nlist_s, 1u);
+            lkey[slot] = float_to_key(v[j]);
+            lq[slot] = fixed_of(v[j]);
+            lb[slot] = static_cast<uint16_t>(bk[j]);
+        }
+    }
+    __syncthreads();
+
+    // ---- exact position and prefix sum of every candidate: elements of its bucket that precede it
+    Best best{-1.0, 1.0, 0.0, 0};
+    uint32_t my_key = 0, my_less = 0;
+    int my_i = 0;
+    for (int e = tid; e < static_cast<int>(nc); e += THREADS) {
+        const uint32_t key = lkey[e];
+        const int b = lb[e];
+        uint32_t within = 0, less = 0;
+        long long ps = 0;
+#pragma unroll 4
+        for (int q = 0; q < static_cast<int>(nc); ++q) {          // branch-free: the LDS reads pipeline
+            const uint32_t kq = lkey[q];
+            const bool same = lb[q] == b;
+            const bool lt = same && kq < key;
+            const bool le = same && (kq < key || (kq == key && q <= e));
+            within += le ? 1u : 0u;
+            less += lt ? 1u : 0u;
+            ps += le ? lq[q] : 0ll;
+        }
+        const int i = static_cast<int>(cnt[b] + within);
+        if (i >= wlo && i <= whi) {
+            const double P = static_cast<double>(static_cast<long long>(sum[b]) + ps);
+            const double rest = T - P;
+            const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
+            const Best candb{P * P * fr + rest * rest * fi, fi * fr, P, i};
+            if (better(candb, best)) {
+                best = candb;
+                my_key = key;
+                my_less = cnt[b] + less;
+                my_i = i;
+            }
+        }
+    }
+    // only the wavefronts that hold candidates (the first one, as a rule) reduce
+    const int nwr = min(NW, static_cast<int>(nc + 63) >> 6);
+    if (wave < nwr) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const Best o{__shfl_xor(best.num, d, 64), __shfl_xor(best.den, d, 64), __shfl_xor(best.P, d, 64),
+                         __shfl_xor(best.i, d, 64)};
+            if (better(o, best)) best = o;
+        }
+        if (lane == 0) wave_best[wave] = best;
+    }
+    __syncthreads();
+    Best bb = wave_best[0];
+    for (int w = 1; w < nwr; ++w)
+        if (better(wave_best[w], bb)) bb = wave_best[w];
+    if (bb.i < 1) {                                                // no candidate inside the window: not expected
+        if (tid == 0) fallback[f] = 1;
+        return;
+    }
+    if (my_i == bb.i) {                                            // exactly one thread holds the winning position
+        thr_s = key_to_float(my_key);
+        r_s = static_cast<uint32_t>(bb.i) - my_less;               // copies of the value in the lower group
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int is = bb.i;
+        const double mu_lower = bb.P / static_cast<double>(is) / scale;
+        const double mu_upper = (T - bb.P) / static_cast<double>(n - is) / scale;
+        const bool upper = fabs(mu_upper) >= fabs(mu_lower);
+        alpha[f] = static_cast<float>(upper ? mu_upper : mu_lower);
+        beta[f] = static_cast<float>(upper ? mu_lower : mu_upper);
+        Kout[f] = upper ? n - is : is;
+        alpha_is_upper[f] = upper ? 1 : 0;
+        thr_val[f] = thr_s;
+        fallback[f] = 0;
+    }
+
+    // ---- original index of the r-th copy (in index order) of the split value.  Element j of thread
+    // t has index t + j*THREADS, so slot-major order is index order: per slot and wavefront the
+    // number of copies goes to LDS once, and only the threads that hold a copy look their rank up.
+    const float tv = thr_s;
+    const uint32_t r = r_s;
+    uint32_t mine = 0, in_wave[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const bool hit = tid + j * THREADS < n && v[j] == tv;
+        const unsigned long long m = __ballot(hit);
+        in_wave[j] = static_cast<uint32_t>(__popcll(m & ((1ull << lane) - 1ull)));
+        mine |= hit ? 1u << j : 0u;
+        if (lane == 0) w_hits[wave][j] = static_cast<uint16_t>(__popcll(m));
+    }
+    __syncthreads();
+    if (mine) {
+        uint32_t before = 0;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            uint32_t lower = 0, all = 0;
+            for (int w = 0; w < NW; ++w) {
+                const uint32_t h = w_hits[w][j];
+                lower += w < wave ? h : 0u;
+                all += h;
+            }
+            if (((mine >> j) & 1u) && before + lower + in_wave[j] + 1 == r) thr_idx[f] = tid + j * THREADS;
+            before += all;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- sign split (XNOR-Net / BWN)
 // The distribution-agnostic special case of Section 4.1: e = [w >= 0], alpha = mean |w|, beta = -alpha.
 // One workgroup per filter, plain reductions; the outputs have the form of the estimator's, so the
@@ -313,19 +677,38 @@ constexpr int kEstimateMaxN = 1024 * 13;
 template <int THREADS, int ITEMS>
 static int launch_estimate(const float* W, int F, int n, float* alpha, float* beta, int32_t* K, float* thr_val,
                            int32_t* thr_idx, uint8_t* aiu, const int32_t* K_prev, const uint8_t* upper_prev,
-                           int max_change, hipStream_t st) {
+                           int max_change, const uint8_t* only, hipStream_t st) {
     hipLaunchKernelGGL((estimate_kernel<THREADS, ITEMS>), dim3(F), dim3(THREADS), 0, st, W, n, alpha, beta, K,
-                       thr_val, thr_idx, aiu, K_prev, upper_prev, max_change);
+                       thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
     return launch_status();
+}
+
+constexpr int kBucketMinN = 4096;        // shorter rows go to the sort kernel directly (it is faster there)
+
+static size_t estimate_ws_bytes(int F, int n) {
+    return n >= kBucketMinN ? (static_cast<size_t>(F) + 255) & ~static_cast<size_t>(255) : 0;
 }
 
 // Smallest padded size that holds the row; odd item counts keep the per-thread key runs off each
 // other's LDS banks.
 static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* beta, int32_t* K, float* thr_val,
                              int32_t* thr_idx, uint8_t* aiu, const int32_t* K_prev, const uint8_t* upper_prev,
-                             int max_change, hipStream_t st) {
+                             int max_change, void* ws, size_t ws_bytes, hipStream_t st) {
+    // With a workspace for the per-row flags, the bucket kernel goes first and the sort kernel only
+    // works on the rows it hands over; without one the sort kernel does every row.
+    uint8_t* only = nullptr;
+    if (n >= kBucketMinN && ws && ws_bytes >= estimate_ws_bytes(F, n)) {
+        only = static_cast<uint8_t*>(ws);
+        if (n <= 1024 * 8)
+            hipLaunchKernelGGL((estimate_bucket_kernel<1024, 8>), dim3(F), dim3(1024), 0, st, W, n, alpha, beta, K, thr_val,
+                               thr_idx, aiu, K_prev, upper_prev, max_change, only);
+        else
+            hipLaunchKernelGGL((estimate_bucket_kernel<1024, 13>), dim3(F), dim3(1024), 0, st, W, n, alpha, beta, K, thr_val,
+                               thr_idx, aiu, K_prev, upper_prev, max_change, only);
+        if (int rc = launch_status()) return rc;
+    }
 #define DAB_EST(T, I) \
-    return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, st)
+    return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only, st)
     if (n <= 64 * 3) DAB_EST(64, 3);
     if (n <= 256 * 3) DAB_EST(256, 3);
     if (n <= 256 * 5) DAB_EST(256, 5);
@@ -346,21 +729,20 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
 
 extern "C" {
 
-size_t dab_estimate_workspace_bytes(int32_t, int32_t) { return 0; }
+size_t dab_estimate_workspace_bytes(int32_t F, int32_t n) { return F < 1 || n < 2 ? 0 : dab::estimate_ws_bytes(F, n); }
 int32_t dab_estimate_max_n(void) { return dab::kEstimateMaxN; }
 
 int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n, float* alpha, float* beta, int32_t* K,
                             float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* ws, size_t ws_bytes,
                             void* stream) {
     using namespace dab;
-    (void)ws; (void)ws_bytes;
     if (!W || !alpha || !beta || !K || !thr_val || !thr_idx || !alpha_is_upper) return DAB_ERR_NULL;
     if (F < 1 || n < 2) return DAB_ERR_SHAPE;
     if (misaligned(W, 4) || misaligned(alpha, 4) || misaligned(beta, 4) || misaligned(K, 4) ||
         misaligned(thr_val, 4) || misaligned(thr_idx, 4))
         return DAB_ERR_ALIGN;
     if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
-    return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, nullptr, nullptr, 0,
+    return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, nullptr, nullptr, 0, ws, ws_bytes,
                              static_cast<hipStream_t>(stream));
 }
 
@@ -369,7 +751,6 @@ int dab_estimate_alpha_beta_bounded(const float* W, int32_t F, int32_t n, const 
                                     int32_t* K, float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* ws,
                                     size_t ws_bytes, void* stream) {
     using namespace dab;
-    (void)ws; (void)ws_bytes;
     if (!W || !K_prev || !alpha_is_upper_prev || !alpha || !beta || !K || !thr_val || !thr_idx || !alpha_is_upper)
         return DAB_ERR_NULL;
     if (F < 1 || n < 2 || max_change < 0) return DAB_ERR_SHAPE;
@@ -378,7 +759,7 @@ int dab_estimate_alpha_beta_bounded(const float* W, int32_t F, int32_t n, const 
         return DAB_ERR_ALIGN;
     if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
     return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, K_prev, alpha_is_upper_prev,
-                             max_change, static_cast<hipStream_t>(stream));
+                             max_change, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int dab_estimate_sign_split(const float* W, int32_t F, int32_t n, float* alpha, float* beta, int32_t* K,

@@ -130,6 +130,51 @@ def test_estimate_degenerate_rows():
     assert got["K"][3] == n // 2 and got["alpha"][3] == 0.5 and got["beta"][3] == -0.5
 
 
+@pytest.mark.parametrize("kind", ["gauss", "laplace", "mixture", "dupes", "onesided"])
+@pytest.mark.parametrize("n", [4096, 5003, 12544])
+def test_estimate_long_rows(kind, n):
+    """Rows long enough for the bucket kernel (value buckets, bounds, exact ranking of the few
+    candidates), including rows it hands over to the sort kernel (many equal values)."""
+    rng = np.random.default_rng(n + len(kind))
+    W = weight_rows(rng, 7, n, kind)
+    got, _ = gu.gpu_estimate(W)
+    _, differ = gu.check_estimate(W, got)
+    assert differ <= 1
+
+
+def test_estimate_long_degenerate_rows():
+    n = 6000
+    rng = np.random.default_rng(61)
+    wide = (rng.standard_normal(n) * np.exp(rng.uniform(-30, 0, n))).astype(np.float32)     # 13 decades of magnitudes
+    tiny = (rng.standard_normal(n) * 1e-41).astype(np.float32)                             # denormals only
+    outl = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    outl[17] = 250.0                                                                       # one huge value: the rest shares few buckets
+    two = np.where(rng.random(n) < 0.3, 0.25, -0.125).astype(np.float32)
+    near = (1.0 + rng.integers(0, 50, n) * 2.0 ** -23).astype(np.float32)                  # 50 neighbouring floats
+    rows = [
+        np.full(n, 0.25, np.float32),                                         # constant
+        np.concatenate([np.zeros(n // 2), -np.zeros(n // 2)]).astype(np.float32),   # +0 / -0 only
+        np.concatenate([np.full(n - 1, -1.0), [3.0]]).astype(np.float32),     # one outlier among equal values
+        two, np.arange(n, dtype=np.float32) / n, -np.arange(n, dtype=np.float32) / n,
+        wide, tiny, outl, near,
+    ]
+    W = np.stack(rows)
+    got, _ = gu.gpu_estimate(W)
+    _, differ = gu.check_estimate(W, got)
+    assert differ <= 1
+    assert got["K"][0] == 1 and got["thr_idx"][0] == n - 2
+    # the same rows without a workspace (sort kernel only) give the same splits
+    t = gu.to_gpu(W)
+    out = dab.estimate_outputs(W.shape[0], t.device)
+    rc = dab.lib().dab_estimate_alpha_beta(t.data_ptr(), W.shape[0], n, out["alpha"].data_ptr(), out["beta"].data_ptr(),
+                                           out["K"].data_ptr(), out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(),
+                                           out["alpha_is_upper"].data_ptr(), None, 0, None)
+    torch.cuda.synchronize()
+    assert rc == 0
+    plain = {k: v.cpu().numpy() for k, v in out.items()}
+    gu.check_estimate(W, plain)
+
+
 def test_estimate_xnor_special_case():
     """Symmetric filter: K = n/2 and alpha = -beta = mean|W| (Section 4.2's XNOR-Net simulation)."""
     rng = np.random.default_rng(23)
