@@ -272,16 +272,13 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
 // Sums are integers: with 2^e > max |w| the values are scaled by 2^(48 - e) and rounded to int64,
 // which is exact for every element within 2^-24 of the row's largest magnitude (smaller ones are
 // rounded at 2^-49 of it), and integer atomics make the result independent of their order.
-constexpr int kFastBuckets = 4096;
-constexpr int kFastCap = 1024;          // candidate elements ranked exactly
-constexpr int kFastBigBucket = 64;      // buckets above this size are candidates without a bound
+constexpr int kFastBigBucket = 96;      // buckets above this size are candidates without a bound
 
-__device__ __forceinline__ double d_score(double P, double T, double i, double n) {
-    const double rest = T - P;
-    return P * P / i + rest * rest / (n - i);
-}
-
-template <int THREADS, int ITEMS>
+// THREADS threads with up to ITEMS elements each, NB value buckets, at most CAP candidate elements.
+// The row is read from global memory (L2) in each of its four passes, every load of a pass in
+// flight at once, so nothing of it stays in registers between the phases, little LDS is needed and
+// several workgroups share a compute unit: every phase is a short latency chain between barriers.
+template <int THREADS, int ITEMS, int NB, int CAP>
 __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* __restrict__ Wt, int n,
                                                                   float* __restrict__ alpha, float* __restrict__ beta,
                                                                   int32_t* Kout, float* __restrict__ thr_val,
@@ -289,13 +286,13 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
                                                                   const int32_t* K_prev, const uint8_t* upper_prev,
                                                                   int max_change, uint8_t* __restrict__ fallback) {
     constexpr int NW = THREADS / 64;
-    constexpr int BPT = kFastBuckets / THREADS;                  // buckets per thread
-    __shared__ uint32_t cnt[kFastBuckets + 1];                     // counts, then the exclusive prefix N_b (N_4096 = n)
-    __shared__ unsigned long long sum[kFastBuckets + 1];           // fixed-point sums, then the exclusive prefix S_b
-    __shared__ uint8_t cand[kFastBuckets];
-    __shared__ uint32_t lkey[kFastCap];
-    __shared__ long long lq[kFastCap];
-    __shared__ uint16_t lb[kFastCap];
+    constexpr int BPT = NB / THREADS;                              // buckets per thread
+    __shared__ uint32_t cnt[NB + 1];                               // counts, then the exclusive prefix N_b (N_NB = n)
+    __shared__ unsigned long long sum[NB + 1];                     // fixed-point sums, then the exclusive prefix S_b
+    __shared__ uint8_t cand[NB];
+    __shared__ uint32_t lkey[CAP];
+    __shared__ long long lq[CAP];
+    __shared__ uint16_t lb[CAP];
     __shared__ float w_min[NW], w_max[NW];
     __shared__ uint32_t w_cnt[NW], w_cnt2[NW];
     __shared__ long long w_sum[NW];
@@ -303,29 +300,31 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     __shared__ Best wave_best[NW];
     __shared__ uint32_t nlist_s, r_s;
     __shared__ float thr_s;
-    __shared__ uint16_t w_hits[NW][ITEMS];
+    __shared__ unsigned long long w_mask[NW][ITEMS];
 
     DAB_RESERVE_VGPRS();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int f = blockIdx.x;
     const float* row = Wt + static_cast<size_t>(f) * n;
 
-    // ---- the row, once, into registers (element j of thread t is row[t + j*THREADS])
-    float v[ITEMS];
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j) v[j] = row[min(tid + j * THREADS, n - 1)];
+    // ---- range of the row
     float mn = INFINITY, mx = -INFINITY;
+    {
+        float x[ITEMS];
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        mn = fminf(mn, v[j]);                                      // (the clamped repeats change nothing)
-        mx = fmaxf(mx, v[j]);
+        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            mn = fminf(mn, x[j]);                                  // (the clamped repeats change nothing)
+            mx = fmaxf(mx, x[j]);
+        }
     }
     for (int d = 32; d >= 1; d >>= 1) {
         mn = fminf(mn, __shfl_xor(mn, d, 64));
         mx = fmaxf(mx, __shfl_xor(mx, d, 64));
     }
     if (lane == 0) { w_min[wave] = mn; w_max[wave] = mx; }
-    for (int b = tid; b < kFastBuckets; b += THREADS) { cnt[b] = 0u; sum[b] = 0ull; cand[b] = 0; }
+    for (int b = tid; b < NB; b += THREADS) { cnt[b] = 0u; sum[b] = 0ull; cand[b] = 0; }
     if (tid == 0) nlist_s = 0u;
     __syncthreads();
     for (int w = 0; w < NW; ++w) { mn = fminf(mn, w_min[w]); mx = fmaxf(mx, w_max[w]); }
@@ -340,28 +339,27 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     // bucket of a value: fp32 arithmetic, monotone in the value (subtraction, multiplication by a
     // positive constant and truncation all are); the rounding moves a value by less than 1e-3 of
     // a bucket, which the bounds below allow for
-    const float bscalef = static_cast<float>(kFastBuckets * (1.0 - 1.0 / 4096.0) / (static_cast<double>(mx) - vmin));
+    const float bscalef = static_cast<float>(NB * (1.0 - 1.0 / 4096.0) / (static_cast<double>(mx) - vmin));
     const double bwidth = 1.0 / static_cast<double>(bscalef);     // value units per bucket
+    auto bucket_of = [&](float x) -> int { return max(min(static_cast<int>((x - mn) * bscalef), NB - 1), 0); };
+    // x * 2^(48 - ex) rounded to an integer (|.| < 2^48): added to 1.5 * 2^52, the integer sits in
+    // the low bits of the double
+    auto fixed_of = [&](float x) -> long long {
+        return __double_as_longlong(fma(static_cast<double>(x), scale, 6755399441055744.0)) - 0x4338000000000000ll;
+    };
 
     // ---- histogram: count and exact sum per bucket
-    int bk[ITEMS];
-    // x * 2^(48 - ex) as an integer, from the bits of x: the 24-bit significand shifted by the
-    // exponent difference (to the right, rounding half up, only for elements below 2^-24 of the
-    // row's largest magnitude)
-    auto fixed_of = [&](float x) -> long long {
-        const uint32_t u = __float_as_uint(x);
-        const int e = static_cast<int>((u >> 23) & 0xFFu);
-        const long long m = e ? static_cast<long long>((u & 0x7FFFFFu) | 0x800000u) : static_cast<long long>(u & 0x7FFFFFu);
-        const int sh = (e ? e : 1) - 150 + 48 - ex;                 // value = m * 2^(e - 150); sh <= 24
-        const long long q = sh >= 0 ? m << sh : (sh > -63 ? (m + (1ll << (-sh - 1))) >> -sh : 0ll);
-        return (u >> 31) ? -q : q;
-    };
+    {
+        float x[ITEMS];
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        bk[j] = max(min(static_cast<int>((v[j] - mn) * bscalef), kFastBuckets - 1), 0);
-        if (tid + j * THREADS < n) {
-            atomicAdd(&cnt[bk[j]], 1u);
-            atomicAdd(&sum[bk[j]], static_cast<unsigned long long>(fixed_of(v[j])));
+        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (tid + j * THREADS < n) {
+                const int b = bucket_of(x[j]);
+                atomicAdd(&cnt[b], 1u);
+                atomicAdd(&sum[b], static_cast<unsigned long long>(fixed_of(x[j])));
+            }
         }
     }
     __syncthreads();
@@ -405,12 +403,12 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
             sum[tid * BPT + k] = static_cast<unsigned long long>(sv[k] + sbase);
         }
         if (tid == 0) {
-            cnt[kFastBuckets] = static_cast<uint32_t>(n);
-            sum[kFastBuckets] = static_cast<unsigned long long>(total);
+            cnt[NB] = static_cast<uint32_t>(n);
+            sum[NB] = static_cast<unsigned long long>(total);
         }
     }
     __syncthreads();
-    const double T = static_cast<double>(static_cast<long long>(sum[kFastBuckets])), dn = static_cast<double>(n);
+    const double T = static_cast<double>(static_cast<long long>(sum[NB]));
 
     // ---- allowed splits: 1 .. n-1, or the window around the previous split
     int wlo = 1, whi = n - 1;
@@ -424,9 +422,10 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
 
     // ---- D at the end of every bucket (the hardware reciprocal is accurate far beyond the margin
     // used below).  Buckets are dealt out round robin: the populated ones are neighbours.
-    auto score = [&](double P, double ri, double rr) -> double {
+    const double dn = static_cast<double>(n);
+    auto score = [&](double P, double i) -> double {              // D at a (real) position i with prefix sum P
         const double rest = T - P;
-        return P * P * ri + rest * rest * rr;
+        return P * P * __builtin_amdgcn_rcp(i) + rest * rest * __builtin_amdgcn_rcp(dn - i);
     };
     double dend = -INFINITY;
 #pragma unroll
@@ -434,9 +433,7 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
         const int b = tid + k * THREADS;
         const int i0 = static_cast<int>(cnt[b]), iend = static_cast<int>(cnt[b + 1]);
         if (iend > i0 && iend >= wlo && iend <= whi)
-            dend = fmax(dend, score(static_cast<double>(static_cast<long long>(sum[b + 1])),
-                                    __builtin_amdgcn_rcp(static_cast<double>(iend)),
-                                    __builtin_amdgcn_rcp(static_cast<double>(n - iend))));
+            dend = fmax(dend, score(static_cast<double>(static_cast<long long>(sum[b + 1])), static_cast<double>(iend)));
     }
     for (int d = 32; d >= 1; d >>= 1) dend = fmax(dend, __shfl_xor(dend, d, 64));
     if (lane == 0) w_d[wave] = dend;
@@ -444,11 +441,11 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     for (int w = 0; w < NW; ++w) dend = fmax(dend, w_d[w]);
     const double need = dend - 1e-6 * fabs(dend);
 
-    // ---- candidates: buckets that can hold a split reaching `need`.  Inside a bucket P_i lies in
-    // [S_b + j lo, S_b + j hi] and in [S_e - (c-j) hi, S_e - (c-j) lo] (j elements of the bucket are
-    // below the split); D is convex in P and in i separately, so over a box of (i, P) it is largest
-    // at a corner.  First the box of the whole bucket, then, only where that is not enough to rule
-    // the bucket out, position by position.
+    // ---- candidates: buckets that can hold a split reaching `need`.  With j elements of the bucket
+    // below the split, P lies between L(j) = max(S_b + j lo, S_e - (c-j) hi) and
+    // U(j) = min(S_b + j hi, S_e - (c-j) lo): a convex region of the (i, P) plane, and D (a sum of
+    // squares over linear terms) is jointly convex there, so it is largest at a vertex: at the two
+    // ends of the j range or where the two lines of L or of U cross.
     uint32_t ncand = 0;
 #pragma unroll
     for (int k = 0; k < BPT; ++k) {
@@ -459,9 +456,7 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
         const double Sb = static_cast<double>(static_cast<long long>(sum[b]));
         const double Se = static_cast<double>(static_cast<long long>(sum[b + 1]));
         bool is_cand = false;
-        if (iend >= wlo && iend <= whi)
-            is_cand = score(Se, __builtin_amdgcn_rcp(static_cast<double>(iend)),
-                            __builtin_amdgcn_rcp(static_cast<double>(n - iend))) >= need;
+        if (iend >= wlo && iend <= whi) is_cand = score(Se, static_cast<double>(iend)) >= need;
         const int jlo = max(1, wlo - i0), jhi = min(c - 1, whi - i0);
         if (!is_cand && jlo <= jhi) {
             if (c > kFastBigBucket) {
@@ -470,25 +465,17 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
                 // value range of the bucket in fixed-point units, widened against rounding
                 const double lo = (vmin + (static_cast<double>(b) - 2e-3) * bwidth) * scale - 1.0;
                 const double hi = (vmin + (static_cast<double>(b) + 1.0 + 2e-3) * bwidth) * scale + 1.0;
-                const double ja = static_cast<double>(jlo), jb = static_cast<double>(jhi);
-                const double ra = static_cast<double>(c - jlo), rb = static_cast<double>(c - jhi);
-                const double Pl = fmax(fmin(Sb + ja * lo, Sb + jb * lo), fmin(Se - ra * hi, Se - rb * hi));
-                const double Ph = fmin(fmax(Sb + ja * hi, Sb + jb * hi), fmax(Se - ra * lo, Se - rb * lo));
-                const double ri0 = __builtin_amdgcn_rcp(static_cast<double>(i0 + jlo));
-                const double rr0 = __builtin_amdgcn_rcp(static_cast<double>(n - i0 - jlo));
-                const double ri1 = __builtin_amdgcn_rcp(static_cast<double>(i0 + jhi));
-                const double rr1 = __builtin_amdgcn_rcp(static_cast<double>(n - i0 - jhi));
-                const double box = fmax(fmax(score(Pl, ri0, rr0), score(Ph, ri0, rr0)),
-                                        fmax(score(Pl, ri1, rr1), score(Ph, ri1, rr1)));
-                if (box >= need) {
-                    for (int j = jlo; j <= jhi && !is_cand; ++j) {
-                        const double dj = static_cast<double>(j), dr = static_cast<double>(c - j);
-                        const double pl = fmax(Sb + dj * lo, Se - dr * hi), ph = fmin(Sb + dj * hi, Se - dr * lo);
-                        const double ri = __builtin_amdgcn_rcp(static_cast<double>(i0 + j));
-                        const double rr = __builtin_amdgcn_rcp(static_cast<double>(n - i0 - j));
-                        is_cand = fmax(score(pl, ri, rr), score(ph, ri, rr)) >= need;
-                    }
-                }
+                const double dc = static_cast<double>(c), ja = static_cast<double>(jlo), jb = static_cast<double>(jhi);
+                auto L = [&](double j) { return fmax(Sb + j * lo, Se - (dc - j) * hi); };
+                auto U = [&](double j) { return fmin(Sb + j * hi, Se - (dc - j) * lo); };
+                const double inv = __builtin_amdgcn_rcp(hi - lo);
+                const double jl = fmin(fmax((Sb - Se + dc * hi) * inv, ja), jb);    // the lines of L cross here
+                const double ju = fmin(fmax((Se - Sb - dc * lo) * inv, ja), jb);    // the lines of U cross here
+                const double di0 = static_cast<double>(i0);
+                double best_b = fmax(fmax(score(L(ja), di0 + ja), score(U(ja), di0 + ja)),
+                                     fmax(score(L(jb), di0 + jb), score(U(jb), di0 + jb)));
+                best_b = fmax(best_b, fmax(score(L(jl), di0 + jl), score(U(ju), di0 + ju)));
+                is_cand = best_b >= need;
             }
         }
         if (is_cand) {
@@ -501,19 +488,27 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     __syncthreads();
     uint32_t nc = 0;
     for (int w = 0; w < NW; ++w) nc += w_cnt2[w];
-    if (nc > kFastCap || nc == 0) {
+    if (nc > CAP || nc == 0) {
         if (tid == 0) fallback[f] = 1;
         return;
     }
 
     // ---- the candidates' elements
+    {
+        float x[ITEMS];
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        if (tid + j * THREADS < n && cand[bk[j]]) {
-            const uint32_t slot = atomicAdd(&nlist_s, 1u);
-            lkey[slot] = float_to_key(v[j]);
-            lq[slot] = fixed_of(v[j]);
-            lb[slot] = static_cast<uint16_t>(bk[j]);
+        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (tid + j * THREADS < n) {
+                const int b = bucket_of(x[j]);
+                if (cand[b]) {
+                    const uint32_t slot = atomicAdd(&nlist_s, 1u);
+                    lkey[slot] = float_to_key(x[j]);
+                    lq[slot] = fixed_of(x[j]);
+                    lb[slot] = static_cast<uint16_t>(b);
+                }
+            }
         }
     }
     __syncthreads();
@@ -589,31 +584,35 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     }
 
     // ---- original index of the r-th copy (in index order) of the split value.  Element j of thread
-    // t has index t + j*THREADS, so slot-major order is index order: per slot and wavefront the
-    // number of copies goes to LDS once, and only the threads that hold a copy look their rank up.
+    // t has index t + j*THREADS, so slot-major order is index order: the ballot of every slot goes
+    // to LDS, and only the threads that hold a copy (one, as a rule) work out their rank.
     const float tv = thr_s;
     const uint32_t r = r_s;
-    uint32_t mine = 0, in_wave[ITEMS];
+    uint32_t mine = 0;
+    {
+        float x[ITEMS];
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const bool hit = tid + j * THREADS < n && v[j] == tv;
-        const unsigned long long m = __ballot(hit);
-        in_wave[j] = static_cast<uint32_t>(__popcll(m & ((1ull << lane) - 1ull)));
-        mine |= hit ? 1u << j : 0u;
-        if (lane == 0) w_hits[wave][j] = static_cast<uint16_t>(__popcll(m));
+        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const bool hit = tid + j * THREADS < n && x[j] == tv;
+            const unsigned long long m = __ballot(hit);
+            mine |= hit ? 1u << j : 0u;
+            if (lane == 0) w_mask[wave][j] = m;
+        }
     }
     __syncthreads();
     if (mine) {
         uint32_t before = 0;
-#pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             uint32_t lower = 0, all = 0;
             for (int w = 0; w < NW; ++w) {
-                const uint32_t h = w_hits[w][j];
+                const uint32_t h = static_cast<uint32_t>(__popcll(w_mask[w][j]));
                 lower += w < wave ? h : 0u;
                 all += h;
             }
-            if (((mine >> j) & 1u) && before + lower + in_wave[j] + 1 == r) thr_idx[f] = tid + j * THREADS;
+            const uint32_t in_wave = static_cast<uint32_t>(__popcll(w_mask[wave][j] & ((1ull << lane) - 1ull)));
+            if (((mine >> j) & 1u) && before + lower + in_wave + 1 == r) thr_idx[f] = tid + j * THREADS;
             before += all;
         }
     }
@@ -699,12 +698,12 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
     uint8_t* only = nullptr;
     if (n >= kBucketMinN && ws && ws_bytes >= estimate_ws_bytes(F, n)) {
         only = static_cast<uint8_t*>(ws);
-        if (n <= 1024 * 8)
-            hipLaunchKernelGGL((estimate_bucket_kernel<1024, 8>), dim3(F), dim3(1024), 0, st, W, n, alpha, beta, K, thr_val,
-                               thr_idx, aiu, K_prev, upper_prev, max_change, only);
+        if (n <= 512 * 16)
+            hipLaunchKernelGGL((estimate_bucket_kernel<512, 16, 2048, 512>), dim3(F), dim3(512), 0, st, W, n, alpha, beta,
+                               K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
         else
-            hipLaunchKernelGGL((estimate_bucket_kernel<1024, 13>), dim3(F), dim3(1024), 0, st, W, n, alpha, beta, K, thr_val,
-                               thr_idx, aiu, K_prev, upper_prev, max_change, only);
+            hipLaunchKernelGGL((estimate_bucket_kernel<512, 26, 2048, 512>), dim3(F), dim3(512), 0, st, W, n, alpha, beta,
+                               K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
         if (int rc = launch_status()) return rc;
     }
 #define DAB_EST(T, I) \
