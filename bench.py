@@ -126,7 +126,7 @@ class Schedule:
     """One step of all layers over HIP streams of equal (default) priority.
 
     The weight side of a layer (estimation, weight packing) depends on no activation, so the
-    weight sides run on side streams (longest first, spread by sort work) while the current
+    weight sides run on side streams (the heaviest layer alone, the others dealt out in layer order) while the current
     stream packs the activations of all layers (every input is resident when the step starts;
     memory-bound work beside the LDS-bound estimation).  The binary products then alternate
     between the current stream and one more: a product waits for its own layer's weights only
@@ -142,15 +142,18 @@ class Schedule:
         self.states = states
         self.side = [torch.cuda.Stream() for _ in range(n_side)]
         self.extra = [torch.cuda.Stream() for _ in range(max(n_product, 1) - 1)] if n_side > 0 else []
-        # longest-processing-time assignment by sort work F * n; layer order kept inside a stream
-        load = [0.0] * max(n_side, 1)
+        # the layer with by far the most weights (conv6) has a side stream to itself; the others are
+        # dealt out in layer order over the remaining side streams, so that their weights become
+        # ready in the order the products need them
         self.assign = [[] for _ in range(max(n_side, 1))]
-        for i in sorted(range(len(states)), key=lambda i: -states[i].W2.numel()):
-            q = min(range(len(load)), key=lambda q: load[q])
-            load[q] += states[i].W2.numel()
-            self.assign[q].append(i)
-        for a in self.assign:
-            a.sort()
+        heavy = max(range(len(states)), key=lambda i: states[i].W2.numel())
+        if n_side >= 2:
+            self.assign[0].append(heavy)
+            rest = [i for i in range(len(states)) if i != heavy]
+            for k, i in enumerate(rest):
+                self.assign[1 + k % (n_side - 1)].append(i)
+        else:
+            self.assign[0] = list(range(len(states)))
         self.fork = torch.cuda.Event()
         self.packed = torch.cuda.Event()
         self.ready = [torch.cuda.Event() for _ in self.side]

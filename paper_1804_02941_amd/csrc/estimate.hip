@@ -21,6 +21,11 @@
 //   4. the split descriptor: the value at the split and, among equal values, the original
 //      index up to which they belong to the lower group (recovered from the unsorted row,
 //      so the sort itself carries no indices).
+//
+// Long rows (4096 weights and more) go first through a kernel that needs no full sort (further
+// down: value buckets with exact sums, a bound on D inside every bucket, exact ranking of the few
+// elements that can hold the arg-max); the sort kernel then only works on the rows that kernel
+// hands over, and does every row when the caller gives no workspace for the hand-over flags.
 #include "dab_internal.h"
 
 namespace dab {

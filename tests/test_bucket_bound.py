@@ -1,0 +1,97 @@
+"""The mathematics behind estimating long rows without a full sort (CPU check, numpy only).
+
+The GPU kernel puts a row into value buckets, knows for every bucket the number N_b and sum S_b of
+all smaller elements, and bounds D at the positions inside a bucket without knowing their order:
+with j of the bucket's c elements below the split, the prefix sum lies between
+L(j) = max(S_b + j lo, S_e - (c-j) hi) and U(j) = min(S_b + j hi, S_e - (c-j) lo) for value bounds
+lo <= x <= hi of the bucket, and D(i, P) = P^2/i + (T-P)^2/(n-i) is jointly convex in (i, P), so
+over that convex region it is largest at a vertex.  This test evaluates that bound with numpy and
+checks it against the oracle's exact D at every position, and that few buckets survive it.
+"""
+import numpy as np
+import pytest
+
+from oracle import estimate as oest
+
+
+def vertex_bound(Sb, Se, c, i0, lo, hi, T, n):
+    """Upper bound of D over the positions i0 + j, j = 1 .. c-1, of one bucket."""
+    def D(P, i):
+        return P * P / i + (T - P) ** 2 / (n - i)
+
+    def L(j):
+        return max(Sb + j * lo, Se - (c - j) * hi)
+
+    def U(j):
+        return min(Sb + j * hi, Se - (c - j) * lo)
+
+    ja, jb = 1.0, float(c - 1)
+    jl = min(max((Sb - Se + c * hi) / (hi - lo), ja), jb)
+    ju = min(max((Se - Sb - c * lo) / (hi - lo), ja), jb)
+    pts = [(L(ja), ja), (U(ja), ja), (L(jb), jb), (U(jb), jb), (L(jl), jl), (U(ju), ju)]
+    return max(D(P, i0 + j) for P, j in pts)
+
+
+@pytest.mark.parametrize("kind", ["gauss", "mixture", "laplace", "onesided"])
+def test_bound_holds_and_prunes(kind):
+    rng = np.random.default_rng(len(kind))
+    n, NB = 6000, 2048
+    if kind == "gauss":
+        w = rng.standard_normal(n) * 0.05 + 0.01
+    elif kind == "mixture":
+        w = np.where(rng.random(n) < 0.7, 0.3, -0.7) * 0.04 + 0.02 * rng.standard_normal(n)
+    elif kind == "laplace":
+        w = rng.laplace(0.004, 0.03, n)
+    else:
+        w = np.abs(rng.standard_normal(n)) + 0.25
+    w = w.astype(np.float32).astype(np.float64)
+    order, P, D = oest.split_scores(w)                    # D[i-1] = D_i, exact in sorted order
+    ws = w[order]
+    T = P[-1]
+    vmin, vmax = ws[0], ws[-1]
+    width = (vmax - vmin) / (NB * (1 - 1 / 4096))
+    bucket = np.minimum(((ws - vmin) / width).astype(int), NB - 1)
+    best_end, survivors, checked = -np.inf, 0, 0
+    alive = set()
+    ends = {}
+    for b in np.unique(bucket):
+        idx = np.flatnonzero(bucket == b)
+        i0, iend = idx[0], idx[-1] + 1                    # N_b and N_b + c
+        if iend < n:
+            ends[b] = D[iend - 1]
+            best_end = max(best_end, D[iend - 1])
+    for b in np.unique(bucket):
+        idx = np.flatnonzero(bucket == b)
+        c, i0 = len(idx), idx[0]
+        if c < 2:
+            continue
+        Sb = P[i0 - 1] if i0 > 0 else 0.0
+        Se = P[i0 + c - 1]
+        lo, hi = vmin + b * width, vmin + (b + 1) * width
+        bound = vertex_bound(Sb, Se, c, i0, lo, hi, T, n)
+        inside = D[i0:i0 + c - 1]                          # positions i0+1 .. i0+c-1
+        assert inside.max() <= bound * (1 + 1e-12)
+        checked += 1
+        if bound >= best_end * (1 - 1e-6):
+            survivors += c
+            alive.add(int(b))
+    assert checked > 100
+    # the true optimum is at a bucket end or inside a surviving bucket; few elements survive
+    assert survivors < 300
+    i_star = int(np.flatnonzero(D == D.max())[-1]) + 1       # position of the arg-max (its last element is ws[i*-1])
+    b_star = int(bucket[i_star - 1])
+    at_bucket_end = i_star == n or bucket[i_star] != b_star
+    assert at_bucket_end or b_star in alive
+
+
+def test_joint_convexity_of_the_score():
+    """D(i, P) is convex along arbitrary segments of the (i, P) plane (0 < i < n)."""
+    rng = np.random.default_rng(3)
+    n, T = 1000.0, 37.5
+    for _ in range(2000):
+        i1, i2 = rng.uniform(1, n - 1, 2)
+        P1, P2 = rng.uniform(-200, 200, 2)
+        t = rng.uniform(0, 1)
+        D = lambda P, i: P * P / i + (T - P) ** 2 / (n - i)
+        mid = D(t * P1 + (1 - t) * P2, t * i1 + (1 - t) * i2)
+        assert mid <= t * D(P1, i1) + (1 - t) * D(P2, i2) + 1e-9 * (abs(mid) + 1)
