@@ -103,13 +103,14 @@ int dab_last_hip_error(void);
  *                  group iff w_i < thr_val or (w_i == thr_val and i <= thr_idx)
  *   alpha_is_upper [F] uint8 out: 1 if the alpha group is the upper group
  *   ws, ws_bytes   scratch of at least dab_estimate_workspace_bytes(F, n) bytes (one flag per
- *                  filter for long rows).  With it, long rows are estimated without a full
- *                  sort: value buckets with exact integer sums give D at every bucket end
- *                  and an upper bound inside every bucket, and only the few elements of
- *                  the buckets that can hold the arg-max are ranked exactly; rows where
- *                  that does not apply (many equal values) are flagged and sorted.  The
- *                  result is the same split.  ws may be NULL (or too small): then every
- *                  row is sorted.
+ *                  filter for rows of 4096 weights and more, nothing for shorter rows).
+ *                  Rows of more than 256 weights are estimated without a full sort: value
+ *                  buckets with exact integer sums give D at every bucket end and an
+ *                  upper bound inside every bucket, and only the few elements of the
+ *                  buckets that can hold the arg-max are ranked exactly; rows where that
+ *                  does not apply (many equal values) are sorted, the long ones through
+ *                  their flag in ws by a second kernel.  The result is the same split.
+ *                  ws may be NULL (or too small): then every long row is sorted.
  * Errors: NULL pointers, F < 1 or n < 2 (a filter needs both groups non-empty)
  * -> DAB_ERR_SHAPE; n above the largest supported row (dab_estimate_max_n())
  * -> DAB_ERR_UNSUPPORTED.

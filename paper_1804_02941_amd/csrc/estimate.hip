@@ -22,10 +22,12 @@
 //      index up to which they belong to the lower group (recovered from the unsorted row,
 //      so the sort itself carries no indices).
 //
-// Long rows (4096 weights and more) go first through a kernel that needs no full sort (further
-// down: value buckets with exact sums, a bound on D inside every bucket, exact ranking of the few
-// elements that can hold the arg-max); the sort kernel then only works on the rows that kernel
-// hands over, and does every row when the caller gives no workspace for the hand-over flags.
+// Rows of more than 256 weights first go through a search that needs no full sort (further down:
+// value buckets with exact sums, a bound on D inside every bucket, exact ranking of the few
+// elements that can hold the arg-max), and only rows it cannot finish are sorted: by the same
+// workgroup for rows below 4096 weights (one launch, the row in registers), and for longer rows by
+// the sort kernel launched behind, which then only works on the rows handed over (and does every
+// row when the caller gives no workspace for the hand-over flags).
 #include "dab_internal.h"
 
 namespace dab {
@@ -71,6 +73,51 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
     return v;
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ long long dpp_add(long long v) {
+    const uint32_t lo = static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(v)), CTRL, ROW_MASK, 0xf, false));
+    const uint32_t hi = static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<unsigned long long>(v) >> 32), CTRL, ROW_MASK, 0xf, false));
+    return v + static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo);
+}
+__device__ __forceinline__ long long wave_inclusive_scan_i64(long long v) {
+    v = dpp_add<0x111, 0xf>(v);
+    v = dpp_add<0x112, 0xf>(v);
+    v = dpp_add<0x114, 0xf>(v);
+    v = dpp_add<0x118, 0xf>(v);
+    v = dpp_add<0x142, 0xa>(v);
+    v = dpp_add<0x143, 0xc>(v);
+    return v;
+}
+// The same moves for reductions: a lane without a source gets its own value back, and after the six
+// steps lane 63 holds the result over the wavefront (the other lanes hold partial ones).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_from(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_from(float v) {
+    return __int_as_float(dpp_from<CTRL, ROW_MASK>(__float_as_int(v)));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_from(double v) {
+    return __hiloint2double(dpp_from<CTRL, ROW_MASK>(__double2hiint(v)), dpp_from<CTRL, ROW_MASK>(__double2loint(v)));
+}
+#define DAB_DPP_STEPS(STEP) \
+    STEP(0x111, 0xf) STEP(0x112, 0xf) STEP(0x114, 0xf) STEP(0x118, 0xf) STEP(0x142, 0xa) STEP(0x143, 0xc)
+__device__ __forceinline__ void wave_min_max_f32(float& mn, float& mx) {      // results in lane 63
+#define DAB_STEP(C, M) { const float a = dpp_from<C, M>(mn), b = dpp_from<C, M>(mx); mn = fminf(mn, a); mx = fmaxf(mx, b); }
+    DAB_DPP_STEPS(DAB_STEP)
+#undef DAB_STEP
+}
+__device__ __forceinline__ double wave_max_f64(double v) {                    // result in lane 63
+#define DAB_STEP(C, M) v = fmax(v, dpp_from<C, M>(v));
+    DAB_DPP_STEPS(DAB_STEP)
+#undef DAB_STEP
+    return v;
+}
+
 // Candidate split: D = num / den with den > 0; P is the prefix sum at the split.
 struct Best {
     double num, den, P;
@@ -80,16 +127,24 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b) {   // a be
     const double l = a.num * b.den, r = b.num * a.den;
     return l > r || (l == r && a.i > b.i);
 }
+__device__ __forceinline__ Best wave_best_of(Best v) {                        // result in lane 63
+#define DAB_STEP(C, M) \
+    { \
+        const Best o{dpp_from<C, M>(v.num), dpp_from<C, M>(v.den), dpp_from<C, M>(v.P), dpp_from<C, M>(v.i)}; \
+        if (better(o, v)) v = o; \
+    }
+    DAB_DPP_STEPS(DAB_STEP)
+#undef DAB_STEP
+    return v;
+}
 
+// Row f of the layer, by the workgroup's THREADS threads (all of them call this together).
 template <int THREADS, int ITEMS>
-__global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restrict__ Wt, int n,
-                                                           float* __restrict__ alpha, float* __restrict__ beta,
-                                                           int32_t* Kout, float* __restrict__ thr_val,
-                                                           int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
-                                                           const int32_t* K_prev, const uint8_t* upper_prev,
-                                                           int max_change, const uint8_t* __restrict__ only) {
+__device__ __forceinline__ void sort_row(const float* __restrict__ Wt, int n, int f, float* __restrict__ alpha,
+                                         float* __restrict__ beta, int32_t* Kout, float* __restrict__ thr_val,
+                                         int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper, const int32_t* K_prev,
+                                         const uint8_t* upper_prev, int max_change) {
     static_assert(ITEMS >= 1 && ITEMS <= 15, "a digit counter has 4 bits");
-    if (only && !only[blockIdx.x]) return;      // the bucket kernel below has finished this row
     constexpr int NW = THREADS / 64;
     constexpr int N = THREADS * ITEMS;
     __shared__ uint32_t keys[N];
@@ -101,9 +156,8 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     __shared__ int r_s;
     __shared__ float thr_s;
 
-    DAB_RESERVE_VGPRS();   // the 7-items-per-thread instantiations would land on exactly 64 VGPRs
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float* row = Wt + static_cast<size_t>(blockIdx.x) * n;
+    const float* row = Wt + static_cast<size_t>(f) * n;
 
     for (int i = tid; i < N; i += THREADS) keys[i] = i < n ? float_to_key(row[i]) : 0xFFFFFFFFu;
     __syncthreads();
@@ -186,7 +240,7 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
     // the previous outputs may be the buffers this call overwrites)
     int wlo = 1, whi = n - 1;
     if (K_prev) {
-        int ip = upper_prev[blockIdx.x] ? n - K_prev[blockIdx.x] : K_prev[blockIdx.x];
+        int ip = upper_prev[f] ? n - K_prev[f] : K_prev[f];
         ip = min(max(ip, 1), n - 1);
         const int d = min(max(max_change, 0), n);
         wlo = max(1, ip - d);
@@ -222,7 +276,6 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
         const double mu_lower = b.P / static_cast<double>(is);
         const double mu_upper = (T - b.P) / static_cast<double>(n - is);
         const bool upper = fabs(mu_upper) >= fabs(mu_lower);
-        const int f = blockIdx.x;
         alpha[f] = static_cast<float>(upper ? mu_upper : mu_lower);
         beta[f] = static_cast<float>(upper ? mu_lower : mu_upper);
         Kout[f] = upper ? n - is : is;
@@ -254,25 +307,38 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
         uint32_t seen = cbase;
         for (int i = lo; i < hi; ++i) {
             if (row[i] == tv && ++seen == r) {
-                thr_idx[blockIdx.x] = i;
+                thr_idx[f] = i;
                 break;
             }
         }
     }
 }
 
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restrict__ Wt, int n,
+                                                           float* __restrict__ alpha, float* __restrict__ beta,
+                                                           int32_t* Kout, float* __restrict__ thr_val,
+                                                           int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
+                                                           const int32_t* K_prev, const uint8_t* upper_prev,
+                                                           int max_change, const uint8_t* __restrict__ only) {
+    if (only && !only[blockIdx.x]) return;      // the bucket kernel below has finished this row
+    DAB_RESERVE_VGPRS();   // the 7-items-per-thread instantiations would land on exactly 64 VGPRs
+    sort_row<THREADS, ITEMS>(Wt, n, static_cast<int>(blockIdx.x), alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev,
+                             upper_prev, max_change);
+}
+
 // ---------------------------------------------------------------- estimation without the full sort
 // The arg-max of D needs the sorted order only near the optimum.  One pass of LDS atomics puts the
-// row into 4096 value buckets (count and exact fixed-point sum each), a scan gives, for every
+// row into NB value buckets (count and exact fixed-point sum each), a scan gives, for every
 // bucket, the number and sum of all smaller elements, and with them D at the last element of every
-// bucket exactly and an upper bound of D at the positions inside it: there P_i lies between
-// S_b + j*lo_b and S_b + j*hi_b (and the same from the bucket's other end), and D is convex in P,
-// so the larger of the two ends bounds it.  Only buckets whose bound reaches the best bucket-end
-// value can hold the arg-max; their elements (a few dozen for the weight distributions of a
-// network) are ranked exactly, with exact prefix sums, and the split is chosen among them by the
-// same comparison as in the sort kernel.  A row whose candidates exceed the list (many equal
-// values, a constant row) is flagged and left to the sort kernel, which is launched behind this
-// one and returns at once for rows that are not flagged.
+// bucket exactly and an upper bound of D at the positions inside it (the prefix sum there is
+// confined to a convex polygon of the (i, P) plane, and D is largest at one of its vertices).
+// Only buckets whose bound reaches the best bucket-end value can hold the arg-max; their elements
+// (a few dozen for the weight distributions of a network) are ranked exactly, with exact prefix
+// sums, and the split is chosen among them by the same comparison as in the sort.  All copies of
+// a value share a bucket, so the candidates also tell which copy of the split value is the last of
+// the lower group in the order of the row.  A row whose candidates exceed the list (many equal
+// values, a constant row) is left to the sort.
 //
 // Sums are integers: with 2^e > max |w| the values are scaled by 2^(48 - e) and rounded to int64,
 // which is exact for every element within 2^-24 of the row's largest magnitude (smaller ones are
@@ -280,16 +346,17 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
 constexpr int kFastBigBucket = 96;      // buckets above this size are candidates without a bound
 
 // THREADS threads with up to ITEMS elements each, NB value buckets, at most CAP candidate elements.
-// The row is read from global memory (L2) in each of its four passes, every load of a pass in
+// The row is read from global memory (L2) in each of its three passes, every load of a pass in
 // flight at once, so nothing of it stays in registers between the phases, little LDS is needed and
 // several workgroups share a compute unit: every phase is a short latency chain between barriers.
-template <int THREADS, int ITEMS, int NB, int CAP>
-__global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* __restrict__ Wt, int n,
-                                                                  float* __restrict__ alpha, float* __restrict__ beta,
-                                                                  int32_t* Kout, float* __restrict__ thr_val,
-                                                                  int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
-                                                                  const int32_t* K_prev, const uint8_t* upper_prev,
-                                                                  int max_change, uint8_t* __restrict__ fallback) {
+//
+// Short rows (REG) are read once and stay in registers.  The result says whether the row is done
+// (the same for every thread of the workgroup); nothing has been written when it is not.
+template <int THREADS, int ITEMS, int NB, int CAP, bool REG>
+__device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, int f, float* __restrict__ alpha,
+                                           float* __restrict__ beta, int32_t* Kout, float* __restrict__ thr_val,
+                                           int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper, const int32_t* K_prev,
+                                           const uint8_t* upper_prev, int max_change) {
     constexpr int NW = THREADS / 64;
     constexpr int BPT = NB / THREADS;                              // buckets per thread
     __shared__ uint32_t cnt[NB + 1];                               // counts, then the exclusive prefix N_b (N_NB = n)
@@ -297,46 +364,40 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     __shared__ uint8_t cand[NB];
     __shared__ uint32_t lkey[CAP];
     __shared__ long long lq[CAP];
-    __shared__ uint16_t lb[CAP];
+    __shared__ uint16_t lb[CAP], lidx[CAP];                         // bucket and index in the row of a candidate
     __shared__ float w_min[NW], w_max[NW];
     __shared__ uint32_t w_cnt[NW], w_cnt2[NW];
     __shared__ long long w_sum[NW];
     __shared__ double w_d[NW];
     __shared__ Best wave_best[NW];
-    __shared__ uint32_t nlist_s, r_s;
-    __shared__ float thr_s;
-    __shared__ unsigned long long w_mask[NW][ITEMS];
+    __shared__ uint32_t nlist_s, r_s, wkey_s;
+    static_assert(CAP <= THREADS && THREADS * ITEMS <= 65536, "a candidate per thread, 16-bit indices");
 
-    DAB_RESERVE_VGPRS();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int f = blockIdx.x;
     const float* row = Wt + static_cast<size_t>(f) * n;
+    float x[ITEMS];
+    auto read_row = [&]() {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+    };
 
     // ---- range of the row
     float mn = INFINITY, mx = -INFINITY;
     {
-        float x[ITEMS];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+        read_row();
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             mn = fminf(mn, x[j]);                                  // (the clamped repeats change nothing)
             mx = fmaxf(mx, x[j]);
         }
     }
-    for (int d = 32; d >= 1; d >>= 1) {
-        mn = fminf(mn, __shfl_xor(mn, d, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
-    }
-    if (lane == 0) { w_min[wave] = mn; w_max[wave] = mx; }
+    wave_min_max_f32(mn, mx);
+    if (lane == 63) { w_min[wave] = mn; w_max[wave] = mx; }
     for (int b = tid; b < NB; b += THREADS) { cnt[b] = 0u; sum[b] = 0ull; cand[b] = 0; }
     if (tid == 0) nlist_s = 0u;
     __syncthreads();
     for (int w = 0; w < NW; ++w) { mn = fminf(mn, w_min[w]); mx = fmaxf(mx, w_max[w]); }
-    if (!(mx > mn) || !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY)) {   // constant row (or not finite)
-        if (tid == 0) fallback[f] = 1;
-        return;
-    }
+    if (!(mx > mn) || !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY)) return false;   // constant row (or not finite)
     const float M = fmaxf(fabsf(mn), fabsf(mx));
     const int ex = static_cast<int>((__float_as_uint(M) >> 23) & 0xFFu) - 126;     // M < 2^ex
     const double scale = ldexp(1.0, 48 - ex);
@@ -355,9 +416,7 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
 
     // ---- histogram: count and exact sum per bucket
     {
-        float x[ITEMS];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+        if (!REG) read_row();
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             if (tid + j * THREADS < n) {
@@ -388,12 +447,7 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
             srun += ts;
         }
         const uint32_t cinc = wave_inclusive_scan_u32(crun);
-        long long sinc = srun;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const long long o = __shfl_up(sinc, d, 64);
-            if (lane >= d) sinc += o;
-        }
+        const long long sinc = wave_inclusive_scan_i64(srun);
         if (lane == 63) { w_cnt[wave] = cinc; w_sum[wave] = sinc; }
         __syncthreads();
         uint32_t cbase = cinc - crun;
@@ -440,8 +494,8 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
         if (iend > i0 && iend >= wlo && iend <= whi)
             dend = fmax(dend, score(static_cast<double>(static_cast<long long>(sum[b + 1])), static_cast<double>(iend)));
     }
-    for (int d = 32; d >= 1; d >>= 1) dend = fmax(dend, __shfl_xor(dend, d, 64));
-    if (lane == 0) w_d[wave] = dend;
+    dend = wave_max_f64(dend);
+    if (lane == 63) w_d[wave] = dend;
     __syncthreads();
     for (int w = 0; w < NW; ++w) dend = fmax(dend, w_d[w]);
     const double need = dend - 1e-6 * fabs(dend);
@@ -460,16 +514,30 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
         if (c == 0) continue;
         const double Sb = static_cast<double>(static_cast<long long>(sum[b]));
         const double Se = static_cast<double>(static_cast<long long>(sum[b + 1]));
+        // D(i, P) >= need without a division: both sides times i (n - i) > 0
+        auto reaches = [&](double P, double i) -> bool {
+            const double rest = T - P, r = dn - i;
+            return P * P * r + rest * rest * i >= need * (i * r);
+        };
         bool is_cand = false;
-        if (iend >= wlo && iend <= whi) is_cand = score(Se, static_cast<double>(iend)) >= need;
+        if (iend >= wlo && iend <= whi) is_cand = reaches(Se, static_cast<double>(iend));
         const int jlo = max(1, wlo - i0), jhi = min(c - 1, whi - i0);
         if (!is_cand && jlo <= jhi) {
             if (c > kFastBigBucket) {
                 is_cand = true;
             } else {
-                // value range of the bucket in fixed-point units, widened against rounding
-                const double lo = (vmin + (static_cast<double>(b) - 2e-3) * bwidth) * scale - 1.0;
-                const double hi = (vmin + (static_cast<double>(b) + 1.0 + 2e-3) * bwidth) * scale + 1.0;
+                // value range of the bucket, widened against the rounding of the bucket index
+                const double lov = vmin + (static_cast<double>(b) - 2e-3) * bwidth;
+                const double hiv = vmin + (static_cast<double>(b) + 1.0 + 2e-3) * bwidth;
+                // Cheap test first (most buckets end here): with values of one sign, P inside the bucket
+                // lies between the prefix sums at its two ends, so D is at most the larger P^2 over the
+                // smallest i plus the larger (T - P)^2 over the smallest n - i.
+                if (lov >= 0.0 || hiv <= 0.0) {
+                    const double il = static_cast<double>(i0 + jlo), rr = static_cast<double>(n - i0 - jhi);
+                    const double rb = T - Sb, re = T - Se;
+                    if (fmax(Sb * Sb, Se * Se) * rr + fmax(rb * rb, re * re) * il < need * (il * rr)) continue;
+                }
+                const double lo = lov * scale - 1.0, hi = hiv * scale + 1.0;    // in fixed-point units
                 const double dc = static_cast<double>(c), ja = static_cast<double>(jlo), jb = static_cast<double>(jhi);
                 auto L = [&](double j) { return fmax(Sb + j * lo, Se - (dc - j) * hi); };
                 auto U = [&](double j) { return fmin(Sb + j * hi, Se - (dc - j) * lo); };
@@ -477,10 +545,8 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
                 const double jl = fmin(fmax((Sb - Se + dc * hi) * inv, ja), jb);    // the lines of L cross here
                 const double ju = fmin(fmax((Se - Sb - dc * lo) * inv, ja), jb);    // the lines of U cross here
                 const double di0 = static_cast<double>(i0);
-                double best_b = fmax(fmax(score(L(ja), di0 + ja), score(U(ja), di0 + ja)),
-                                     fmax(score(L(jb), di0 + jb), score(U(jb), di0 + jb)));
-                best_b = fmax(best_b, fmax(score(L(jl), di0 + jl), score(U(ju), di0 + ju)));
-                is_cand = best_b >= need;
+                is_cand = reaches(L(ja), di0 + ja) || reaches(U(ja), di0 + ja) || reaches(L(jb), di0 + jb) ||
+                          reaches(U(jb), di0 + jb) || reaches(L(jl), di0 + jl) || reaches(U(ju), di0 + ju);
             }
         }
         if (is_cand) {
@@ -493,16 +559,11 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     __syncthreads();
     uint32_t nc = 0;
     for (int w = 0; w < NW; ++w) nc += w_cnt2[w];
-    if (nc > CAP || nc == 0) {
-        if (tid == 0) fallback[f] = 1;
-        return;
-    }
+    if (nc > CAP || nc == 0) return false;
 
     // ---- the candidates' elements
     {
-        float x[ITEMS];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
+        if (!REG) read_row();
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             if (tid + j * THREADS < n) {
@@ -512,6 +573,7 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
                     lkey[slot] = float_to_key(x[j]);
                     lq[slot] = fixed_of(x[j]);
                     lb[slot] = static_cast<uint16_t>(b);
+                    lidx[slot] = static_cast<uint16_t>(tid + j * THREADS);
                 }
             }
         }
@@ -519,62 +581,57 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
     __syncthreads();
 
     // ---- exact position and prefix sum of every candidate: elements of its bucket that precede it
+    // (thread e owns candidate e; among equal values it also counts those that come first in the row)
     Best best{-1.0, 1.0, 0.0, 0};
-    uint32_t my_key = 0, my_less = 0;
-    int my_i = 0;
-    for (int e = tid; e < static_cast<int>(nc); e += THREADS) {
+    uint32_t my_key = 0, my_less = 0, my_first = 0, my_idx = 0;
+    if (tid < static_cast<int>(nc)) {
+        const int e = tid;
         const uint32_t key = lkey[e];
         const int b = lb[e];
-        uint32_t within = 0, less = 0;
+        my_idx = lidx[e];
+        uint32_t within = 0, less = 0, first = 0;
         long long ps = 0;
 #pragma unroll 4
         for (int q = 0; q < static_cast<int>(nc); ++q) {          // branch-free: the LDS reads pipeline
             const uint32_t kq = lkey[q];
             const bool same = lb[q] == b;
             const bool lt = same && kq < key;
-            const bool le = same && (kq < key || (kq == key && q <= e));
+            const bool eq = same && kq == key;
+            const bool le = lt || (eq && q <= e);
             within += le ? 1u : 0u;
             less += lt ? 1u : 0u;
+            first += (eq && lidx[q] < my_idx) ? 1u : 0u;
             ps += le ? lq[q] : 0ll;
         }
+        my_key = key;
+        my_less = cnt[b] + less;
+        my_first = first;
         const int i = static_cast<int>(cnt[b] + within);
         if (i >= wlo && i <= whi) {
             const double P = static_cast<double>(static_cast<long long>(sum[b]) + ps);
             const double rest = T - P;
             const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
-            const Best candb{P * P * fr + rest * rest * fi, fi * fr, P, i};
-            if (better(candb, best)) {
-                best = candb;
-                my_key = key;
-                my_less = cnt[b] + less;
-                my_i = i;
-            }
+            best = Best{P * P * fr + rest * rest * fi, fi * fr, P, i};
         }
     }
+    const int my_i = best.i;
     // only the wavefronts that hold candidates (the first one, as a rule) reduce
     const int nwr = min(NW, static_cast<int>(nc + 63) >> 6);
     if (wave < nwr) {
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            const Best o{__shfl_xor(best.num, d, 64), __shfl_xor(best.den, d, 64), __shfl_xor(best.P, d, 64),
-                         __shfl_xor(best.i, d, 64)};
-            if (better(o, best)) best = o;
-        }
-        if (lane == 0) wave_best[wave] = best;
+        const Best wb = wave_best_of(best);
+        if (lane == 63) wave_best[wave] = wb;
     }
     __syncthreads();
     Best bb = wave_best[0];
     for (int w = 1; w < nwr; ++w)
         if (better(wave_best[w], bb)) bb = wave_best[w];
-    if (bb.i < 1) {                                                // no candidate inside the window: not expected
-        if (tid == 0) fallback[f] = 1;
-        return;
-    }
+    if (bb.i < 1) return false;                                    // no candidate inside the window: not expected
     if (my_i == bb.i) {                                            // exactly one thread holds the winning position
-        thr_s = key_to_float(my_key);
+        wkey_s = my_key;
         r_s = static_cast<uint32_t>(bb.i) - my_less;               // copies of the value in the lower group
     }
     __syncthreads();
+    const uint32_t wkey = wkey_s;
     if (tid == 0) {
         const int is = bb.i;
         const double mu_lower = bb.P / static_cast<double>(is) / scale;
@@ -584,43 +641,46 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
         beta[f] = static_cast<float>(upper ? mu_lower : mu_upper);
         Kout[f] = upper ? n - is : is;
         alpha_is_upper[f] = upper ? 1 : 0;
-        thr_val[f] = thr_s;
-        fallback[f] = 0;
+        thr_val[f] = key_to_float(wkey);
     }
 
-    // ---- original index of the r-th copy (in index order) of the split value.  Element j of thread
-    // t has index t + j*THREADS, so slot-major order is index order: the ballot of every slot goes
-    // to LDS, and only the threads that hold a copy (one, as a rule) work out their rank.
-    const float tv = thr_s;
-    const uint32_t r = r_s;
-    uint32_t mine = 0;
-    {
-        float x[ITEMS];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const bool hit = tid + j * THREADS < n && x[j] == tv;
-            const unsigned long long m = __ballot(hit);
-            mine |= hit ? 1u << j : 0u;
-            if (lane == 0) w_mask[wave][j] = m;
-        }
-    }
+    // ---- the split descriptor's index: the r-th copy of the split value in the order of the row.
+    // Every copy is a candidate (equal values share a bucket) and knows how many copies precede it.
+    if (tid < static_cast<int>(nc) && my_key == wkey && my_first + 1 == r_s) thr_idx[f] = static_cast<int32_t>(my_idx);
+    return true;
+}
+
+// Long rows: three passes over the row in L2, a flag per row for the sort kernel launched behind.
+template <int THREADS, int ITEMS, int NB, int CAP>
+__global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* __restrict__ Wt, int n,
+                                                                  float* __restrict__ alpha, float* __restrict__ beta,
+                                                                  int32_t* Kout, float* __restrict__ thr_val,
+                                                                  int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
+                                                                  const int32_t* K_prev, const uint8_t* upper_prev,
+                                                                  int max_change, uint8_t* __restrict__ fallback) {
+    DAB_RESERVE_VGPRS();
+    const int f = static_cast<int>(blockIdx.x);
+    const bool done = bucket_row<THREADS, ITEMS, NB, CAP, false>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper,
+                                                                 K_prev, upper_prev, max_change);
+    if (threadIdx.x == 0) fallback[f] = done ? 0 : 1;
+}
+
+// Short rows: the row stays in registers, and a row the buckets cannot finish is sorted by the same
+// workgroup, so one launch does the layer.
+template <int THREADS, int ITEMS, int NB, int CAP>
+__global__ __launch_bounds__(THREADS) void estimate_short_kernel(const float* __restrict__ Wt, int n,
+                                                                 float* __restrict__ alpha, float* __restrict__ beta,
+                                                                 int32_t* Kout, float* __restrict__ thr_val,
+                                                                 int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper,
+                                                                 const int32_t* K_prev, const uint8_t* upper_prev,
+                                                                 int max_change) {
+    DAB_RESERVE_VGPRS();
+    const int f = static_cast<int>(blockIdx.x);
+    if (bucket_row<THREADS, ITEMS, NB, CAP, true>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev,
+                                                  upper_prev, max_change))
+        return;
     __syncthreads();
-    if (mine) {
-        uint32_t before = 0;
-        for (int j = 0; j < ITEMS; ++j) {
-            uint32_t lower = 0, all = 0;
-            for (int w = 0; w < NW; ++w) {
-                const uint32_t h = static_cast<uint32_t>(__popcll(w_mask[w][j]));
-                lower += w < wave ? h : 0u;
-                all += h;
-            }
-            const uint32_t in_wave = static_cast<uint32_t>(__popcll(w_mask[wave][j] & ((1ull << lane) - 1ull)));
-            if (((mine >> j) & 1u) && before + lower + in_wave + 1 == r) thr_idx[f] = tid + j * THREADS;
-            before += all;
-        }
-    }
+    sort_row<THREADS, ITEMS>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev, upper_prev, max_change);
 }
 
 // ---------------------------------------------------------------- sign split (XNOR-Net / BWN)
@@ -687,7 +747,8 @@ static int launch_estimate(const float* W, int F, int n, float* alpha, float* be
     return launch_status();
 }
 
-constexpr int kBucketMinN = 4096;        // shorter rows go to the sort kernel directly (it is faster there)
+constexpr int kBucketMinN = 4096;        // rows from here on: bucket kernel, then the sort kernel for the rows it flags
+constexpr int kShortMinN = 256;          // rows above this and below kBucketMinN: the one-launch kernel for short rows
 
 static size_t estimate_ws_bytes(int F, int n) {
     return n >= kBucketMinN ? (static_cast<size_t>(F) + 255) & ~static_cast<size_t>(255) : 0;
@@ -711,6 +772,23 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
                                K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
         if (int rc = launch_status()) return rc;
     }
+    // rows between the two: one launch, buckets first and the sort inside the kernel where needed
+#define DAB_SHORT(T, I, NB) \
+    do { \
+        hipLaunchKernelGGL((estimate_short_kernel<T, I, NB, 256>), dim3(F), dim3(T), 0, st, W, n, alpha, beta, K, thr_val, \
+                           thr_idx, aiu, K_prev, upper_prev, max_change); \
+        return launch_status(); \
+    } while (0)
+    if (n > kShortMinN && n < kBucketMinN) {
+        if (n <= 256 * 3) DAB_SHORT(256, 3, 512);
+        if (n <= 256 * 5) DAB_SHORT(256, 5, 1024);
+        if (n <= 256 * 7) DAB_SHORT(256, 7, 1024);
+        if (n <= 256 * 9) DAB_SHORT(256, 9, 1024);
+        if (n <= 256 * 11) DAB_SHORT(256, 11, 1024);
+        if (n <= 512 * 7) DAB_SHORT(512, 7, 2048);
+        DAB_SHORT(512, 9, 2048);
+    }
+#undef DAB_SHORT
 #define DAB_EST(T, I) \
     return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only, st)
     if (n <= 64 * 3) DAB_EST(64, 3);
