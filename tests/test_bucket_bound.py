@@ -32,6 +32,14 @@ def vertex_bound(Sb, Se, c, i0, lo, hi, T, n):
     return max(D(P, i0 + j) for P, j in pts)
 
 
+def box_bound(Sb, Se, c, i0, T, n):
+    """Cheaper bound for a bucket whose values share one sign: the prefix sum inside lies between
+    the sums at its two ends, so D is at most the larger P^2 over the smallest i plus the larger
+    (T - P)^2 over the smallest n - i."""
+    il, rr = i0 + 1, n - (i0 + c - 1)
+    return max(Sb * Sb, Se * Se) / il + max((T - Sb) ** 2, (T - Se) ** 2) / rr
+
+
 @pytest.mark.parametrize("kind", ["gauss", "mixture", "laplace", "onesided"])
 def test_bound_holds_and_prunes(kind):
     rng = np.random.default_rng(len(kind))
@@ -51,7 +59,7 @@ def test_bound_holds_and_prunes(kind):
     vmin, vmax = ws[0], ws[-1]
     width = (vmax - vmin) / (NB * (1 - 1 / 4096))
     bucket = np.minimum(((ws - vmin) / width).astype(int), NB - 1)
-    best_end, survivors, checked = -np.inf, 0, 0
+    best_end, survivors, checked, boxed, box_alive = -np.inf, 0, 0, 0, 0
     alive = set()
     ends = {}
     for b in np.unique(bucket):
@@ -71,11 +79,17 @@ def test_bound_holds_and_prunes(kind):
         bound = vertex_bound(Sb, Se, c, i0, lo, hi, T, n)
         inside = D[i0:i0 + c - 1]                          # positions i0+1 .. i0+c-1
         assert inside.max() <= bound * (1 + 1e-12)
+        if lo >= 0.0 or hi <= 0.0:                         # the quick test that runs first on the GPU
+            box = box_bound(Sb, Se, c, i0, T, n)
+            assert inside.max() <= box * (1 + 1e-12)
+            boxed += 1
+            box_alive += box >= best_end * (1 - 1e-6)
         checked += 1
         if bound >= best_end * (1 - 1e-6):
             survivors += c
             alive.add(int(b))
     assert checked > 100
+    assert boxed >= checked - 1 and box_alive < 0.2 * boxed    # it applies to all buckets but one, and discards most
     # the true optimum is at a bucket end or inside a surviving bucket; few elements survive
     assert survivors < 300
     i_star = int(np.flatnonzero(D == D.max())[-1]) + 1       # position of the arg-max (its last element is ws[i*-1])
