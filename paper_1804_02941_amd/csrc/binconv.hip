@@ -83,6 +83,16 @@ __device__ __forceinline__ uint32_t spread8(uint32_t x) {
     return x;
 }
 
+// 8 bits -> 8 fp4 codes (4 bytes): every byte holds two codes, so it takes one of four values, picked
+// by a byte permute from `lut` (byte v = the codes of the bit pair v) with the bit pairs as selectors.
+__device__ __forceinline__ uint32_t expand8(uint32_t x, uint32_t lut) {
+    x = (x | (x << 12)) & 0x000F000Fu;
+    x = (x | (x << 6)) & 0x03030303u;                       // byte j = bits 2j, 2j+1
+    return __builtin_amdgcn_perm(0u, lut, x);
+}
+constexpr uint32_t kLutPlusMinus = 0x222AA2AAu;            // bit 1 -> +1.0 (0x2), bit 0 -> -1.0 (0xA)
+constexpr uint32_t kLutOneZero = 0x22200200u;              // bit 1 -> 1.0 (0x2), bit 0 -> 0
+
 // ---------------------------------------------------------------- prepare
 __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, const uint32_t* __restrict__ A,
                                                               const uint32_t* __restrict__ E,
@@ -110,13 +120,13 @@ __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, 
                 if (y >= 0 && y < g.H && x >= 0 && x < g.W) {
                     const uint32_t bits = A[((static_cast<size_t>(b) * g.H + y) * g.W + x) * g.Cw + w];
                     const int nv = min(32, g.C - 32 * w);
-                    const uint32_t valid = nv == 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
                     uint32_t o[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint32_t s = spread8((bits >> (8 * q)) & 0xFFu);
-                        const uint32_t v = spread8((valid >> (8 * q)) & 0xFFu) * 0xFu;
-                        o[q] = (0xAAAAAAAAu ^ (s << 3)) & v;            // bit 1 -> +1.0, bit 0 -> -1.0, past C -> 0
+                    for (int q = 0; q < 4; ++q) o[q] = expand8((bits >> (8 * q)) & 0xFFu, kLutPlusMinus);
+                    if (nv < 32) {                                      // channels past C -> 0
+                        const uint32_t valid = (1u << nv) - 1u;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) o[q] &= spread8((valid >> (8 * q)) & 0xFFu) * 0xFu;
                     }
                     out = make_uint4(o[0], o[1], o[2], o[3]);
                 }
@@ -150,8 +160,8 @@ __global__ __launch_bounds__(256) void binconv_prepare_kernel(const MfmaGeom g, 
         uint4 out = make_uint4(0, 0, 0, 0);
         if (w < g.Cw && f < g.Fp) {
             const uint32_t bits = E[static_cast<size_t>(tap * g.Cw + w) * g.Fp + f];
-            out = make_uint4(spread8(bits & 0xFFu) << 1, spread8((bits >> 8) & 0xFFu) << 1,
-                             spread8((bits >> 16) & 0xFFu) << 1, spread8(bits >> 24) << 1);   // bit 1 -> 1.0
+            out = make_uint4(expand8(bits & 0xFFu, kLutOneZero), expand8((bits >> 8) & 0xFFu, kLutOneZero),
+                             expand8((bits >> 16) & 0xFFu, kLutOneZero), expand8(bits >> 24, kLutOneZero));
         }
         E4[i] = out;
         return;

@@ -158,10 +158,13 @@ __global__ __launch_bounds__(256) void pack_act_nchw_kernel(const float* __restr
 
 // ---------------------------------------------------------------- weights
 // One workgroup per (padded) filter column.  The filter is brought into LDS with coalesced
-// reads, a slab of whole channels at a time; one work item is then 64 consecutive channels
-// of one tap, gathered from LDS with stride kh*kw, compared, balloted and written as two
-// words of column f.  Per-tap counts are accumulated in LDS.  The slab holds a whole filter
-// of up to 24K weights, so most layers need one pass.
+// reads, a slab of whole channels at a time; a wavefront then takes one tap and four groups
+// of 64 consecutive channels at a time: gathered from LDS with stride kh*kw (four reads in
+// flight), compared (the compare's lane mask is the two bit words), written as words of
+// column f by two lanes.  The gather is bound by instruction issue (about fifteen per 64
+// weights), so the loop carries no division and no per-word branch.  Per-tap counts are
+// accumulated in LDS.  The slab holds a whole filter of up to 24K weights, so most layers
+// need one pass.
 constexpr int kWeightSlabFloats = 24 * 1024;   // 96 KB
 
 __global__ __launch_bounds__(1024) void pack_weights_kernel(const float* __restrict__ Wt, const float* __restrict__ thr_val,
@@ -219,25 +222,42 @@ __global__ __launch_bounds__(1024) void pack_weights_kernel(const float* __restr
         }
         for (int i = head + 4 * body4 + tid; i < count; i += blockDim.x) sl[i] = src[i];
         __syncthreads();
+        // Work items: (tap, chunk of four 64-channel groups), dealt out to the wavefronts.  The four
+        // LDS reads of an item are issued together; a compare writes the wavefront's mask directly,
+        // lanes 0 and 1 store its two words.  (Lanes past the slab's last channel read inside the
+        // slab's allocation, whole 64-channel groups, and are masked out of the ballot.)
         const int groups = (nc + 63) >> 6;                 // 64-channel groups in this slab
-        for (int it = wave; it < groups * T; it += nwaves) {
-            const int tap = it / groups;
-            const int grp = it - tap * groups;
-            const int cl = grp * 64 + lane;                // channel within the slab
-            bool bit = false;
-            if (cl < nc) {
-                const float w = sl[cl * T + tap];
-                const int idx = (c0 + cl) * T + tap;       // position in the flattened filter
-                const bool lower = w < tv || (w == tv && idx <= ti);
-                bit = lower != upper;
+        const int nchunks = (groups + 3) >> 2;
+        const int adv_t = nwaves / nchunks, adv_c = nwaves - adv_t * nchunks;
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);          // tell the compiler it is uniform
+        int tap = wave_u / nchunks, chunk = wave_u - tap * nchunks;
+        while (tap < T) {
+            const int g0 = chunk * 4;
+            const int gn = min(4, groups - g0);
+            const float* sp = sl + (g0 * 64 + lane) * T + tap;
+            float w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (u < gn) w[u] = sp[u * 64 * T];
+            const int w0 = (c0 >> 5) + g0 * 2;             // word index within the tap
+            uint32_t* ep = E + static_cast<size_t>(tap * Cw + w0 + (lane & 1)) * Fp + f;
+            uint32_t ones = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (u < gn) {
+                    const int cl = (g0 + u) * 64 + lane;   // channel within the slab
+                    const int idx = (c0 + cl) * T + tap;   // position in the flattened filter
+                    const bool lower = w[u] < tv || (w[u] == tv && idx <= ti);
+                    const unsigned long long mask = __ballot(cl < nc && lower != upper);
+                    ones += static_cast<uint32_t>(__popcll(mask));
+                    const uint32_t word = (lane & 1) ? static_cast<uint32_t>(mask >> 32) : static_cast<uint32_t>(mask);
+                    if (lane < 2 && w0 + 2 * u + lane < Cw) ep[static_cast<size_t>(2 * u) * Fp] = word;
+                }
             }
-            const unsigned long long mask = __ballot(bit);
-            if (lane == 0) {
-                const int w0 = (c0 >> 5) + grp * 2;        // word index within the tap
-                E[static_cast<size_t>(tap * Cw + w0) * Fp + f] = static_cast<uint32_t>(mask);
-                if (w0 + 1 < Cw) E[static_cast<size_t>(tap * Cw + w0 + 1) * Fp + f] = static_cast<uint32_t>(mask >> 32);
-                atomicAdd(&cnt[tap], static_cast<uint32_t>(__popcll(mask)));
-            }
+            if (lane == 0) atomicAdd(&cnt[tap], ones);
+            tap += adv_t;
+            chunk += adv_c;
+            if (chunk >= nchunks) { chunk -= nchunks; ++tap; }
         }
     }
     __syncthreads();
