@@ -25,7 +25,7 @@
 // Rows of more than 256 weights first go through a search that needs no full sort (further down:
 // value buckets with exact sums, a bound on D inside every bucket, exact ranking of the few
 // elements that can hold the arg-max), and only rows it cannot finish are sorted: by the same
-// workgroup for rows below 4096 weights (one launch, the row in registers), and for longer rows by
+// workgroup for rows below 4096 weights (one launch), and for longer rows by
 // the sort kernel launched behind, which then only works on the rows handed over (and does every
 // row when the caller gives no workspace for the hand-over flags).
 #include "dab_internal.h"
@@ -346,13 +346,11 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
 constexpr int kFastBigBucket = 96;      // buckets above this size are candidates without a bound
 
 // THREADS threads with up to ITEMS elements each, NB value buckets, at most CAP candidate elements.
-// The row is read from global memory (L2) in each of its three passes, every load of a pass in
-// flight at once, so nothing of it stays in registers between the phases, little LDS is needed and
-// several workgroups share a compute unit: every phase is a short latency chain between barriers.
-//
-// Short rows (REG) are read once and stay in registers.  The result says whether the row is done
+// The row is read once, every load in flight at once, and stays in registers (element j of thread t
+// is row[t + j * THREADS]); little LDS is needed and several workgroups share a compute unit:
+// every phase is a short latency chain between barriers.  The result says whether the row is done
 // (the same for every thread of the workgroup); nothing has been written when it is not.
-template <int THREADS, int ITEMS, int NB, int CAP, bool REG>
+template <int THREADS, int ITEMS, int NB, int CAP>
 __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, int f, float* __restrict__ alpha,
                                            float* __restrict__ beta, int32_t* Kout, float* __restrict__ thr_val,
                                            int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper, const int32_t* K_prev,
@@ -371,25 +369,20 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
     __shared__ double w_d[NW];
     __shared__ Best wave_best[NW];
     __shared__ uint32_t nlist_s, r_s, wkey_s;
-    static_assert(CAP <= THREADS && THREADS * ITEMS <= 65536, "a candidate per thread, 16-bit indices");
+    static_assert(CAP <= THREADS && CAP < 1024 && THREADS * ITEMS <= 65536, "a candidate per thread, 10-bit counts, 16-bit indices");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* row = Wt + static_cast<size_t>(f) * n;
     float x[ITEMS];
-    auto read_row = [&]() {
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
-    };
+    for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
 
     // ---- range of the row
     float mn = INFINITY, mx = -INFINITY;
-    {
-        read_row();
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            mn = fminf(mn, x[j]);                                  // (the clamped repeats change nothing)
-            mx = fmaxf(mx, x[j]);
-        }
+    for (int j = 0; j < ITEMS; ++j) {
+        mn = fminf(mn, x[j]);                                      // (the clamped repeats change nothing)
+        mx = fmaxf(mx, x[j]);
     }
     wave_min_max_f32(mn, mx);
     if (lane == 63) { w_min[wave] = mn; w_max[wave] = mx; }
@@ -416,7 +409,6 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
 
     // ---- histogram: count and exact sum per bucket
     {
-        if (!REG) read_row();
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             if (tid + j * THREADS < n) {
@@ -563,7 +555,6 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
 
     // ---- the candidates' elements
     {
-        if (!REG) read_row();
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             if (tid + j * THREADS < n) {
@@ -581,42 +572,66 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
     __syncthreads();
 
     // ---- exact position and prefix sum of every candidate: elements of its bucket that precede it
-    // (thread e owns candidate e; among equal values it also counts those that come first in the row)
+    // (among equal values it also counts those that come first in the row).  P neighbouring threads
+    // share candidate e = tid / P: each scans every P-th entry of the list, and the partial counts
+    // (packed, 10 bits each) and sums are added across the P lanes by DPP moves.
+    int pshift = 0;
+    while (pshift < 4 && (2 << pshift) * static_cast<int>(nc) <= THREADS) ++pshift;
+    const int P = 1 << pshift;
+    const int e = tid >> pshift, part = tid & (P - 1);
+    const bool has = e < static_cast<int>(nc);
     Best best{-1.0, 1.0, 0.0, 0};
     uint32_t my_key = 0, my_less = 0, my_first = 0, my_idx = 0;
-    if (tid < static_cast<int>(nc)) {
-        const int e = tid;
-        const uint32_t key = lkey[e];
-        const int b = lb[e];
-        my_idx = lidx[e];
-        uint32_t within = 0, less = 0, first = 0;
+    {
+        uint32_t key = 0, counts = 0;
+        int b = 0;
         long long ps = 0;
+        if (has) {
+            key = lkey[e];
+            b = lb[e];
+            my_idx = lidx[e];
 #pragma unroll 4
-        for (int q = 0; q < static_cast<int>(nc); ++q) {          // branch-free: the LDS reads pipeline
-            const uint32_t kq = lkey[q];
-            const bool same = lb[q] == b;
-            const bool lt = same && kq < key;
-            const bool eq = same && kq == key;
-            const bool le = lt || (eq && q <= e);
-            within += le ? 1u : 0u;
-            less += lt ? 1u : 0u;
-            first += (eq && lidx[q] < my_idx) ? 1u : 0u;
-            ps += le ? lq[q] : 0ll;
+            for (int q = part; q < static_cast<int>(nc); q += P) {    // branch-free: the LDS reads pipeline
+                const uint32_t kq = lkey[q];
+                const bool same = lb[q] == b;
+                const bool lt = same && kq < key;
+                const bool eq = same && kq == key;
+                const bool le = lt || (eq && q <= e);
+                counts += (le ? 1u : 0u) + (lt ? 1u << 10 : 0u) + ((eq && lidx[q] < my_idx) ? 1u << 20 : 0u);
+                ps += le ? lq[q] : 0ll;
+            }
         }
-        my_key = key;
-        my_less = cnt[b] + less;
-        my_first = first;
-        const int i = static_cast<int>(cnt[b] + within);
-        if (i >= wlo && i <= whi) {
-            const double P = static_cast<double>(static_cast<long long>(sum[b]) + ps);
-            const double rest = T - P;
-            const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
-            best = Best{P * P * fr + rest * rest * fi, fi * fr, P, i};
+#define DAB_GROUP_ADD(CTRL) \
+        { \
+            counts += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(counts), CTRL, 0xf, 0xf, false)); \
+            const uint32_t lo = static_cast<uint32_t>( \
+                __builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(ps)), CTRL, 0xf, 0xf, false)); \
+            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_update_dpp( \
+                0, static_cast<int>(static_cast<unsigned long long>(ps) >> 32), CTRL, 0xf, 0xf, false)); \
+            ps += static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo); \
+        }
+        if (P >= 2) DAB_GROUP_ADD(0xB1)      // lanes 1 0 3 2 of every four
+        if (P >= 4) DAB_GROUP_ADD(0x4E)      // lanes 2 3 0 1
+        if (P >= 8) DAB_GROUP_ADD(0x141)     // the eight lanes of a half row mirrored
+        if (P >= 16) DAB_GROUP_ADD(0x140)    // the sixteen lanes of a row mirrored
+#undef DAB_GROUP_ADD
+        if (has && part == 0) {
+            const uint32_t within = counts & 1023u, less = (counts >> 10) & 1023u;
+            my_key = key;
+            my_less = cnt[b] + less;
+            my_first = counts >> 20;
+            const int i = static_cast<int>(cnt[b] + within);
+            if (i >= wlo && i <= whi) {
+                const double Pi = static_cast<double>(static_cast<long long>(sum[b]) + ps);
+                const double rest = T - Pi;
+                const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
+                best = Best{Pi * Pi * fr + rest * rest * fi, fi * fr, Pi, i};
+            }
         }
     }
     const int my_i = best.i;
     // only the wavefronts that hold candidates (the first one, as a rule) reduce
-    const int nwr = min(NW, static_cast<int>(nc + 63) >> 6);
+    const int nwr = min(NW, static_cast<int>((nc << pshift) + 63) >> 6);
     if (wave < nwr) {
         const Best wb = wave_best_of(best);
         if (lane == 63) wave_best[wave] = wb;
@@ -646,11 +661,11 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
 
     // ---- the split descriptor's index: the r-th copy of the split value in the order of the row.
     // Every copy is a candidate (equal values share a bucket) and knows how many copies precede it.
-    if (tid < static_cast<int>(nc) && my_key == wkey && my_first + 1 == r_s) thr_idx[f] = static_cast<int32_t>(my_idx);
+    if (has && part == 0 && my_key == wkey && my_first + 1 == r_s) thr_idx[f] = static_cast<int32_t>(my_idx);
     return true;
 }
 
-// Long rows: three passes over the row in L2, a flag per row for the sort kernel launched behind.
+// Long rows: a flag per row for the sort kernel launched behind.
 template <int THREADS, int ITEMS, int NB, int CAP>
 __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* __restrict__ Wt, int n,
                                                                   float* __restrict__ alpha, float* __restrict__ beta,
@@ -660,13 +675,13 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
                                                                   int max_change, uint8_t* __restrict__ fallback) {
     DAB_RESERVE_VGPRS();
     const int f = static_cast<int>(blockIdx.x);
-    const bool done = bucket_row<THREADS, ITEMS, NB, CAP, false>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper,
+    const bool done = bucket_row<THREADS, ITEMS, NB, CAP>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper,
                                                                  K_prev, upper_prev, max_change);
     if (threadIdx.x == 0) fallback[f] = done ? 0 : 1;
 }
 
-// Short rows: the row stays in registers, and a row the buckets cannot finish is sorted by the same
-// workgroup, so one launch does the layer.
+// Short rows: a row the buckets cannot finish is sorted by the same workgroup, so one launch does the
+// layer.
 template <int THREADS, int ITEMS, int NB, int CAP>
 __global__ __launch_bounds__(THREADS) void estimate_short_kernel(const float* __restrict__ Wt, int n,
                                                                  float* __restrict__ alpha, float* __restrict__ beta,
@@ -676,7 +691,7 @@ __global__ __launch_bounds__(THREADS) void estimate_short_kernel(const float* __
                                                                  int max_change) {
     DAB_RESERVE_VGPRS();
     const int f = static_cast<int>(blockIdx.x);
-    if (bucket_row<THREADS, ITEMS, NB, CAP, true>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev,
+    if (bucket_row<THREADS, ITEMS, NB, CAP>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev,
                                                   upper_prev, max_change))
         return;
     __syncthreads();
