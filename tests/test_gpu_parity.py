@@ -68,7 +68,8 @@ def weight_rows(rng, F, n, kind):
     raise ValueError(kind)
 
 
-@pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 576, 1024, 1025, 1600, 2304, 3072, 3073, 4608, 5120, 5121, 9216, 12544, 13312])
+@pytest.mark.parametrize("n", [2, 3, 63, 64, 65, 256, 257, 576, 768, 769, 1024, 1025, 1600, 2304, 2817, 3072, 3073, 3585, 4095, 4096,
+                               4608, 5120, 5121, 8192, 8193, 9216, 12544, 13312])
 def test_estimate_sizes(n):
     rng = np.random.default_rng(n)
     F = 6 if n > 3000 else 10
