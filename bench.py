@@ -46,8 +46,8 @@ CONV2_CALL_HBM_BYTES = 157136400
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
     ap.add_argument("--cpu-batch", type=int, default=256, help="images of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--product-streams", type=int, default=2,
