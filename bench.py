@@ -10,7 +10,8 @@ fp32 inputs of all layers and the fp32 weights are resident in HBM before the ti
 
 A step is launched as one captured HIP graph: the weight sides of all layers (they depend on
 no activation) run on side streams while the main stream packs the activations of all layers;
-the products follow, alternating over two streams.  The timed region is K graph launches.
+the products follow on two streams (each on the one with less product time so far).  The timed
+region is K graph launches.
 
 Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
 call (the binary product of the largest layer) from HIP-event timings of an eager pass over
@@ -128,8 +129,9 @@ class Schedule:
     The weight side of a layer (estimation, weight packing) depends on no activation, so the
     weight sides run on side streams (the heaviest layer alone, the others dealt out in layer order) while the current
     stream packs the activations of all layers (every input is resident when the step starts;
-    memory-bound work beside the LDS-bound estimation).  The binary products then alternate
-    between the current stream and one more: a product waits for its own layer's weights only
+    memory-bound work beside the LDS-bound estimation).  The binary products then go, in layer
+    order, to the current stream and one more (to the one with less product time so far, or
+    alternating when the durations are not given): a product waits for its own layer's weights only
     (an event per layer), so the weight sides of later layers run beside the products of earlier
     ones, and with two product streams the prepare kernel of the next layer runs beside the
     main kernel of this one, whose last workgroups hand their compute units straight to the next
@@ -137,7 +139,7 @@ class Schedule:
     overlap, and the whole step can be captured into one HIP graph.
     """
 
-    def __init__(self, states, n_side, torch, per_layer=True, n_product=2):
+    def __init__(self, states, n_side, torch, per_layer=True, n_product=2, product_ms=None):
         self.torch = torch
         self.states = states
         self.side = [torch.cuda.Stream() for _ in range(n_side)]
@@ -154,6 +156,17 @@ class Schedule:
                 self.assign[1 + k % (n_side - 1)].append(i)
         else:
             self.assign[0] = list(range(len(states)))
+        # products: in layer order, each on the product stream with the least work so far when the
+        # durations of the products are known (the small late layers then run beside a large one
+        # instead of alone at the end), else alternating
+        n_q = 1 + len(self.extra)
+        self.product_on = [i % n_q for i in range(len(states))]
+        if product_ms is not None and n_q > 1:
+            load = [0.0] * n_q
+            for i, ms in enumerate(product_ms):
+                q = min(range(n_q), key=lambda j: load[j])
+                self.product_on[i] = q
+                load[q] += ms
         self.fork = torch.cuda.Event()
         self.packed = torch.cuda.Event()
         self.ready = [torch.cuda.Event() for _ in self.side]
@@ -191,7 +204,7 @@ class Schedule:
                 for done in self.ready:
                     q.wait_event(done)
         for i, s in enumerate(states):
-            q = streams[i % len(streams)]
+            q = streams[self.product_on[i]]
             if self.per_layer:
                 q.wait_event(self.layer_ready[i])
             with torch.cuda.stream(q):
@@ -447,11 +460,6 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    sched = Schedule(states, args.side_streams, torch, per_layer=not args.wait_all, n_product=args.product_streams)
-    for _ in range(args.warmup):
-        sched.step(dab)
-    torch.cuda.synchronize()
-
     # Kernel timing pass: every layer launched eagerly on one stream with a HIP event pair around its
     # binary product (events cannot be recorded inside a captured graph on this platform, and with
     # several streams the eager launches are host-bound, which would put launch gaps between the
@@ -459,9 +467,20 @@ def main():
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in states]
           for _ in range(args.steps)]
     torch.cuda.synchronize()
+    for _ in range(min(args.warmup, 3)):
+        for s in states:
+            run_layer(s, dab)
     for k in range(args.steps):
         for s, e in zip(states, ev[k]):
             run_layer(s, dab, e)
+    torch.cuda.synchronize()
+    product_ms = [sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
+                  for i in range(len(states))]
+
+    sched = Schedule(states, args.side_streams, torch, per_layer=not args.wait_all, n_product=args.product_streams,
+                     product_ms=product_ms)
+    for _ in range(args.warmup):
+        sched.step(dab)
     torch.cuda.synchronize()
 
     # The schedule launched eagerly (host-bound with side streams; reported for comparison)
@@ -497,7 +516,7 @@ def main():
     conv_ms = 0.0
     algo_bytes = 0
     for i, s in enumerate(states):
-        ms = sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
+        ms = product_ms[i]
         conv_ms += ms
         nbytes = s.Y.numel() * 4 + s.A.numel() * 4 + s.EW[0].numel() * 4 + 8 * s.L.F
         algo_bytes += nbytes
@@ -570,6 +589,7 @@ def main():
                    "batch": args.batch, "binary_macs_per_step": total_macs,
                    "streams": 1 + args.side_streams + (max(args.product_streams, 1) - 1 if args.side_streams else 0),
                    "launch": "eager" if args.no_graph else "one captured HIP graph per step",
+                   "product_stream_of_layer": sched.product_on,
                    "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
                    "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "rebinarized_chain": fused,
