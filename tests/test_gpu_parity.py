@@ -192,7 +192,8 @@ def test_estimate_xnor_special_case():
 
 # ------------------------------------------------------------------ dab_pack_weights
 @pytest.mark.parametrize("F,C,kh,kw", [(5, 3, 1, 1), (64, 64, 3, 3), (70, 45, 2, 3), (130, 100, 5, 5),
-                                       (9, 256, 7, 7), (33, 9216, 1, 1), (3, 13000, 1, 1), (4, 330, 3, 3)])
+                                       (9, 256, 7, 7), (33, 9216, 1, 1), (3, 13000, 1, 1), (4, 330, 3, 3),
+                                       (2, 700, 7, 7), (3, 30000, 1, 1)])    # the last two: filters longer than one LDS slab
 def test_pack_weights_with_oracle_split(F, C, kh, kw):
     """The packer alone, fed the oracle's split descriptor: bits and counts exact."""
     rng = np.random.default_rng(F * C)
