@@ -229,7 +229,7 @@ class FusedChain:
     (3/2 max-pooling as an OR on the bits after conv2 and conv5), so between conv2 and fc7 no fp32
     activation is written or read.  conv2 packs its fp32 input as in the plain step and fc7 writes
     fp32.  Thresholds of the hand-over are the per-channel means the plain step uses.  The weight
-    sides run first on the schedule's side streams, as in the plain step."""
+    sides run on the side streams of the schedule it is given (bench.py: one, in layer order)."""
 
     def __init__(self, states, sched, dab, torch):
         self.states, self.sched, self.torch = states, sched, torch
@@ -575,7 +575,9 @@ def main():
     # The next row of the scope table, measured beside the headline: the fused chain
     fused = None
     if args.side_streams > 0 and not args.no_fused:
-        chain = FusedChain(states, sched, dab, torch)
+        # its products form one dependent chain, so one side stream (weight sides in layer order) delivers
+        # every layer's weights in time, and every further branch of the graph only costs launch overhead
+        chain = FusedChain(states, Schedule(states, 1, torch), dab, torch)
         for _ in range(args.warmup):
             chain.step(dab)
         torch.cuda.synchronize()
