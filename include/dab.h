@@ -17,15 +17,20 @@
  *
  * General rules
  *   - All data pointers are DEVICE pointers unless a comment says "host".
- *     The caller owns every buffer; the library allocates nothing, keeps no
- *     state between calls and never frees or retains a pointer.
+ *     The caller owns every buffer; the library allocates nothing and never
+ *     frees or retains a pointer.  Its only state is a one-time set-up per
+ *     device (dab_init), which every entry point that needs it performs on
+ *     its first call on that device.
  *   - "stream" is a hipStream_t passed as void* (NULL = the null stream).
  *     Work is enqueued on it and the call returns without synchronising.
  *   - Every call returns a dab_status.  Arguments are validated on the host
- *     before anything is enqueued; on any status other than DAB_OK nothing was
- *     launched.  Launch failures give DAB_ERR_HIP and the hipError_t is kept
- *     for dab_last_hip_error().  Faults inside a kernel surface at the
- *     caller's next synchronisation, as with any HIP work.
+ *     before anything is enqueued: on DAB_ERR_NULL, _SHAPE, _ALIGN, _WORKSPACE
+ *     and _UNSUPPORTED nothing was launched.  A failing launch gives
+ *     DAB_ERR_HIP (the status of that launch call, kept for
+ *     dab_last_hip_error()); kernels of the same call enqueued before it
+ *     stay enqueued and only write the call's own outputs and workspace.
+ *     Faults inside a kernel surface at the caller's next synchronisation,
+ *     as with any HIP work.
  *   - Float buffers are fp32, 4-byte aligned; packed buffers and Y are
  *     16-byte aligned (DAB_ERR_ALIGN otherwise).
  *   - Inputs must be finite.  A NaN activation binarizes to -1 (x >= tau is
@@ -83,6 +88,15 @@ const char* dab_strerror(int status);
 
 /* hipError_t of the last failed HIP call made by this thread (0 if none). */
 int dab_last_hip_error(void);
+
+/*
+ * dab_init - one-time set-up of the current device: raises the dynamic-LDS limit of the kernels
+ * that stage more than the default 48 KB and looks up the address of the library's own device
+ * memory.  Optional: entry points that depend on it do the same on their first call on a device.
+ * Callers that capture a stream into a graph call it before the capture begins, so that no
+ * attribute call falls inside it.  Thread-safe; later calls return at once.
+ */
+int dab_init(void);
 
 /*
  * dab_estimate_alpha_beta - optimal alpha, beta, K and split of every filter.

@@ -46,6 +46,7 @@ class dab_conv_desc(ctypes.Structure):
 _SIGNATURES = {
     "dab_strerror": (c_char_p, [c_int]),
     "dab_last_hip_error": (c_int, []),
+    "dab_init": (c_int, []),
     "dab_estimate_alpha_beta": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_estimate_alpha_beta_bounded": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, c_void_p,

@@ -45,8 +45,6 @@
 
 namespace dab {
 
-thread_local int g_last_hip_error = 0;
-
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -1045,16 +1043,28 @@ template <int WAVES, int MODE, int KIND = kFp4>
 static int launch_main(const MfmaPlan& pl, hipStream_t st, const char* a4, const uint4* e4, float* sa,
                        const float* alpha, const float* beta, float* Y, int32_t* dbg_s1, float* ws_s1,
                        const int32_t* pixsum, const int32_t* ktab, const float* tau_out, uint32_t* out_bits) {
-    static thread_local size_t granted = 0;
-    if (pl.lds_bytes > 48 * 1024 && pl.lds_bytes > granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE, KIND>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pl.lds_bytes));
-        if (e != hipSuccess) return hip_failed(e);
-        granted = pl.lds_bytes;
-    }
-    hipLaunchKernelGGL((binconv_mfma_kernel<WAVES, MODE, KIND>), dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4,
-                       e4, alpha, beta, Y, dbg_s1, ws_s1, sa, pixsum, ktab, tau_out, out_bits);
-    return launch_status();
+    return launch(binconv_mfma_kernel<WAVES, MODE, KIND>, dim3(pl.grid), dim3(64 * WAVES), pl.lds_bytes, st, pl.g, a4, e4,
+                  alpha, beta, Y, dbg_s1, ws_s1, sa, pixsum, ktab, tau_out, out_bits);
+}
+
+// One-time set-up on the current device: the panel of the main kernel takes up to kMaxChunk * 4 KB
+// of dynamic LDS, above the default limit of a launch.
+template <int WAVES, int MODE, int KIND>
+static int raise_lds_limit() {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&binconv_mfma_kernel<WAVES, MODE, KIND>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaxChunk * 4096);
+    return e == hipSuccess ? static_cast<int>(DAB_OK) : hip_failed(e);
+}
+int init_binconv() {
+    if (int rc = raise_lds_limit<8, kOutY, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<8, kOutYDebug, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<8, kOutBits, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<4, kOutY, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<4, kOutYDebug, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<4, kOutBits, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<4, kOutSplit, kFp4>()) return rc;
+    if (int rc = raise_lds_limit<8, kOutY, kBf16>()) return rc;
+    return raise_lds_limit<4, kOutY, kBf16>();
 }
 
 // Y != nullptr: fp32 output (and optional dbg_s1); Y == nullptr: re-binarized output into out_bits.
@@ -1064,6 +1074,7 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl)) return rc;
     if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
+    if (int rc = ensure_device_ready()) return rc;
     char* a4 = static_cast<char*>(ws);
     uint4* e4 = reinterpret_cast<uint4*>(a4 + pl.a4_bytes);
     float* sa = reinterpret_cast<float*>(a4 + pl.a4_bytes + pl.e4_bytes);
@@ -1072,40 +1083,36 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
 
     int32_t* pixsum = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(sa) + round256(static_cast<size_t>(g.M) * 4));
     int32_t* ktab = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pixsum) + round256(static_cast<size_t>(g.npix) * 4));
-    hipLaunchKernelGGL(binconv_prepare_kernel, dim3(g.blk_act + g.blk_wgt + g.blk_sum + g.blk_tab + g.blk_sa), dim3(256), 0,
-                       st, g, A, E, reinterpret_cast<uint4*>(a4), e4, pixsum, ktab, sa);
-    if (int rc = launch_status()) return rc;
+    if (int rc = launch(binconv_prepare_kernel, dim3(g.blk_act + g.blk_wgt + g.blk_sum + g.blk_tab + g.blk_sa), dim3(256), 0,
+                        st, g, A, E, reinterpret_cast<uint4*>(a4), e4, pixsum, ktab, sa))
+        return rc;
 
     if (pl.small) {
         const unsigned blocks = static_cast<unsigned>(ceil_div(g.M, 32) * g.n_fblocks);
-        auto launch = [&](auto kernel, int waves) {
-            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64 * waves), 0, st, g, a4, e4, alpha, beta, Y, dbg_s1, sa, ktab,
-                               tau_out, out_bits);
+        auto small = [&](auto kernel, int waves) {
+            return launch(kernel, dim3(blocks), dim3(64 * waves), 0, st, g, a4, e4, alpha, beta, Y, dbg_s1, sa, ktab, tau_out,
+                          out_bits);
         };
         // enough wavefronts per block that each keeps a few steps of the reduction
         if (g.nk >= 32) {
-            if (!Y) launch(binconv_small_kernel<kOutBits, 8>, 8);
-            else if (dbg_s1) launch(binconv_small_kernel<kOutYDebug, 8>, 8);
-            else launch(binconv_small_kernel<kOutY, 8>, 8);
-        } else {
-            if (!Y) launch(binconv_small_kernel<kOutBits, 2>, 2);
-            else if (dbg_s1) launch(binconv_small_kernel<kOutYDebug, 2>, 2);
-            else launch(binconv_small_kernel<kOutY, 2>, 2);
+            if (!Y) return small(binconv_small_kernel<kOutBits, 8>, 8);
+            if (dbg_s1) return small(binconv_small_kernel<kOutYDebug, 8>, 8);
+            return small(binconv_small_kernel<kOutY, 8>, 8);
         }
-        return launch_status();
+        if (!Y) return small(binconv_small_kernel<kOutBits, 2>, 2);
+        if (dbg_s1) return small(binconv_small_kernel<kOutYDebug, 2>, 2);
+        return small(binconv_small_kernel<kOutY, 2>, 2);
     }
     if (pl.split) {
         if (int rc = launch_main<4, kOutSplit>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)) return rc;
         const size_t total = static_cast<size_t>(g.M) * d.F;
         if (!Y) {
             const long long items = 1ll * g.M * ceil_div(d.F, 64);
-            hipLaunchKernelGGL(binconv_finish_bits_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st,
-                               s1, sa, alpha, beta, tau_out, out_bits, g.M, d.F, g.ksplit);
-            return launch_status();
+            return launch(binconv_finish_bits_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st, s1, sa,
+                          alpha, beta, tau_out, out_bits, g.M, d.F, g.ksplit);
         }
-        hipLaunchKernelGGL(binconv_finish_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, s1,
-                           sa, alpha, beta, Y, dbg_s1, g.M, d.F, g.ksplit);
-        return launch_status();
+        return launch(binconv_finish_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, s1, sa, alpha,
+                      beta, Y, dbg_s1, g.M, d.F, g.ksplit);
     }
     if (!Y)
         return pl.waves == 8 ? launch_main<8, kOutBits>(pl, st, a4, e4, sa, alpha, beta, Y, dbg_s1, s1, pixsum, ktab, tau_out, out_bits)
@@ -1123,24 +1130,23 @@ static int run_wbin(const dab_conv_desc& d, const float* X, const uint32_t* E, c
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl, true)) return rc;
     if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
+    if (int rc = ensure_device_ready()) return rc;
     char* a16 = static_cast<char*>(ws);
     uint4* e16 = reinterpret_cast<uint4*>(a16 + pl.a4_bytes);
     float* sa = reinterpret_cast<float*>(a16 + pl.a4_bytes + pl.e4_bytes);
     const MfmaGeom& g = pl.g;
     float* pixsum = reinterpret_cast<float*>(reinterpret_cast<char*>(sa) + round256(static_cast<size_t>(g.M) * 4));
     int32_t* ktab = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pixsum) + round256(static_cast<size_t>(g.npix) * 4));
-    hipLaunchKernelGGL(wbin_prepare_kernel, dim3(g.blk_act + g.blk_wgt + g.blk_sum + g.blk_tab + g.blk_sa), dim3(256), 0, st,
-                       g, X, E, reinterpret_cast<uint4*>(a16), e16, pixsum, ktab, sa);
-    if (int rc = launch_status()) return rc;
+    if (int rc = launch(wbin_prepare_kernel, dim3(g.blk_act + g.blk_wgt + g.blk_sum + g.blk_tab + g.blk_sa), dim3(256), 0, st,
+                        g, X, E, reinterpret_cast<uint4*>(a16), e16, pixsum, ktab, sa))
+        return rc;
     if (pl.small) {
         const unsigned blocks = static_cast<unsigned>(ceil_div(g.M, 32) * g.n_fblocks);
         if (g.nk >= 32)
-            hipLaunchKernelGGL((binconv_small_kernel<kOutY, 8, kBf16>), dim3(blocks), dim3(512), 0, st, g, a16, e16, alpha,
-                               beta, Y, nullptr, sa, ktab, nullptr, nullptr);
-        else
-            hipLaunchKernelGGL((binconv_small_kernel<kOutY, 2, kBf16>), dim3(blocks), dim3(128), 0, st, g, a16, e16, alpha,
-                               beta, Y, nullptr, sa, ktab, nullptr, nullptr);
-        return launch_status();
+            return launch(binconv_small_kernel<kOutY, 8, kBf16>, dim3(blocks), dim3(512), 0, st, g, a16, e16, alpha, beta, Y,
+                          nullptr, sa, ktab, nullptr, nullptr);
+        return launch(binconv_small_kernel<kOutY, 2, kBf16>, dim3(blocks), dim3(128), 0, st, g, a16, e16, alpha, beta, Y,
+                      nullptr, sa, ktab, nullptr, nullptr);
     }
     const int32_t* psum = reinterpret_cast<const int32_t*>(pixsum);
     return pl.waves == 8 ? launch_main<8, kOutY, kBf16>(pl, st, a16, e16, sa, alpha, beta, Y, nullptr, nullptr, psum, ktab,

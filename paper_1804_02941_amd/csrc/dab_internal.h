@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+
 #include "dab.h"
 
 namespace dab {
@@ -16,10 +18,19 @@ inline int hip_failed(hipError_t e) {
     return DAB_ERR_HIP;
 }
 
-// Status of the launch that was just enqueued.
-inline int launch_status() {
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? DAB_OK : hip_failed(e);
+// Enqueues one kernel and returns the status of that launch call itself (not the thread's last
+// error, which may stem from HIP work that is not this library's).
+template <typename... KArgs, typename... Args>
+inline int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, const Args&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<KArgs...> vals(static_cast<KArgs>(args)...);
+    return std::apply(
+        [&](auto&... v) {
+            void* ptrs[] = {static_cast<void*>(&v)...};
+            const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, st);
+            return e == hipSuccess ? static_cast<int>(DAB_OK) : hip_failed(e);
+        },
+        vals);
 }
 
 inline bool misaligned(const void* p, size_t a) {
@@ -47,6 +58,13 @@ __device__ __forceinline__ int fdiv(int n, FastDiv d) {
 // returned wrong results as soon as two of its workgroups shared a compute unit, the identical
 // instructions were right with a 72-register allocation; the build refuses 64-VGPR kernels.
 #define DAB_RESERVE_VGPRS() asm volatile("" ::: "v71")
+
+// One-time set-up of the current device (api.hip); the pieces live beside the kernels they prepare.
+constexpr int kMaxDevices = 64;
+int ensure_device_ready(int* dev_out = nullptr);
+int init_binconv();
+int init_pack();
+int init_estimate(int dev);
 
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kNumCU = 256;          // MI355X compute units

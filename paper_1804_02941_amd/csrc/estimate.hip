@@ -753,15 +753,6 @@ __global__ __launch_bounds__(256) void sign_split_kernel(const float* __restrict
 
 constexpr int kEstimateMaxN = 1024 * 13;
 
-template <int THREADS, int ITEMS>
-static int launch_estimate(const float* W, int F, int n, float* alpha, float* beta, int32_t* K, float* thr_val,
-                           int32_t* thr_idx, uint8_t* aiu, const int32_t* K_prev, const uint8_t* upper_prev,
-                           int max_change, const uint8_t* only, hipStream_t st) {
-    hipLaunchKernelGGL((estimate_kernel<THREADS, ITEMS>), dim3(F), dim3(THREADS), 0, st, W, n, alpha, beta, K,
-                       thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
-    return launch_status();
-}
-
 constexpr int kBucketMinN = 4096;        // rows from here on: bucket kernel, then the sort kernel for the rows it flags
 constexpr int kShortMinN = 256;          // rows above this and below kBucketMinN: the one-launch kernel for short rows
 
@@ -779,21 +770,17 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
     uint8_t* only = nullptr;
     if (n >= kBucketMinN && ws && ws_bytes >= estimate_ws_bytes(F, n)) {
         only = static_cast<uint8_t*>(ws);
-        if (n <= 512 * 16)
-            hipLaunchKernelGGL((estimate_bucket_kernel<512, 16, 2048, 512>), dim3(F), dim3(512), 0, st, W, n, alpha, beta,
-                               K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
-        else
-            hipLaunchKernelGGL((estimate_bucket_kernel<512, 26, 2048, 512>), dim3(F), dim3(512), 0, st, W, n, alpha, beta,
-                               K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only);
-        if (int rc = launch_status()) return rc;
+        const int rc = n <= 512 * 16
+            ? launch(estimate_bucket_kernel<512, 16, 2048, 512>, dim3(F), dim3(512), 0, st, W, n, alpha, beta, K, thr_val,
+                     thr_idx, aiu, K_prev, upper_prev, max_change, only)
+            : launch(estimate_bucket_kernel<512, 26, 2048, 512>, dim3(F), dim3(512), 0, st, W, n, alpha, beta, K, thr_val,
+                     thr_idx, aiu, K_prev, upper_prev, max_change, only);
+        if (rc) return rc;
     }
     // rows between the two: one launch, buckets first and the sort inside the kernel where needed
 #define DAB_SHORT(T, I, NB) \
-    do { \
-        hipLaunchKernelGGL((estimate_short_kernel<T, I, NB, 256>), dim3(F), dim3(T), 0, st, W, n, alpha, beta, K, thr_val, \
-                           thr_idx, aiu, K_prev, upper_prev, max_change); \
-        return launch_status(); \
-    } while (0)
+    return launch(estimate_short_kernel<T, I, NB, 256>, dim3(F), dim3(T), 0, st, W, n, alpha, beta, K, thr_val, thr_idx, \
+                  aiu, K_prev, upper_prev, max_change)
     if (n > kShortMinN && n < kBucketMinN) {
         if (n <= 256 * 3) DAB_SHORT(256, 3, 512);
         if (n <= 256 * 5) DAB_SHORT(256, 5, 1024);
@@ -805,7 +792,8 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
     }
 #undef DAB_SHORT
 #define DAB_EST(T, I) \
-    return launch_estimate<T, I>(W, F, n, alpha, beta, K, thr_val, thr_idx, aiu, K_prev, upper_prev, max_change, only, st)
+    return launch(estimate_kernel<T, I>, dim3(F), dim3(T), 0, st, W, n, alpha, beta, K, thr_val, thr_idx, aiu, K_prev, \
+                  upper_prev, max_change, only)
     if (n <= 64 * 3) DAB_EST(64, 3);
     if (n <= 256 * 3) DAB_EST(256, 3);
     if (n <= 256 * 5) DAB_EST(256, 5);
@@ -821,6 +809,8 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
     DAB_EST(1024, 13);
 #undef DAB_EST
 }
+
+int init_estimate(int) { return DAB_OK; }
 
 }  // namespace dab
 
@@ -867,9 +857,8 @@ int dab_estimate_sign_split(const float* W, int32_t F, int32_t n, float* alpha, 
     if (misaligned(W, 4) || misaligned(alpha, 4) || misaligned(beta, 4) || misaligned(K, 4) ||
         misaligned(thr_val, 4) || misaligned(thr_idx, 4))
         return DAB_ERR_ALIGN;
-    hipLaunchKernelGGL(sign_split_kernel, dim3(F), dim3(256), 0, static_cast<hipStream_t>(stream), W, n, alpha, beta, K,
-                       thr_val, thr_idx, alpha_is_upper);
-    return launch_status();
+    return launch(sign_split_kernel, dim3(F), dim3(256), 0, static_cast<hipStream_t>(stream), W, n, alpha, beta, K,
+                  thr_val, thr_idx, alpha_is_upper);
 }
 
 }  // extern "C"

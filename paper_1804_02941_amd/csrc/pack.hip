@@ -282,6 +282,15 @@ __global__ __launch_bounds__(256) void pool_bits_kernel(const uint32_t* __restri
     out[i] = v;
 }
 
+// One-time set-up of this file's kernels on the current device: the weight slab may take up to
+// 96 KB of dynamic LDS, above the default limit of a launch.
+int init_pack() {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_weights_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>((kWeightSlabFloats + 4) * sizeof(float)));
+    return e == hipSuccess ? static_cast<int>(DAB_OK) : hip_failed(e);
+}
+
 }  // namespace dab
 
 extern "C" {
@@ -297,10 +306,9 @@ int dab_pool_bits(const uint32_t* A_packed, int32_t B, int32_t C, int32_t H, int
     const int Ho = (H - kh) / stride_h + 1, Wo = (W - kw) / stride_w + 1;
     const long long n = 1ll * B * Ho * Wo * Cw;
     if (n >= (1ll << 31) || 1ll * B * H * W * Cw >= (1ll << 31)) return DAB_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(pool_bits_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), A_packed, A_pooled, B, H, W, Cw, Ho, Wo, kh, kw, stride_h,
-                       stride_w, make_fastdiv(Cw), make_fastdiv(Wo), make_fastdiv(Ho));
-    return launch_status();
+    return launch(pool_bits_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
+                  static_cast<hipStream_t>(stream), A_packed, A_pooled, B, H, W, Cw, Ho, Wo, kh, kw, stride_h, stride_w,
+                  make_fastdiv(Cw), make_fastdiv(Wo), make_fastdiv(Ho));
 }
 
 int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, int32_t H, int32_t W,
@@ -325,30 +333,28 @@ int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, i
         // of a batch is u mod Cw64 whenever Cw64 divides sixteen
         const bool periodic = Cw64 <= kItemsPerWave && (Cw64 & (Cw64 - 1)) == 0;
         if (periodic && C % 64 == 0) {
-#define DAB_PACK_ALIGNED(N)                                                                                       \
-    hipLaunchKernelGGL(pack_act_nhwc_aligned_kernel<N>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, X, tau, \
-                       A_packed, static_cast<int>(n_items))
+#define DAB_PACK_ALIGNED(N)                                                                                      \
+    return launch(pack_act_nhwc_aligned_kernel<N>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, X, tau, \
+                  A_packed, static_cast<int>(n_items))
             switch (Cw64) {
-                case 1: DAB_PACK_ALIGNED(1); break;
-                case 2: DAB_PACK_ALIGNED(2); break;
-                case 4: DAB_PACK_ALIGNED(4); break;
-                case 8: DAB_PACK_ALIGNED(8); break;
-                default: DAB_PACK_ALIGNED(16); break;
+                case 1: DAB_PACK_ALIGNED(1);
+                case 2: DAB_PACK_ALIGNED(2);
+                case 4: DAB_PACK_ALIGNED(4);
+                case 8: DAB_PACK_ALIGNED(8);
+                default: DAB_PACK_ALIGNED(16);
             }
 #undef DAB_PACK_ALIGNED
-        } else if (periodic)
-            hipLaunchKernelGGL(pack_act_nhwc_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
-                               X, tau, A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
-        else
-            hipLaunchKernelGGL(pack_act_nhwc_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
-                               X, tau, A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
-    } else {
-        const long long HW = 1ll * H * W;
-        if (HW >= (1ll << 31) || Cw > 65535 || B > 65535) return DAB_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(pack_act_nchw_kernel, dim3(ceil_div(static_cast<int>(HW), 256), Cw, B), dim3(256), 0, st,
-                           X, tau, A_packed, C, static_cast<int>(HW), Cw);
+        }
+        if (periodic)
+            return launch(pack_act_nhwc_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, X, tau,
+                          A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
+        return launch(pack_act_nhwc_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, X, tau,
+                      A_packed, static_cast<int>(n_items), C, Cw, Cw64, make_fastdiv(Cw64));
     }
-    return launch_status();
+    const long long HW = 1ll * H * W;
+    if (HW >= (1ll << 31) || Cw > 65535 || B > 65535) return DAB_ERR_UNSUPPORTED;
+    return launch(pack_act_nchw_kernel, dim3(ceil_div(static_cast<int>(HW), 256), Cw, B), dim3(256), 0, st, X, tau,
+                  A_packed, C, static_cast<int>(HW), Cw);
 }
 
 int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t kw,
@@ -368,19 +374,13 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
     if (slab_c < 64) return DAB_ERR_UNSUPPORTED;
     if (slab_c > C) slab_c = 64 * ceil_div(C, 64);
     const size_t lds = (static_cast<size_t>(slab_c) * T + 4) * sizeof(float);
-    static thread_local size_t granted = 0;
-    if (lds > 48 * 1024 && lds > granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pack_weights_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return hip_failed(e);
-        granted = lds;
-    }
+    if (lds > 48 * 1024)
+        if (int rc = ensure_device_ready()) return rc;      // (the slab needs the raised LDS limit)
     // the (tap, 64-channel group) items of a filter are spread over the wavefronts of its workgroup:
     // long filters get sixteen of them
     const int threads = 1ll * C * T >= 8192 ? 1024 : 256;
-    hipLaunchKernelGGL(pack_weights_kernel, dim3(kNumXCD * ceil_div(Fp, kNumXCD)), dim3(threads), lds, static_cast<hipStream_t>(stream),
-                       W, thr_val, thr_idx, alpha_is_upper, E_packed, ecnt, F, C, T, Cw, Fp, slab_c);
-    return launch_status();
+    return launch(pack_weights_kernel, dim3(kNumXCD * ceil_div(Fp, kNumXCD)), dim3(threads), lds,
+                  static_cast<hipStream_t>(stream), W, thr_val, thr_idx, alpha_is_upper, E_packed, ecnt, F, C, T, Cw, Fp, slab_c);
 }
 
 }  // extern "C"

@@ -276,14 +276,13 @@ int dab_mean_center_clamp(const float* W, int32_t F, int32_t C, int32_t T, int32
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int vt = vec_threads(W, W_out, nullptr, C * T);
     if (axis == DAB_CENTER_FILTER && vt == 256)
-        hipLaunchKernelGGL(center_filter_vec_kernel<256>, dim3(F), dim3(256), 0, st, W, C * T, lo, hi, W_out);
+        return launch(center_filter_vec_kernel<256>, dim3(F), dim3(256), 0, st, W, C * T, lo, hi, W_out);
     else if (axis == DAB_CENTER_FILTER && vt == 1024)
-        hipLaunchKernelGGL(center_filter_vec_kernel<1024>, dim3(F), dim3(1024), 0, st, W, C * T, lo, hi, W_out);
+        return launch(center_filter_vec_kernel<1024>, dim3(F), dim3(1024), 0, st, W, C * T, lo, hi, W_out);
     else if (axis == DAB_CENTER_FILTER)
-        hipLaunchKernelGGL(center_filter_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, C * T, lo, hi, W_out);
+        return launch(center_filter_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, C * T, lo, hi, W_out);
     else
-        hipLaunchKernelGGL(center_channel_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, C, T, lo, hi, W_out);
-    return launch_status();
+        return launch(center_channel_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, C, T, lo, hi, W_out);
 }
 
 int dab_binarized_weights(const float* W, int32_t F, int32_t n, const float* alpha, const float* beta, const float* thr_val,
@@ -297,15 +296,14 @@ int dab_binarized_weights(const float* W, int32_t F, int32_t n, const float* alp
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int vt = vec_threads(W, W_tilde, nullptr, n);
     if (vt == 256)
-        hipLaunchKernelGGL(binarized_weights_vec_kernel<256>, dim3(F), dim3(256), 0, st, W, n, alpha, beta, thr_val,
+        return launch(binarized_weights_vec_kernel<256>, dim3(F), dim3(256), 0, st, W, n, alpha, beta, thr_val,
                            thr_idx, alpha_is_upper, W_tilde);
     else if (vt == 1024)
-        hipLaunchKernelGGL(binarized_weights_vec_kernel<1024>, dim3(F), dim3(1024), 0, st, W, n, alpha, beta, thr_val,
+        return launch(binarized_weights_vec_kernel<1024>, dim3(F), dim3(1024), 0, st, W, n, alpha, beta, thr_val,
                            thr_idx, alpha_is_upper, W_tilde);
     else
-        hipLaunchKernelGGL(binarized_weights_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, n, alpha, beta, thr_val,
+        return launch(binarized_weights_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, n, alpha, beta, thr_val,
                            thr_idx, alpha_is_upper, W_tilde);
-    return launch_status();
 }
 
 int dab_weight_gradient(const float* W, int32_t F, int32_t n, const float* thr_val, const int32_t* thr_idx,
@@ -319,15 +317,14 @@ int dab_weight_gradient(const float* W, int32_t F, int32_t n, const float* thr_v
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int vt = vec_threads(W, G_out, upstream, n);
     if (vt == 256)
-        hipLaunchKernelGGL(weight_gradient_vec_kernel<256>, dim3(F), dim3(256), 0, st, W, n, thr_val, thr_idx,
+        return launch(weight_gradient_vec_kernel<256>, dim3(F), dim3(256), 0, st, W, n, thr_val, thr_idx,
                            alpha_is_upper, upstream, G_out);
     else if (vt == 1024)
-        hipLaunchKernelGGL(weight_gradient_vec_kernel<1024>, dim3(F), dim3(1024), 0, st, W, n, thr_val, thr_idx,
+        return launch(weight_gradient_vec_kernel<1024>, dim3(F), dim3(1024), 0, st, W, n, thr_val, thr_idx,
                            alpha_is_upper, upstream, G_out);
     else
-        hipLaunchKernelGGL(weight_gradient_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, n, thr_val, thr_idx,
+        return launch(weight_gradient_kernel, dim3(F), dim3(kTrainThreads), 0, st, W, n, thr_val, thr_idx,
                            alpha_is_upper, upstream, G_out);
-    return launch_status();
 }
 
 }  // extern "C"
