@@ -137,6 +137,26 @@ size_t dab_estimate_workspace_bytes(int32_t F, int32_t n);
 int32_t dab_estimate_max_n(void);
 
 /*
+ * dab_estimate_alpha_beta_noalloc - dab_estimate_alpha_beta for callers that cannot allocate
+ * device memory or bring a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The per-row hand-over flags live in a device array that is part of the
+ * library (dab_estimate_noalloc_max_filters() bytes, held by every GPU the library runs on until
+ * the process ends), so the call takes no workspace and makes no allocating call (its address is
+ * looked up once per device, by dab_init or by the first call).  Same kernels, same outputs, bit
+ * for bit, as dab_estimate_alpha_beta with a workspace.
+ *
+ *   arguments as for dab_estimate_alpha_beta, without ws / ws_bytes
+ * Errors: as dab_estimate_alpha_beta; F above dab_estimate_noalloc_max_filters()
+ * -> DAB_ERR_UNSUPPORTED.  All calls on one GPU share the one array (every flag a call reads it
+ * has written itself, so nothing needs clearing between calls): two such calls whose work may
+ * overlap on the same GPU (different streams) race; calls on one stream are safe.
+ */
+int dab_estimate_alpha_beta_noalloc(const float* W, int32_t F, int32_t n,
+                                    float* alpha, float* beta, int32_t* K,
+                                    float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* stream);
+int32_t dab_estimate_noalloc_max_filters(void);
+
+/*
  * dab_estimate_alpha_beta_bounded - the same estimate with the split kept near the previous
  * iteration's.  Section 5 remarks that on natural images the algorithm needs K restricted to
  * change by slight amounts only and gives no rule; here the partition may move by at most

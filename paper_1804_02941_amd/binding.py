@@ -54,6 +54,9 @@ _SIGNATURES = {
                                                 c_void_p]),
     "dab_estimate_sign_split": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p]),
+    "dab_estimate_alpha_beta_noalloc": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                c_void_p, c_void_p, c_void_p]),
+    "dab_estimate_noalloc_max_filters": (c_int32, []),
     "dab_estimate_workspace_bytes": (c_size_t, [c_int32, c_int32]),
     "dab_estimate_max_n": (c_int32, []),
     "dab_pack_weights": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
@@ -164,6 +167,16 @@ def dab_estimate_alpha_beta(W, out=None, ws=None):
         _ptr(W, torch.float32, "W"), F, n, out["alpha"].data_ptr(), out["beta"].data_ptr(), out["K"].data_ptr(),
         out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(), out["alpha_is_upper"].data_ptr(),
         ws.data_ptr() if ws is not None else None, nbytes, _stream()))
+    return out
+
+
+def dab_estimate_alpha_beta_noalloc(W, out):
+    """dab_estimate_alpha_beta into the tensors of `out` (from estimate_outputs()), with the hand-over flags in
+    the library's own device array: the call allocates nothing."""
+    F, n = W.shape
+    _check("dab_estimate_alpha_beta_noalloc", lib().dab_estimate_alpha_beta_noalloc(
+        _ptr(W, torch.float32, "W"), F, n, out["alpha"].data_ptr(), out["beta"].data_ptr(), out["K"].data_ptr(),
+        out["thr_val"].data_ptr(), out["thr_idx"].data_ptr(), out["alpha_is_upper"].data_ptr(), _stream()))
     return out
 
 

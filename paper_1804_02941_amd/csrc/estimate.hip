@@ -810,7 +810,22 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
 #undef DAB_EST
 }
 
-int init_estimate(int) { return DAB_OK; }
+// ---------------------------------------------------------------- hand-over flags owned by the library
+// dab_estimate_alpha_beta_noalloc keeps the per-row flags of the bucket kernel in this array instead
+// of a caller's workspace.  The name is a host-side stand-in for the symbol: the device address is
+// looked up once per device (every GPU holds its own copy) and only that address is passed on.
+constexpr int kNoAllocMaxFilters = 65536;
+static __device__ __align__(256) unsigned char scratch[kNoAllocMaxFilters];
+static unsigned char* g_scratch_ptr[kMaxDevices];              // written under the set-up lock of api.hip
+
+int init_estimate(int dev) {
+    unsigned char* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_failed(e);
+    if (!ptr) return hip_failed(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = ptr;
+    return DAB_OK;
+}
 
 }  // namespace dab
 
@@ -831,6 +846,25 @@ int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n, float* alpha, 
     if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
     return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, nullptr, nullptr, 0, ws, ws_bytes,
                              static_cast<hipStream_t>(stream));
+}
+
+int32_t dab_estimate_noalloc_max_filters(void) { return dab::kNoAllocMaxFilters; }
+
+int dab_estimate_alpha_beta_noalloc(const float* W, int32_t F, int32_t n, float* alpha, float* beta, int32_t* K,
+                                    float* thr_val, int32_t* thr_idx, uint8_t* alpha_is_upper, void* stream) {
+    using namespace dab;
+    if (!W || !alpha || !beta || !K || !thr_val || !thr_idx || !alpha_is_upper) return DAB_ERR_NULL;
+    if (F < 1 || n < 2) return DAB_ERR_SHAPE;
+    if (misaligned(W, 4) || misaligned(alpha, 4) || misaligned(beta, 4) || misaligned(K, 4) ||
+        misaligned(thr_val, 4) || misaligned(thr_idx, 4))
+        return DAB_ERR_ALIGN;
+    if (n > kEstimateMaxN || F > kNoAllocMaxFilters) return DAB_ERR_UNSUPPORTED;
+    int dev = 0;
+    if (int rc = ensure_device_ready(&dev)) return rc;
+    // every flag the sort kernel reads (rows 0 .. F-1) is written by the bucket kernel of this call,
+    // so the array needs no clearing between calls
+    return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, nullptr, nullptr, 0,
+                             g_scratch_ptr[dev], kNoAllocMaxFilters, static_cast<hipStream_t>(stream));
 }
 
 int dab_estimate_alpha_beta_bounded(const float* W, int32_t F, int32_t n, const int32_t* K_prev,
