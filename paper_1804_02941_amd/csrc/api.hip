@@ -25,6 +25,7 @@ int ensure_device_ready(int* dev_out) {
     std::lock_guard<std::mutex> guard(g_setup_lock);
     if (g_ready[dev].load(std::memory_order_relaxed)) return DAB_OK;
     if (int rc = init_binconv()) return rc;
+    if (int rc = init_direct()) return rc;
     if (int rc = init_pack()) return rc;
     if (int rc = init_estimate(dev)) return rc;
     g_ready[dev].store(1, std::memory_order_release);

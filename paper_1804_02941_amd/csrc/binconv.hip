@@ -42,12 +42,9 @@
 // exactly into three bf16 pieces laid out like the fp4 planes, the masks become bf16 0 / 1, and
 // v_mfma_f32_32x32x16_bf16 takes the place of the fp4 instruction (products exact, fp32 sums).
 #include "dab_internal.h"
+#include "mfma_tools.h"
 
 namespace dab {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kNTile = 128;          // filters per workgroup
 constexpr int kMaxChunk = 36;        // k-steps of B fragments held in LDS at a time (36 x 4 KB)
@@ -395,14 +392,6 @@ __global__ __launch_bounds__(256) void wbin_prepare_kernel(const MfmaGeom g, con
 }
 
 // ---------------------------------------------------------------- main
-__device__ __forceinline__ v16f mfma_fp4(v4i a, v4i b, v16f c) {
-    const v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0};
-    const v8i b8 = {b.x, b.y, b.z, b.w, 0, 0, 0, 0};
-    // cbsz = blgp = 4 selects fp4 for both operands; scale bytes 0x7f = 2^0
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-}
-
-enum { kOutY = 0, kOutYDebug = 1, kOutSplit = 2, kOutBits = 3 };
 // Operand kinds of the main kernel: bits expanded to fp4 (the binarized layer), or bf16 (the
 // weights-only layer: fp32 inputs split into three bf16 pieces, masks as 0 / 1).
 enum { kFp4 = 0, kBf16 = 1 };
@@ -1071,6 +1060,12 @@ int init_binconv() {
 static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t* E, const float* alpha,
                        const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits,
                        void* ws, size_t ws_bytes, hipStream_t st) {
+    // layers with enough tiles and a reduction whose B fragments fit in LDS: one launch, no workspace
+    DirectPlan dp;
+    if (plan_direct(d, &dp)) {
+        if (int rc = ensure_device_ready()) return rc;
+        return launch_direct(dp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
+    }
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl)) return rc;
     if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
@@ -1180,7 +1175,10 @@ extern "C" {
 
 size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d) {
     dab::MfmaPlan pl;
-    if (!d || dab::check_desc(d) != DAB_OK || dab::plan_binconv(*d, &pl) != DAB_OK) return 0;
+    dab::DirectPlan dp;
+    if (!d || dab::check_desc(d) != DAB_OK) return 0;
+    if (dab::plan_direct(*d, &dp)) return 0;
+    if (dab::plan_binconv(*d, &pl) != DAB_OK) return 0;
     return pl.ws_bytes;
 }
 

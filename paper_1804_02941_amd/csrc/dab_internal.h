@@ -66,6 +66,33 @@ int init_binconv();
 int init_pack();
 int init_estimate(int dev);
 
+// The product kernel that reads both operands as packed bits (direct.hip).
+struct DirectGeom {
+    int H, W, C, Cw, WH, F, Fp, kh, kw, ph, pw, sh, sw;   // WH: words per half of a pixel = ceil(Cw / 2)
+    int HoWo, Wo, M, T;
+    int nk;                        // k-steps of the reduction: T * WH
+    int G, NG;                     // activation load groups per tap and in all
+    int odd;                       // odd number of words per pixel
+    int n_ent;                     // entries of the LDS panel (k-steps of whole rounds, plus one)
+    uint32_t step_kx, step_ky;     // byte steps of the load cursor across the window
+    int n_mtiles, wg_per_ntile;    // pixel tiles, persistent workgroups per 128-filter tile
+    int pix_bytes;                 // bytes of a pixel's packed words
+    uint32_t a_bytes;              // bytes of the packed activation tensor
+    uint32_t y_bytes;              // bytes of the fp32 output (below 2^31)
+    FastDiv d_HoWo, d_Wo, d_WH;
+};
+struct DirectPlan {
+    DirectGeom g;
+    int lw, pf, waves;             // words per load, load groups per round, wavefronts per workgroup
+    bool pad;
+    unsigned grid;
+    size_t lds_bytes;
+};
+bool plan_direct(const dab_conv_desc& d, DirectPlan* pl);
+int launch_direct(const DirectPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
+                  const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits);
+int init_direct();
+
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kNumCU = 256;          // MI355X compute units
 constexpr int kNumXCD = 8;           // accelerator complex dies, each with its own L2

@@ -225,11 +225,58 @@ SMALL_LAYERS = [
 @pytest.mark.parametrize("L", SMALL_LAYERS, ids=lambda L: L.name)
 @pytest.mark.parametrize("B", [1, 3])
 def test_small_conv_layers(L, B):
-    rng = np.random.default_rng(abs(hash(L.name)) % 1000 + B)
+    import zlib
+    rng = np.random.default_rng(zlib.crc32(L.name.encode()) % 1000 + B)    # (hash() of a string is salted per process)
     x = rng.standard_normal((B, L.C, L.H, L.W)).astype(np.float32)
     W = weight_rows(rng, L.F, L.n, "mixture")
     gu.check_layer(L, x, W, tau=None, layout="nhwc")
     gu.check_layer(L, x, W, tau=(rng.standard_normal(L.C) * 0.3).astype(np.float32), layout="nchw")
+
+
+# Layers with enough output pixels for the one-launch kernel that reads both operands as bits
+# (at least 129 tiles of 256 pixels), one per load width / padding / odd-word-count variant, with
+# ragged pixel and filter tails; the filter counts stay small so that the oracle finishes in seconds.
+MANY_PIXEL_LAYERS = [
+    (90, Layer("m_c37_pad", C=37, H=20, W=21, F=7, kh=3, kw=3, pad=1)),            # one word per load
+    (340, Layer("m_c70_odd", C=70, H=12, W=12, F=130, kh=3, kw=3)),                 # three words per pixel, F % 4 != 0
+    (345, Layer("m_c128", C=128, H=10, W=10, F=36, kh=3, kw=3, pad=1)),             # two words per load
+    (421, Layer("m_c256", C=256, H=9, W=9, F=20, kh=3, kw=3, pad=1)),               # four words per load
+    (341, Layer("m_c33_5x5_s2", C=33, H=19, W=19, F=5, kh=5, kw=5, pad=2, stride=2)),
+    (350, Layer("m_c64_5x5", C=64, H=14, W=14, F=12, kh=5, kw=5)),                  # 25 groups: queue depth five
+    (1100, Layer("m_pointwise", C=3, H=6, W=6, F=3, kh=1, kw=1)),
+    (140, Layer("m_c96_rect", C=96, H=18, W=17, F=64, kh=2, kw=3, pad=1)),
+]
+
+
+@pytest.mark.parametrize("B,L", MANY_PIXEL_LAYERS, ids=lambda v: v.name if isinstance(v, Layer) else str(v))
+def test_layers_with_many_pixels(B, L):
+    import zlib
+    rng = np.random.default_rng(zlib.crc32(L.name.encode()))
+    assert dab.lib().dab_binconv2d_workspace_bytes(
+        dab.dab_conv_desc(B, L.C, L.H, L.W, L.F, L.kh, L.kw, L.pad, L.pad, L.stride, L.stride)) == 0   # the one-launch kernel
+    x = rng.standard_normal((B, L.C, L.H, L.W)).astype(np.float32)
+    W = weight_rows(rng, L.F, L.n, "mixture")
+    tau = (rng.standard_normal(L.C) * 0.3).astype(np.float32)
+    gu.check_layer(L, x, W, tau=tau)
+    # the re-binarizing epilogue of the same kernel: identical to packing its fp32 output
+    g = gu.gpu_layer(L, x, W, tau, want_s1=False)
+    est = {k: gu.to_gpu(v) for k, v in g["est"].items()}
+    d = dab.dab_conv_desc(B, L.C, L.H, L.W, L.F, L.kh, L.kw, L.pad, L.pad, L.stride, L.stride)
+    tau_out = gu.to_gpu((rng.standard_normal(L.F) * np.abs(g["Y"]).mean()).astype(np.float32))
+    bits = dab.dab_binconv2d_bits(d, gu.to_gpu(g["A"].view(np.int32)), gu.to_gpu(g["E"].view(np.int32)), est["alpha"],
+                                  est["beta"], tau_out)
+    ref = dab.dab_pack_activations(g["Y_gpu"], dab.DAB_LAYOUT_NHWC, tau_out)
+    torch.cuda.synchronize()
+    assert torch.equal(bits, ref)
+
+
+def test_fc_with_many_rows():
+    rng = np.random.default_rng(4242)
+    B, K, F = 40000, 200, 9                                    # seven words per row (odd), 157 tiles
+    L = Layer("fc_rows", C=K, H=1, W=1, F=F, kh=1, kw=1)
+    assert dab.lib().dab_binfc_workspace_bytes(B, K, F) == 0
+    x = rng.standard_normal((B, K)).astype(np.float32)
+    gu.check_layer(L, x, weight_rows(rng, F, K, "gauss"))
 
 
 @pytest.mark.parametrize("B,K,F", [(1, 2, 1), (5, 70, 9), (64, 512, 512), (65, 1000, 130), (300, 4096, 48), (130, 9216, 40)])
