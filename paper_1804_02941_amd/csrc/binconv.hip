@@ -1066,6 +1066,9 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
         if (int rc = ensure_device_ready()) return rc;
         return launch_direct(dp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
     }
+    // layers of a few hundred output blocks: one workgroup per block, also from the bits, no workspace
+    BlockPlan bp;
+    if (plan_block(d, &bp)) return launch_block(bp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl)) return rc;
     if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
@@ -1177,7 +1180,8 @@ size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d) {
     dab::MfmaPlan pl;
     dab::DirectPlan dp;
     if (!d || dab::check_desc(d) != DAB_OK) return 0;
-    if (dab::plan_direct(*d, &dp)) return 0;
+    dab::BlockPlan bp;
+    if (dab::plan_direct(*d, &dp) || dab::plan_block(*d, &bp)) return 0;
     if (dab::plan_binconv(*d, &pl) != DAB_OK) return 0;
     return pl.ws_bytes;
 }

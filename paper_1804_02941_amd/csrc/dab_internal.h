@@ -88,6 +88,23 @@ struct DirectPlan {
     unsigned grid;
     size_t lds_bytes;
 };
+// The kernel for layers of few output blocks (one workgroup per 32 x 32 block, the reduction split
+// over its wavefronts); it shares DirectGeom's description of the layer.
+struct BlockGeom {
+    int n_fblocks, fb_per_xcd;     // 32-filter blocks in all and per XCD
+    uint32_t e_bytes;              // bytes of the packed weight tensor
+    FastDiv d_kw;
+};
+struct BlockPlan {
+    DirectGeom g;
+    BlockGeom bg;
+    int waves;
+    bool pad;
+    unsigned grid;
+};
+bool plan_block(const dab_conv_desc& d, BlockPlan* pl);
+int launch_block(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
+                 const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits);
 bool plan_direct(const dab_conv_desc& d, DirectPlan* pl);
 int launch_direct(const DirectPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
                   const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits);

@@ -473,6 +473,156 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
     }
 }
 
+// ---------------------------------------------------------------- small products
+// Layers with a few hundred 32 x 32 output blocks at most (the last layers of the Sketch-A-Net
+// trunk, a late ResNet stage at small batch) are latency problems: too few tiles for the
+// persistent kernel above.  Here one workgroup owns one 32-pixel x 32-filter block and its
+// wavefronts take consecutive shares of the reduction.  Both operands are read as packed bits
+// straight from memory (L2), eight k-steps per burst into two register sets, expanded in
+// registers and multiplied; the wavefronts' exact partial sums (and their counts of ones for
+// sA) are added through LDS.  Workgroups that share a block of filters run on the same XCD, so
+// the filter words are fetched into one L2 only.
+constexpr int kBlkDepth = 8;
+
+template <bool PAD, bool BITS, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectGeom g, const BlockGeom bg,
+                                                                   const uint32_t* __restrict__ A,
+                                                                   const uint32_t* __restrict__ E,
+                                                                   const float* __restrict__ alpha,
+                                                                   const float* __restrict__ beta, float* __restrict__ Y,
+                                                                   int32_t* __restrict__ dbg_s1,
+                                                                   const float* __restrict__ tau_out,
+                                                                   uint32_t* __restrict__ out_bits) {
+    __shared__ float red[WAVES][16][64];
+    __shared__ int ones_lds[WAVES][64];
+    __shared__ float sA_blk[32];
+    const int lane = threadIdx.x & 63, p = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // block of this workgroup: consecutive workgroups go to consecutive XCDs, and an XCD keeps its filter blocks
+    const int xcd = blockIdx.x % kNumXCD, r = blockIdx.x / kNumXCD;
+    const int mb = r / bg.fb_per_xcd;
+    const int fb = xcd + kNumXCD * (r - mb * bg.fb_per_xcd);
+    if (fb >= bg.n_fblocks) return;                                // (the whole workgroup)
+
+    // this lane's pixel: byte offset of word h*WH of the window's first tap, taps inside the image
+    uint32_t base, tbits = 0xFFFFFFFFu;
+    {
+        const int m = min(mb * 32 + p, g.M - 1);
+        const int b = fdiv(m, g.d_HoWo);
+        const int rr = m - b * g.HoWo;
+        const int oy = fdiv(rr, g.d_Wo);
+        const int ox = rr - oy * g.Wo;
+        const int iy0 = oy * g.sh - g.ph, ix0 = ox * g.sw - g.pw;
+        base = static_cast<uint32_t>(((b * g.H + iy0) * g.W + ix0) * g.pix_bytes + h * g.WH * 4);
+        if (PAD) {
+            uint32_t bitsv = 0;
+            int t = 0;
+            for (int ky = 0; ky < g.kh; ++ky)
+                for (int kx = 0; kx < g.kw; ++kx, ++t) {
+                    const bool in = static_cast<unsigned>(iy0 + ky) < static_cast<unsigned>(g.H) &&
+                                    static_cast<unsigned>(ix0 + kx) < static_cast<unsigned>(g.W);
+                    bitsv |= (in ? 1u : 0u) << t;
+                }
+            tbits = bitsv;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t arsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(A), 0, static_cast<int>(g.a_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t ersrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(E), 0, static_cast<int>(bg.e_bytes), 0x00020000);
+    const int fcol = fb * 32 + p;                                  // this lane's filter (as the B operand's column)
+    const uint32_t ecol = fcol < g.Fp ? static_cast<uint32_t>(fcol * 4) : kOob;
+
+    // this wavefront's k-steps [k0, k1): k-step ks = tap * WH + j multiplies word h*WH + j of the tap
+    const int per = (g.nk + WAVES - 1) / WAVES;
+    const int k0 = min(wave * per, g.nk), k1 = min(k0 + per, g.nk);
+    uint32_t xa[2][kBlkDepth], xe[2][kBlkDepth];
+    bool va[2][kBlkDepth];
+    auto fetch = [&](int set, int first) {
+#pragma unroll
+        for (int d = 0; d < kBlkDepth; ++d) {
+            const int ks = first + d;                              // (wavefront-uniform)
+            const int tap = fdiv(min(ks, g.nk - 1), g.d_WH);
+            const int j = min(ks, g.nk - 1) - tap * g.WH;
+            const int ky = fdiv(tap, bg.d_kw);
+            const int kx = tap - ky * g.kw;
+            const int wd = h * g.WH + j;
+            const bool live = ks < k1 && wd < g.Cw;
+            const bool in = live && (!PAD || ((tbits >> (tap & 31)) & 1u));
+            const uint32_t aoff = base + static_cast<uint32_t>(((ky * g.W + kx) * g.Cw + j) * 4);
+            const uint32_t eoff = ecol + static_cast<uint32_t>((tap * g.Cw + wd) * g.Fp * 4);
+            xa[set][d] = __builtin_amdgcn_raw_buffer_load_b32(arsrc, static_cast<int>(in ? aoff : kOob), 0, 0);
+            xe[set][d] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, static_cast<int>(live ? eoff : kOob), 0, 0);
+            va[set][d] = in;
+        }
+    };
+    uint32_t k8, k2;
+    asm volatile("s_mov_b32 %0, 0x88888888" : "=s"(k8));
+    asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(k2));
+    v16f acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    int ones = 0;
+    auto multiply = [&](int set) {
+#pragma unroll
+        for (int d = 0; d < kBlkDepth; ++d) {
+            const uint32_t x = xa[set][d];
+            ones += __builtin_popcount(x);                         // (words that were not loaded are zero)
+            const v4i a = expand_a(x, va[set][d] ? k8 : 0u, va[set][d] ? k2 : 0u);
+            const uint4 e = expand_e(xe[set][d]);
+            const v4i bv = {static_cast<int>(e.x), static_cast<int>(e.y), static_cast<int>(e.z), static_cast<int>(e.w)};
+            acc = mfma_fp4(a, bv, acc);                            // (a k-step past k1 multiplies zeros)
+        }
+    };
+    fetch(0, k0);
+    for (int st = k0; st < k1; st += 2 * kBlkDepth) {
+        fetch(1, st + kBlkDepth);
+        multiply(0);
+        fetch(0, st + 2 * kBlkDepth);
+        multiply(1);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
+    ones_lds[wave][lane] = ones;
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        // sA of the block's pixels: ones of both halves and all wavefronts, taps inside the image
+        int both = 0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) both += ones_lds[w][p] + ones_lds[w][p + 32];
+        const int taps = PAD ? __builtin_popcount(tbits) : g.T;
+        sA_blk[p] = static_cast<float>(2 * both - taps * g.C);
+    }
+    __syncthreads();
+
+    // register v of lane l is row (v/4)*8 + (l/32)*4 + v%4 of the block, column l%32; wavefront w
+    // finishes registers w, w + WAVES, ...  The accumulators hold -s1.
+    const int f = min(fcol, g.F - 1);
+    const float al = alpha[f], be = beta[f];
+    const float tcol = (BITS && tau_out) ? tau_out[f] : 0.0f;
+    const bool fvalid = fcol < g.F;
+    const float dcol = be - al;
+    const int Fw = (g.F + 31) >> 5;
+#pragma unroll
+    for (int v = wave; v < 16; v += WAVES) {
+        const int rl = (v >> 2) * 8 + h * 4 + (v & 3);
+        const int row = mb * 32 + rl;
+        float ns1 = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) ns1 += red[w][v][lane];
+        const float y = fmaf(dcol, ns1, be * sA_blk[rl]);
+        if (BITS) {
+            const unsigned long long mask = __ballot(fvalid && y >= tcol);
+            const uint32_t word = static_cast<uint32_t>(lane < 32 ? mask : mask >> 32);
+            if (p == 0 && row < g.M) out_bits[static_cast<size_t>(row) * Fw + fb] = word;
+        } else if (row < g.M && fvalid) {
+            const size_t o = static_cast<size_t>(row) * g.F + fcol;
+            Y[o] = y;
+            if (dbg_s1) dbg_s1[o] = -static_cast<int>(ns1);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ host side
 
 // Whether the direct kernel covers the layer, and its geometry.  It needs the B fragments of the
@@ -530,6 +680,65 @@ bool plan_direct(const dab_conv_desc& d, DirectPlan* pl) {
     pl->grid = static_cast<unsigned>(g.wg_per_ntile * n_ntiles);
     pl->lds_bytes = static_cast<size_t>(g.n_ent) * 4096;
     return true;
+}
+
+// Layers for the block kernel: too few tiles for the persistent kernel, at most 512 blocks of 32 x 32.
+bool plan_block(const dab_conv_desc& d, BlockPlan* pl) {
+    DirectGeom& g = pl->g;
+    g = DirectGeom{};
+    g.H = d.H; g.W = d.W; g.C = d.C; g.F = d.F; g.kh = d.kh; g.kw = d.kw;
+    g.ph = d.pad_h; g.pw = d.pad_w; g.sh = d.stride_h; g.sw = d.stride_w;
+    g.Cw = ceil_div(d.C, 32);
+    g.WH = (g.Cw + 1) / 2;
+    g.Fp = 64 * ceil_div(d.F, 64);
+    const int Ho = (d.H + 2 * d.pad_h - d.kh) / d.stride_h + 1;
+    g.Wo = (d.W + 2 * d.pad_w - d.kw) / d.stride_w + 1;
+    g.HoWo = Ho * g.Wo;
+    g.T = d.kh * d.kw;
+    const long long M = 1ll * d.B * g.HoWo;
+    const long long a_bytes = 1ll * d.B * d.H * d.W * g.Cw * 4;
+    const long long e_bytes = 1ll * g.T * g.Cw * g.Fp * 4;
+    const long long nk = 1ll * g.T * g.WH;
+    if (M >= (1ll << 30) || a_bytes >= (1ll << 30) || e_bytes >= (1ll << 30) || nk >= (1 << 20)) return false;
+    if (1ll * d.C * g.T >= (1ll << 24)) return false;             // |s1| must stay exact in fp32
+    pl->pad = d.pad_h > 0 || d.pad_w > 0;
+    if (pl->pad && g.T > 32) return false;
+    g.M = static_cast<int>(M);
+    g.a_bytes = static_cast<uint32_t>(a_bytes);
+    g.pix_bytes = g.Cw * 4;
+    g.nk = static_cast<int>(nk);
+    g.d_HoWo = make_fastdiv(g.HoWo); g.d_Wo = make_fastdiv(g.Wo); g.d_WH = make_fastdiv(g.WH);
+    BlockGeom& bg = pl->bg;
+    bg.n_fblocks = ceil_div(d.F, 32);
+    bg.fb_per_xcd = ceil_div(bg.n_fblocks, kNumXCD);
+    bg.e_bytes = static_cast<uint32_t>(e_bytes);
+    bg.d_kw = make_fastdiv(d.kw);
+    const long long blocks = 1ll * ceil_div(g.M, 32) * bg.n_fblocks;
+    const int tiles256 = ceil_div(g.M, 256) * ceil_div(d.F, kDirNTile);
+    if (tiles256 * 2 > kNumCU || blocks > 512) return false;
+    pl->grid = static_cast<unsigned>(ceil_div(g.M, 32) * bg.fb_per_xcd * kNumXCD);
+    // enough wavefronts per block that each keeps a few k-steps of the reduction
+    pl->waves = g.nk >= 32 ? 8 : 2;
+    return true;
+}
+
+template <bool PAD, bool BITS, int WAVES>
+static int launch_block_as(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
+                           const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits) {
+    return launch(binconv_block_kernel<PAD, BITS, WAVES>, dim3(pl.grid), dim3(64 * WAVES), 0, st, pl.g, pl.bg, A, E, alpha,
+                  beta, Y, dbg_s1, tau_out, out_bits);
+}
+
+int launch_block(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
+                 const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits) {
+    const bool bits = Y == nullptr;
+#define DAB_X(PAD, BITS, WAVES) \
+    if (pl.pad == PAD && bits == BITS && pl.waves == WAVES) \
+        return launch_block_as<PAD, BITS, WAVES>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
+    DAB_X(false, false, 8) DAB_X(false, true, 8) DAB_X(true, false, 8) DAB_X(true, true, 8)
+    DAB_X(false, false, 2) DAB_X(false, true, 2) DAB_X(true, false, 2) DAB_X(true, true, 2)
+#undef DAB_X
+    return DAB_ERR_UNSUPPORTED;
 }
 
 template <int LW, int PF, bool PAD, bool BITS>

@@ -135,12 +135,12 @@ def test_config3_fused_chain_matches_fp32_chain():
 
 
 def test_error_codes_of_the_new_entry_points():
-    d = dab.dab_conv_desc(1, 64, 8, 8, 64, 3, 3, 1, 1, 1, 1)
-    A = torch.zeros((1, 8, 8, 2), dtype=torch.int32, device="cuda:0")
-    E = torch.zeros((18, 64), dtype=torch.int32, device="cuda:0")
-    ab = torch.ones(64, dtype=torch.float32, device="cuda:0")
+    d = dab.dab_conv_desc(2048, 64, 1, 1, 512, 1, 1, 0, 0, 1, 1)     # a mid-sized layer: its operands are expanded into a workspace
+    A = torch.zeros((2048, 1, 1, 2), dtype=torch.int32, device="cuda:0")
+    E = torch.zeros((2, 512), dtype=torch.int32, device="cuda:0")
+    ab = torch.ones(512, dtype=torch.float32, device="cuda:0")
     import ctypes
-    out = torch.zeros((1, 8, 8, 2), dtype=torch.int32, device="cuda:0")
+    out = torch.zeros((2048, 1, 1, 16), dtype=torch.int32, device="cuda:0")
     small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
     rc = dab.lib().dab_binconv2d_bits(ctypes.byref(d), A.data_ptr(), E.data_ptr(), ab.data_ptr(), ab.data_ptr(), None,
                                       out.data_ptr(), small.data_ptr(), 256, None)
@@ -148,5 +148,6 @@ def test_error_codes_of_the_new_entry_points():
     rc = dab.lib().dab_binconv2d_bits(ctypes.byref(d), A.data_ptr(), E.data_ptr(), ab.data_ptr(), ab.data_ptr(), None,
                                       None, small.data_ptr(), 256, None)
     assert rc == 1                                                   # no output buffer
+    A = torch.zeros((1, 8, 8, 2), dtype=torch.int32, device="cuda:0")
     rc = dab.lib().dab_pool_bits(A.data_ptr(), 1, 64, 8, 8, 9, 3, 1, 1, out.data_ptr(), None)
     assert rc == 2                                                   # window larger than the image
