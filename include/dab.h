@@ -208,6 +208,35 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
                      uint32_t* E_packed, uint32_t* ecnt, void* stream);
 
 /*
+ * dab_binarize_weights_multi - the whole weight side of several layers in two or three launches:
+ * for every job, dab_estimate_alpha_beta (or, with K_prev, dab_estimate_alpha_beta_bounded) of its
+ * filters followed by dab_pack_weights of the resulting masks.  Section 4.3.1 handles all filters of
+ * a layer together; filters of different layers are just as independent, so they share the
+ * launches (a workgroup looks up its job), and a filter's mask (Corollary 1) is packed by the
+ * workgroup that has just found its split, while the row is still in cache.  Results are, bit
+ * for bit, those of the separate calls.
+ *
+ *   jobs      host array of n_jobs descriptors (read during the call only); every pointer inside is a
+ *             device pointer with the meaning it has in dab_estimate_alpha_beta / dab_pack_weights.
+ *             E_packed and ecnt may both be NULL (estimation only); K_prev and alpha_is_upper_prev
+ *             may both be NULL (unrestricted search), else max_change >= 0 bounds the split's move.
+ *   ws        scratch of dab_binarize_weights_multi_workspace_bytes(jobs, n_jobs) bytes (one flag per
+ *             filter of the jobs with long rows; 0 when every row has at most 4608 weights)
+ * Errors: per job as in the separate calls (rows above dab_estimate_max_n(), more than 128 taps with
+ * packing -> DAB_ERR_UNSUPPORTED); more than 16 jobs -> DAB_ERR_UNSUPPORTED; ws missing or too
+ * small -> DAB_ERR_WORKSPACE.
+ */
+typedef struct dab_weight_job {
+    const float* W;                       /* [F][C][kh][kw] fp32 */
+    int32_t F, C, kh, kw;
+    float* alpha; float* beta; int32_t* K; float* thr_val; int32_t* thr_idx; uint8_t* alpha_is_upper;   /* [F] out */
+    uint32_t* E_packed; uint32_t* ecnt;   /* out, or both NULL */
+    const int32_t* K_prev; const uint8_t* alpha_is_upper_prev; int32_t max_change;   /* previous split, or both NULL */
+} dab_weight_job;
+size_t dab_binarize_weights_multi_workspace_bytes(const dab_weight_job* jobs /* host */, int32_t n_jobs);
+int dab_binarize_weights_multi(const dab_weight_job* jobs /* host */, int32_t n_jobs, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * dab_pack_activations - sign binarization of a layer input (Section 4: inputs
  * are +1 / -1) into bits along the channel dimension: bit = [x >= tau_c],
  * tau = 0 when tau is NULL (sign(0) = +1).
@@ -218,6 +247,23 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
  */
 int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, int32_t H, int32_t W,
                          const float* tau, uint32_t* A_packed, void* stream);
+
+/*
+ * dab_pack_activations_multi - dab_pack_activations for several tensors in one launch: the inputs
+ * of all binarized layers of a network that are resident together (Section 4: every binarized
+ * layer's input is +1 / -1).  Each job is one NHWC tensor with its own thresholds and output; the
+ * results are those of n_jobs separate calls.
+ *
+ *   jobs      host array of n_jobs descriptors (read during the call only); pointers inside are device pointers
+ * Errors: as dab_pack_activations per job; more than 16 jobs -> DAB_ERR_UNSUPPORTED.
+ */
+typedef struct dab_pack_job {
+    const float* X;              /* fp32 NHWC [B][H][W][C] */
+    const float* tau;            /* [C] or NULL */
+    uint32_t* A_packed;          /* uint32 [B][H][W][ceil(C/32)] out */
+    int32_t B, C, H, W;
+} dab_pack_job;
+int dab_pack_activations_multi(const dab_pack_job* jobs /* host */, int32_t n_jobs, void* stream);
 
 /*
  * dab_binconv2d - binarized convolution, Section 4.3.2's I (*) W~ on packed

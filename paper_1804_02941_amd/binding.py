@@ -63,6 +63,9 @@ _SIGNATURES = {
                                  c_void_p, c_void_p, c_void_p]),
     "dab_pack_activations": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
                                      c_void_p]),
+    "dab_pack_activations_multi": (c_int, [c_void_p, c_int32, c_void_p]),
+    "dab_binarize_weights_multi": (c_int, [c_void_p, c_int32, c_void_p, c_size_t, c_void_p]),
+    "dab_binarize_weights_multi_workspace_bytes": (c_size_t, [c_void_p, c_int32]),
     "dab_binconv2d": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p,
                               c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_binconv2d_workspace_bytes": (c_size_t, [ctypes.POINTER(dab_conv_desc)]),
@@ -225,6 +228,64 @@ def dab_pack_activations(X, layout=DAB_LAYOUT_NHWC, tau=None, out=None):
         _ptr(X, torch.float32, "X"), layout, B, C, H, W, _ptr(tau, torch.float32, "tau"),
         _ptr(A, torch.int32, "A_packed"), _stream()))
     return A
+
+
+class dab_weight_job(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("F", c_int32), ("C", c_int32), ("kh", c_int32), ("kw", c_int32),
+                ("alpha", c_void_p), ("beta", c_void_p), ("K", c_void_p), ("thr_val", c_void_p), ("thr_idx", c_void_p),
+                ("alpha_is_upper", c_void_p), ("E_packed", c_void_p), ("ecnt", c_void_p),
+                ("K_prev", c_void_p), ("alpha_is_upper_prev", c_void_p), ("max_change", c_int32)]
+
+
+def weight_jobs(items):
+    """A host array of dab_weight_job from dicts(W=[F,C,kh,kw], est=estimate_outputs(), packed=(E, ecnt) or None,
+    prev=(K_prev, alpha_is_upper_prev, max_change) or None); built once, reused per call."""
+    arr = (dab_weight_job * len(items))()
+    for k, it in enumerate(items):
+        W, est = it["W"], it["est"]
+        F, C, kh, kw = W.shape
+        E, ecnt = it.get("packed") or (None, None)
+        Kp, up, mc = it.get("prev") or (None, None, 0)
+        arr[k] = dab_weight_job(
+            _ptr(W, torch.float32, "W"), F, C, kh, kw, _ptr(est["alpha"], torch.float32, "alpha"),
+            _ptr(est["beta"], torch.float32, "beta"), _ptr(est["K"], torch.int32, "K"),
+            _ptr(est["thr_val"], torch.float32, "thr_val"), _ptr(est["thr_idx"], torch.int32, "thr_idx"),
+            _ptr(est["alpha_is_upper"], torch.uint8, "alpha_is_upper"), _ptr(E, torch.int32, "E_packed"),
+            _ptr(ecnt, torch.int32, "ecnt"), _ptr(Kp, torch.int32, "K_prev"), _ptr(up, torch.uint8, "alpha_is_upper_prev"), mc)
+    return arr
+
+
+def dab_binarize_weights_multi(jobs, ws=None):
+    """Estimation and weight packing of every job of weight_jobs() in two or three launches."""
+    nbytes = lib().dab_binarize_weights_multi_workspace_bytes(jobs, len(jobs))
+    if nbytes and (ws is None or ws.numel() * ws.element_size() < nbytes):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    _check("dab_binarize_weights_multi", lib().dab_binarize_weights_multi(
+        jobs, len(jobs), ws.data_ptr() if nbytes else None, nbytes, _stream()))
+
+
+class dab_pack_job(ctypes.Structure):
+    _fields_ = [("X", c_void_p), ("tau", c_void_p), ("A_packed", c_void_p),
+                ("B", c_int32), ("C", c_int32), ("H", c_int32), ("W", c_int32)]
+
+
+def pack_jobs(items):
+    """A host array of dab_pack_job from (X NHWC or [B,C], tau or None, A_packed) triples (built once, reused per call)."""
+    arr = (dab_pack_job * len(items))()
+    for k, (X, tau, A) in enumerate(items):
+        if X.dim() == 2:
+            B, C = X.shape
+            H = W = 1
+        else:
+            B, H, W, C = X.shape
+        arr[k] = dab_pack_job(_ptr(X, torch.float32, "X"), _ptr(tau, torch.float32, "tau"), _ptr(A, torch.int32, "A_packed"),
+                              B, C, H, W)
+    return arr
+
+
+def dab_pack_activations_multi(jobs):
+    """dab_pack_activations for every job of pack_jobs() in one launch."""
+    _check("dab_pack_activations_multi", lib().dab_pack_activations_multi(jobs, len(jobs), _stream()))
 
 
 def dab_binconv2d(desc, A_packed, E_packed, alpha, beta, want_s1=False, out=None, ws=None):

@@ -138,12 +138,20 @@ __device__ __forceinline__ Best wave_best_of(Best v) {                        //
     return v;
 }
 
+// The split descriptor of the row a workgroup has just estimated, left in LDS for the packing that
+// follows in the same kernel (nullptr where nothing follows).
+struct SplitInfo {
+    float thr_val;
+    int thr_idx;
+    int upper;
+};
+
 // Row f of the layer, by the workgroup's THREADS threads (all of them call this together).
 template <int THREADS, int ITEMS>
 __device__ __forceinline__ void sort_row(const float* __restrict__ Wt, int n, int f, float* __restrict__ alpha,
                                          float* __restrict__ beta, int32_t* Kout, float* __restrict__ thr_val,
                                          int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper, const int32_t* K_prev,
-                                         const uint8_t* upper_prev, int max_change) {
+                                         const uint8_t* upper_prev, int max_change, SplitInfo* info = nullptr) {
     static_assert(ITEMS >= 1 && ITEMS <= 15, "a digit counter has 4 bits");
     constexpr int NW = THREADS / 64;
     constexpr int N = THREADS * ITEMS;
@@ -290,6 +298,7 @@ __device__ __forceinline__ void sort_row(const float* __restrict__ Wt, int n, in
         thr_s = key_to_float(tk);
         thr_val[f] = thr_s;
         r_s = is - a;                               // >= 1 copies of the value are "lower"
+        if (info) { info->thr_val = thr_s; info->upper = upper ? 1 : 0; }
     }
     __syncthreads();
 
@@ -308,6 +317,7 @@ __device__ __forceinline__ void sort_row(const float* __restrict__ Wt, int n, in
         for (int i = lo; i < hi; ++i) {
             if (row[i] == tv && ++seen == r) {
                 thr_idx[f] = i;
+                if (info) info->thr_idx = i;
                 break;
             }
         }
@@ -354,7 +364,7 @@ template <int THREADS, int ITEMS, int NB, int CAP>
 __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, int f, float* __restrict__ alpha,
                                            float* __restrict__ beta, int32_t* Kout, float* __restrict__ thr_val,
                                            int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper, const int32_t* K_prev,
-                                           const uint8_t* upper_prev, int max_change) {
+                                           const uint8_t* upper_prev, int max_change, SplitInfo* info = nullptr) {
     constexpr int NW = THREADS / 64;
     constexpr int BPT = NB / THREADS;                              // buckets per thread
     __shared__ uint32_t cnt[NB + 1];                               // counts, then the exclusive prefix N_b (N_NB = n)
@@ -657,11 +667,15 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
         Kout[f] = upper ? n - is : is;
         alpha_is_upper[f] = upper ? 1 : 0;
         thr_val[f] = key_to_float(wkey);
+        if (info) { info->thr_val = key_to_float(wkey); info->upper = upper ? 1 : 0; }
     }
 
     // ---- the split descriptor's index: the r-th copy of the split value in the order of the row.
     // Every copy is a candidate (equal values share a bucket) and knows how many copies precede it.
-    if (has && part == 0 && my_key == wkey && my_first + 1 == r_s) thr_idx[f] = static_cast<int32_t>(my_idx);
+    if (has && part == 0 && my_key == wkey && my_first + 1 == r_s) {
+        thr_idx[f] = static_cast<int32_t>(my_idx);
+        if (info) info->thr_idx = static_cast<int>(my_idx);
+    }
     return true;
 }
 
@@ -696,6 +710,133 @@ __global__ __launch_bounds__(THREADS) void estimate_short_kernel(const float* __
         return;
     __syncthreads();
     sort_row<THREADS, ITEMS>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev, upper_prev, max_change);
+}
+
+// ---------------------------------------------------------------- estimation and packing of several layers
+// Section 4.3.1 treats all filters of a layer at once; nothing ties a filter to its layer, so the
+// filters of several layers can share a launch, and the mask of a filter (Corollary 1) can be packed
+// by the workgroup that has just found its split, while the row is still in L2: the weights are
+// read from memory once, and a network's weight side is two or three launches whatever its depth.
+constexpr int kMaxEstJobs = 16;
+constexpr int kPackMaxTaps = 128;
+struct EstJob {
+    const float* W;
+    float* alpha; float* beta; int32_t* K; float* thr_val; int32_t* thr_idx; uint8_t* aiu;
+    const int32_t* K_prev; const uint8_t* upper_prev;
+    uint32_t* E; uint32_t* ecnt;                   // packed mask [T*Cw][Fp] and per-tap counts [F][T], or both nullptr
+    uint8_t* flags;                                // long rows: one hand-over flag per filter
+    int n, F, C, T, Cw, Fp, max_change;
+    unsigned blk_end;                              // first workgroup past this job's range
+};
+struct EstJobs {
+    int n;
+    EstJob job[kMaxEstJobs];
+};
+
+// Workgroup r of a job takes filter column f: consecutive workgroups go to consecutive XCDs, and a
+// column of E is one 4-byte word per row, so an XCD gets a contiguous range of columns and the
+// partial lines of neighbouring filters merge in one L2.
+__device__ __forceinline__ int job_column(unsigned r, int Fp) {
+    const int per_xcd = (Fp + kNumXCD - 1) / kNumXCD;
+    const int f = static_cast<int>(r % kNumXCD) * per_xcd + static_cast<int>(r / kNumXCD);
+    return static_cast<int>(r / kNumXCD) < per_xcd ? f : Fp;
+}
+
+// The mask of filter column f as bits (Corollary 1, by stable rank: the split descriptor), by the
+// whole workgroup: a byte per weight into LDS (the row is re-read, from L2), then one thread per
+// packed word gathers its 32 channels (stride T), writes the word into column f of E and adds its
+// ones to the tap's count.  Columns past F are written as zeros.
+template <int THREADS, int MAXN>
+__device__ __forceinline__ void pack_row(const EstJob& q, int f, const SplitInfo* info) {
+    __shared__ uint8_t maskb[MAXN];
+    __shared__ uint32_t tapcnt[kPackMaxTaps];
+    const int tid = threadIdx.x;
+    const int R = q.T * q.Cw;
+    if (f >= q.F) {
+        for (int r = tid; r < R; r += THREADS) q.E[static_cast<size_t>(r) * q.Fp + f] = 0u;
+        return;
+    }
+    const float tv = info->thr_val;
+    const int ti = info->thr_idx;
+    const bool upper = info->upper != 0;
+    const float* row = q.W + static_cast<size_t>(f) * q.n;
+    for (int i = tid; i < q.n; i += THREADS) {
+        const float w = row[i];
+        const bool lower = w < tv || (w == tv && i <= ti);
+        maskb[i] = lower != upper ? 1 : 0;
+    }
+    for (int t = tid; t < q.T; t += THREADS) tapcnt[t] = 0u;
+    __syncthreads();
+    for (int r = tid; r < R; r += THREADS) {
+        const int tap = r / q.Cw, w = r - tap * q.Cw;
+        const int c0 = 32 * w, nc = min(32, q.C - c0);
+        uint32_t word = 0;
+        for (int k = 0; k < nc; ++k) word |= static_cast<uint32_t>(maskb[(c0 + k) * q.T + tap]) << k;
+        q.E[static_cast<size_t>(r) * q.Fp + f] = word;
+        atomicAdd(&tapcnt[tap], static_cast<uint32_t>(__builtin_popcount(word)));
+    }
+    __syncthreads();
+    for (int t = tid; t < q.T; t += THREADS) q.ecnt[static_cast<size_t>(f) * q.T + t] = tapcnt[t];
+}
+
+__device__ __forceinline__ const EstJob& find_job(const EstJobs& jobs, unsigned* blk0) {
+    int j = 0;
+    *blk0 = 0;
+    while (j + 1 < jobs.n && blockIdx.x >= jobs.job[j].blk_end) *blk0 = jobs.job[j++].blk_end;
+    return jobs.job[j];
+}
+
+// Rows of up to THREADS * ITEMS weights: buckets first, the sort by the same workgroup where they
+// cannot finish the row, then the packing.
+template <int THREADS, int ITEMS, int NB, int CAP>
+__global__ __launch_bounds__(THREADS) void binarize_short_kernel(const EstJobs jobs) {
+    DAB_RESERVE_VGPRS();
+    __shared__ SplitInfo info;
+    unsigned blk0;
+    const EstJob& q = find_job(jobs, &blk0);
+    const int f = job_column(blockIdx.x - blk0, q.Fp);
+    if (f >= q.Fp) return;
+    if (f < q.F) {
+        if (!bucket_row<THREADS, ITEMS, NB, CAP>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev,
+                                                 q.upper_prev, q.max_change, &info)) {
+            __syncthreads();
+            sort_row<THREADS, ITEMS>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev, q.upper_prev,
+                                     q.max_change, &info);
+        }
+        __syncthreads();
+    }
+    if (q.E) pack_row<THREADS, THREADS * ITEMS>(q, f, &info);
+}
+
+// Longer rows: buckets; a row they cannot finish is flagged for the sort kernel launched behind.
+template <int THREADS, int ITEMS, int NB, int CAP>
+__global__ __launch_bounds__(THREADS) void binarize_long_kernel(const EstJobs jobs) {
+    DAB_RESERVE_VGPRS();
+    __shared__ SplitInfo info;
+    unsigned blk0;
+    const EstJob& q = find_job(jobs, &blk0);
+    const int f = job_column(blockIdx.x - blk0, q.Fp);
+    if (f >= q.Fp) return;
+    bool done = true;
+    if (f < q.F) {
+        done = bucket_row<THREADS, ITEMS, NB, CAP>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev,
+                                                   q.upper_prev, q.max_change, &info);
+        if (threadIdx.x == 0) q.flags[f] = done ? 0 : 1;
+        __syncthreads();
+    }
+    if (q.E && done) pack_row<THREADS, THREADS * ITEMS>(q, f, &info);
+}
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void binarize_sort_kernel(const EstJobs jobs) {
+    __shared__ SplitInfo info;
+    unsigned blk0;
+    const EstJob& q = find_job(jobs, &blk0);
+    const int f = static_cast<int>(blockIdx.x - blk0);
+    if (f >= q.F || !q.flags[f]) return;            // the bucket kernel has finished this row
+    sort_row<THREADS, ITEMS>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev, q.upper_prev, q.max_change,
+                             &info);
+    __syncthreads();
+    if (q.E) pack_row<THREADS, THREADS * ITEMS>(q, f, &info);
 }
 
 // ---------------------------------------------------------------- sign split (XNOR-Net / BWN)
@@ -810,6 +951,69 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
 #undef DAB_EST
 }
 
+// ---------------------------------------------------------------- host side of the multi-layer call
+constexpr int kShortMaxN = 512 * 9;                // rows up to here: binarize_short_kernel (one configuration for all)
+
+static int check_weight_job(const dab_weight_job& j) {
+    if (!j.W || !j.alpha || !j.beta || !j.K || !j.thr_val || !j.thr_idx || !j.alpha_is_upper) return DAB_ERR_NULL;
+    if ((j.E_packed == nullptr) != (j.ecnt == nullptr)) return DAB_ERR_NULL;
+    if ((j.K_prev == nullptr) != (j.alpha_is_upper_prev == nullptr)) return DAB_ERR_NULL;
+    if (j.F < 1 || j.C < 1 || j.kh < 1 || j.kw < 1 || 1ll * j.C * j.kh * j.kw < 2 || (j.K_prev && j.max_change < 0))
+        return DAB_ERR_SHAPE;
+    if (misaligned(j.W, 4) || misaligned(j.alpha, 4) || misaligned(j.beta, 4) || misaligned(j.K, 4) || misaligned(j.thr_val, 4) ||
+        misaligned(j.thr_idx, 4) || (j.E_packed && (misaligned(j.E_packed, 64) || misaligned(j.ecnt, 4))) ||
+        (j.K_prev && misaligned(j.K_prev, 4)))
+        return DAB_ERR_ALIGN;
+    if (1ll * j.C * j.kh * j.kw > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
+    if (j.E_packed && j.kh * j.kw > kPackMaxTaps) return DAB_ERR_UNSUPPORTED;
+    return DAB_OK;
+}
+
+static size_t weight_jobs_ws_bytes(const dab_weight_job* jobs, int n_jobs) {
+    size_t total = 0;
+    for (int i = 0; i < n_jobs; ++i)
+        if (1ll * jobs[i].C * jobs[i].kh * jobs[i].kw > kShortMaxN) total += (static_cast<size_t>(jobs[i].F) + 255) & ~static_cast<size_t>(255);
+    return total;
+}
+
+static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, size_t ws_bytes, hipStream_t st) {
+    EstJobs shortj, longj, sortj;
+    shortj.n = longj.n = sortj.n = 0;
+    unsigned short_end = 0, long_end = 0, sort_end = 0;
+    uint8_t* flags = static_cast<uint8_t*>(ws);
+    for (int i = 0; i < n_jobs; ++i) {
+        const dab_weight_job& in = jobs[i];
+        EstJob q{};
+        q.W = in.W; q.alpha = in.alpha; q.beta = in.beta; q.K = in.K; q.thr_val = in.thr_val; q.thr_idx = in.thr_idx;
+        q.aiu = in.alpha_is_upper; q.K_prev = in.K_prev; q.upper_prev = in.alpha_is_upper_prev; q.max_change = in.max_change;
+        q.E = in.E_packed; q.ecnt = in.ecnt;
+        q.F = in.F; q.C = in.C; q.T = in.kh * in.kw; q.n = in.C * q.T; q.Cw = ceil_div(in.C, 32); q.Fp = 64 * ceil_div(in.F, 64);
+        const unsigned columns = static_cast<unsigned>(kNumXCD * ceil_div(q.Fp, kNumXCD));
+        if (q.n <= kShortMaxN) {
+            short_end += columns;
+            q.blk_end = short_end;
+            shortj.job[shortj.n++] = q;
+        } else {
+            q.flags = flags;
+            flags += (static_cast<size_t>(in.F) + 255) & ~static_cast<size_t>(255);
+            long_end += columns;
+            q.blk_end = long_end;
+            longj.job[longj.n++] = q;
+            sort_end += static_cast<unsigned>(in.F);
+            q.blk_end = sort_end;
+            sortj.job[sortj.n++] = q;
+        }
+    }
+    (void)ws_bytes;
+    if (shortj.n)
+        if (int rc = launch(binarize_short_kernel<512, 9, 2048, 256>, dim3(short_end), dim3(512), 0, st, shortj)) return rc;
+    if (longj.n) {
+        if (int rc = launch(binarize_long_kernel<512, 26, 2048, 512>, dim3(long_end), dim3(512), 0, st, longj)) return rc;
+        if (int rc = launch(binarize_sort_kernel<1024, 13>, dim3(sort_end), dim3(1024), 0, st, sortj)) return rc;
+    }
+    return DAB_OK;
+}
+
 // ---------------------------------------------------------------- hand-over flags owned by the library
 // dab_estimate_alpha_beta_noalloc keeps the per-row flags of the bucket kernel in this array instead
 // of a caller's workspace.  The name is a host-side stand-in for the symbol: the device address is
@@ -846,6 +1050,23 @@ int dab_estimate_alpha_beta(const float* W, int32_t F, int32_t n, float* alpha, 
     if (n > kEstimateMaxN) return DAB_ERR_UNSUPPORTED;
     return dispatch_estimate(W, F, n, alpha, beta, K, thr_val, thr_idx, alpha_is_upper, nullptr, nullptr, 0, ws, ws_bytes,
                              static_cast<hipStream_t>(stream));
+}
+
+size_t dab_binarize_weights_multi_workspace_bytes(const dab_weight_job* jobs, int32_t n_jobs) {
+    if (!jobs || n_jobs < 1 || n_jobs > dab::kMaxEstJobs) return 0;
+    return dab::weight_jobs_ws_bytes(jobs, n_jobs);
+}
+
+int dab_binarize_weights_multi(const dab_weight_job* jobs, int32_t n_jobs, void* ws, size_t ws_bytes, void* stream) {
+    using namespace dab;
+    if (!jobs) return DAB_ERR_NULL;
+    if (n_jobs < 1) return DAB_ERR_SHAPE;
+    if (n_jobs > kMaxEstJobs) return DAB_ERR_UNSUPPORTED;
+    for (int i = 0; i < n_jobs; ++i)
+        if (int rc = check_weight_job(jobs[i])) return rc;
+    const size_t need = weight_jobs_ws_bytes(jobs, n_jobs);
+    if (need && (!ws || ws_bytes < need)) return DAB_ERR_WORKSPACE;
+    return run_weight_jobs(jobs, n_jobs, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int32_t dab_estimate_noalloc_max_filters(void) { return dab::kNoAllocMaxFilters; }

@@ -17,14 +17,12 @@ namespace dab {
 // thresholds in registers.
 constexpr int kItemsPerWave = 16;
 
+// (wave, n_waves: this wavefront's index among those that share the tensor)
 template <bool PERIODIC>
-__global__ __launch_bounds__(256) void pack_act_nhwc_kernel(const float* __restrict__ X, const float* __restrict__ tau,
-                                                            uint32_t* __restrict__ A, int n_items,
-                                                            int C, int Cw, int Cw64, FastDiv d_Cw64) {
-    DAB_RESERVE_VGPRS();
+__device__ __forceinline__ void pack_act_nhwc(const float* __restrict__ X, const float* __restrict__ tau,
+                                              uint32_t* __restrict__ A, int n_items, int C, int Cw, int Cw64,
+                                              FastDiv d_Cw64, int wave, int n_waves) {
     const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const int n_waves = gridDim.x * (blockDim.x >> 6);
 
     float th[kItemsPerWave];
     if (PERIODIC) {
@@ -63,19 +61,25 @@ __global__ __launch_bounds__(256) void pack_act_nhwc_kernel(const float* __restr
     }
 }
 
+template <bool PERIODIC>
+__global__ __launch_bounds__(256) void pack_act_nhwc_kernel(const float* __restrict__ X, const float* __restrict__ tau,
+                                                            uint32_t* __restrict__ A, int n_items,
+                                                            int C, int Cw, int Cw64, FastDiv d_Cw64) {
+    DAB_RESERVE_VGPRS();
+    pack_act_nhwc<PERIODIC>(X, tau, A, n_items, C, Cw, Cw64, d_Cw64,
+                            static_cast<int>(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)),
+                            static_cast<int>(gridDim.x * (blockDim.x >> 6)));
+}
+
 // Fast path: C a multiple of 64 whose 64-channel groups divide sixteen.  Item t then starts at
 // float 64*t of X and at word 2*t of A, so a batch of sixteen items is one base address plus
 // immediate offsets, and the thresholds of the batch stay in registers.
 // CW64 (the 64-channel groups per pixel: 1, 2, 4, 8 or 16) is a template parameter so that only
 // CW64 thresholds are held beside the two batches of sixteen values (45-48 VGPRs up to 256 channels).
 template <int CW64>
-__global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float* __restrict__ X,
-                                                                    const float* __restrict__ tau,
-                                                                    uint32_t* __restrict__ A, int n_items) {
-    if (CW64 >= 8) DAB_RESERVE_VGPRS();                     // these would land on 64 registers
+__device__ __forceinline__ void pack_act_nhwc_aligned(const float* __restrict__ X, const float* __restrict__ tau,
+                                                      uint32_t* __restrict__ A, int n_items, int wave, int n_waves) {
     const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const int n_waves = gridDim.x * (blockDim.x >> 6);
     float thc[CW64];
 #pragma unroll
     for (int u = 0; u < CW64; ++u) thc[u] = tau ? tau[u * 64 + lane] : 0.0f;
@@ -125,6 +129,52 @@ __global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float*
             if (lane == 2 * u + 1) word = static_cast<uint32_t>(mask >> 32);
         }
         if (lane < 2 * kItemsPerWave && t0 + (lane >> 1) < n_items) A[static_cast<size_t>(t0) * 2 + lane] = word;
+    }
+}
+
+template <int CW64>
+__global__ __launch_bounds__(256) void pack_act_nhwc_aligned_kernel(const float* __restrict__ X,
+                                                                    const float* __restrict__ tau,
+                                                                    uint32_t* __restrict__ A, int n_items) {
+    if (CW64 >= 8) DAB_RESERVE_VGPRS();                     // these would land on 64 registers
+    pack_act_nhwc_aligned<CW64>(X, tau, A, n_items, static_cast<int>(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)),
+                                static_cast<int>(gridDim.x * (blockDim.x >> 6)));
+}
+
+// Several tensors in one launch (the inputs of all layers of a network that are resident together):
+// every tensor gets a contiguous range of the grid's workgroups, in proportion to its size, and
+// those workgroups run the code of its own kind (the aligned fast path for its channel count, or
+// the general one).
+constexpr int kMaxPackJobs = 16;
+struct PackJob {
+    const float* X;
+    const float* tau;
+    uint32_t* A;
+    int n_items, C, Cw, Cw64, kind;       // kind: 64-channel groups per pixel of the aligned path (1..16), 0 = general periodic, -1 = general
+    FastDiv d_Cw64;
+    unsigned blk_end;                     // first workgroup past this tensor's range
+};
+struct PackJobs {
+    int n;
+    PackJob job[kMaxPackJobs];
+};
+
+__global__ __launch_bounds__(256) void pack_act_multi_kernel(const PackJobs jobs) {
+    DAB_RESERVE_VGPRS();
+    int j = 0;
+    unsigned blk0 = 0;
+    while (j + 1 < jobs.n && blockIdx.x >= jobs.job[j].blk_end) blk0 = jobs.job[j++].blk_end;
+    const PackJob& q = jobs.job[j];
+    const int wave = static_cast<int>((blockIdx.x - blk0) * (blockDim.x >> 6) + (threadIdx.x >> 6));
+    const int n_waves = static_cast<int>((q.blk_end - blk0) * (blockDim.x >> 6));
+    switch (q.kind) {
+        case 1: pack_act_nhwc_aligned<1>(q.X, q.tau, q.A, q.n_items, wave, n_waves); break;
+        case 2: pack_act_nhwc_aligned<2>(q.X, q.tau, q.A, q.n_items, wave, n_waves); break;
+        case 4: pack_act_nhwc_aligned<4>(q.X, q.tau, q.A, q.n_items, wave, n_waves); break;
+        case 8: pack_act_nhwc_aligned<8>(q.X, q.tau, q.A, q.n_items, wave, n_waves); break;
+        case 16: pack_act_nhwc_aligned<16>(q.X, q.tau, q.A, q.n_items, wave, n_waves); break;
+        case 0: pack_act_nhwc<true>(q.X, q.tau, q.A, q.n_items, q.C, q.Cw, q.Cw64, q.d_Cw64, wave, n_waves); break;
+        default: pack_act_nhwc<false>(q.X, q.tau, q.A, q.n_items, q.C, q.Cw, q.Cw64, q.d_Cw64, wave, n_waves); break;
     }
 }
 
@@ -355,6 +405,45 @@ int dab_pack_activations(const float* X, int32_t layout, int32_t B, int32_t C, i
     if (HW >= (1ll << 31) || Cw > 65535 || B > 65535) return DAB_ERR_UNSUPPORTED;
     return launch(pack_act_nchw_kernel, dim3(ceil_div(static_cast<int>(HW), 256), Cw, B), dim3(256), 0, st, X, tau,
                   A_packed, C, static_cast<int>(HW), Cw);
+}
+
+int dab_pack_activations_multi(const dab_pack_job* jobs, int32_t n_jobs, void* stream) {
+    using namespace dab;
+    if (!jobs) return DAB_ERR_NULL;
+    if (n_jobs < 1) return DAB_ERR_SHAPE;
+    if (n_jobs > kMaxPackJobs) return DAB_ERR_UNSUPPORTED;
+    PackJobs pj;
+    pj.n = n_jobs;
+    long long total = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const dab_pack_job& in = jobs[i];
+        if (!in.X || !in.A_packed) return DAB_ERR_NULL;
+        if (in.B < 1 || in.C < 1 || in.H < 1 || in.W < 1) return DAB_ERR_SHAPE;
+        if (misaligned(in.X, 4) || misaligned(in.A_packed, 16) || (in.tau && misaligned(in.tau, 4))) return DAB_ERR_ALIGN;
+        const long long pixels = 1ll * in.B * in.H * in.W;
+        const int Cw64 = ceil_div(in.C, 64);
+        const long long n_items = pixels * Cw64;
+        if (n_items >= (1ll << 30)) return DAB_ERR_UNSUPPORTED;
+        PackJob& q = pj.job[i];
+        q.X = in.X; q.tau = in.tau; q.A = in.A_packed;
+        q.n_items = static_cast<int>(n_items); q.C = in.C; q.Cw = ceil_div(in.C, 32); q.Cw64 = Cw64;
+        q.d_Cw64 = make_fastdiv(Cw64);
+        const bool periodic = Cw64 <= kItemsPerWave && (Cw64 & (Cw64 - 1)) == 0;
+        q.kind = periodic && in.C % 64 == 0 ? Cw64 : (periodic ? 0 : -1);
+        total += n_items;
+    }
+    // four wavefronts per SIMD over the chip, shared out by size (at least one workgroup per tensor)
+    const long long budget = 4ll * kNumCU;
+    unsigned end = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const long long waves = (pj.job[i].n_items + kItemsPerWave - 1) / kItemsPerWave;
+        long long blocks = (budget * pj.job[i].n_items + total - 1) / total;
+        if (blocks > (waves + 3) / 4) blocks = (waves + 3) / 4;
+        if (blocks < 1) blocks = 1;
+        end += static_cast<unsigned>(blocks);
+        pj.job[i].blk_end = end;
+    }
+    return launch(pack_act_multi_kernel, dim3(end), dim3(256), 0, static_cast<hipStream_t>(stream), pj);
 }
 
 int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t kw,

@@ -1,0 +1,104 @@
+"""The grouped entry points: several layers' weight sides in one call (dab_binarize_weights_multi).
+
+Every job's estimate is checked against the oracle filter by filter (as in test_gpu_parity.py) and its
+packed mask and per-tap counts bit for bit against the oracle's packing of the mask the estimate
+implies; the call with a previous split is checked against the oracle's restricted search."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import packing as opk
+from paper_1804_02941_amd import binding as dab
+from paper_1804_02941_amd import workloads as wl
+
+import gpu_util as gu
+from test_gpu_parity import weight_rows
+from test_gpu_training import check_bounded
+
+pytestmark = pytest.mark.gpu
+
+# (F, C, kh, kw, kind): short rows down to two weights, rows around the limits of the kernels, long
+# rows including ones the value buckets hand over to the sort (few distinct values), filter counts
+# that are not multiples of 64
+JOBS = [(70, 45, 2, 3, "dupes"), (5, 3, 1, 1, "gauss"), (64, 64, 3, 3, "mixture"), (130, 100, 5, 5, "laplace"),
+        (9, 256, 7, 7, "gauss"), (33, 5000, 1, 1, "dupes"), (40, 512, 1, 1, "mixture"), (3, 2, 1, 1, "onesided"),
+        (17, 4608, 1, 1, "gauss"), (6, 4609, 1, 1, "mixture"), (4, 13312, 1, 1, "laplace"), (12, 256, 3, 3, "onesided")]
+
+
+def make_items(rng, with_packing=True):
+    items, Ws = [], []
+    for (F, C, kh, kw, kind) in JOBS:
+        W = weight_rows(rng, F, C * kh * kw, kind).reshape(F, C, kh, kw)
+        if kind == "dupes":
+            W[0] = 0.25                                           # a constant filter
+        Ws.append(W)
+        Wt = gu.to_gpu(W)
+        items.append(dict(W=Wt, est=dab.estimate_outputs(F, Wt.device),
+                          packed=dab.pack_weights_outputs(F, C, kh, kw, Wt.device) if with_packing else None))
+    return items, Ws
+
+
+def test_binarize_weights_multi_against_the_oracle():
+    rng = np.random.default_rng(2024)
+    items, Ws = make_items(rng)
+    for it in items:                                              # every word must be written by the call
+        it["packed"][0].fill_(-1)
+        it["packed"][1].fill_(-1)
+    dab.dab_binarize_weights_multi(dab.weight_jobs(items))
+    torch.cuda.synchronize()
+    for it, W in zip(items, Ws):
+        got = {k: v.cpu().numpy() for k, v in it["est"].items()}
+        e, differ = gu.check_estimate(W, got)
+        assert differ <= 1
+        E_ref, ecnt_ref = opk.pack_weights(e)
+        assert np.array_equal(gu.u32(it["packed"][0]), E_ref), W.shape
+        assert np.array_equal(gu.u32(it["packed"][1]), ecnt_ref), W.shape
+
+
+def test_binarize_weights_multi_equals_separate_calls_and_runs_without_packing():
+    rng = np.random.default_rng(2025)
+    items, Ws = make_items(rng)
+    dab.dab_binarize_weights_multi(dab.weight_jobs(items))
+    bare, _ = make_items(np.random.default_rng(2025), with_packing=False)
+    dab.dab_binarize_weights_multi(dab.weight_jobs(bare))
+    torch.cuda.synchronize()
+    for it, b, W in zip(items, bare, Ws):
+        for k in it["est"]:
+            assert torch.equal(it["est"][k], b["est"][k]), k       # packing changes nothing of the estimate
+        # the packing of the separate call, fed this estimate
+        E, ecnt = dab.dab_pack_weights(it["W"], it["est"]["thr_val"], it["est"]["thr_idx"], it["est"]["alpha_is_upper"])
+        torch.cuda.synchronize()
+        assert torch.equal(E, it["packed"][0]) and torch.equal(ecnt, it["packed"][1])
+
+
+def test_binarize_weights_multi_with_previous_split():
+    rng = np.random.default_rng(2026)
+    shapes = [(24, 64, 3, 3), (10, 700, 3, 3), (16, 128, 5, 5)]
+    items, W1 = [], []
+    for (F, C, kh, kw) in shapes:
+        n = C * kh * kw
+        w0 = wl.skewed_mixture_weights(rng, rng, F, n, n)
+        prev = dab.dab_estimate_alpha_beta(gu.to_gpu(w0))
+        w1 = (w0 + 0.05 * np.float32(np.sqrt(2.0 / n)) * rng.standard_normal((F, n))).astype(np.float32)
+        W1.append((w1, prev["K"].cpu().numpy(), prev["alpha_is_upper"].cpu().numpy()))
+        Wt = gu.to_gpu(w1.reshape(F, C, kh, kw))
+        items.append(dict(W=Wt, est=dab.estimate_outputs(F, Wt.device), packed=dab.pack_weights_outputs(F, C, kh, kw, Wt.device),
+                          prev=(prev["K"], prev["alpha_is_upper"], max(2, n // 50))))
+    dab.dab_binarize_weights_multi(dab.weight_jobs(items))
+    torch.cuda.synchronize()
+    for it, (w1, Kp, up), (F, C, kh, kw) in zip(items, W1, shapes):
+        check_bounded(w1, {k: v.cpu().numpy() for k, v in it["est"].items()}, Kp, up, max(2, C * kh * kw // 50))
+
+
+def test_binarize_weights_multi_errors():
+    lib = dab.lib()
+    rng = np.random.default_rng(1)
+    items, _ = make_items(rng)
+    jobs = dab.weight_jobs(items)
+    assert lib.dab_binarize_weights_multi(None, 1, None, 0, None) == dab.DAB_ERR_NULL
+    assert lib.dab_binarize_weights_multi(jobs, 0, None, 0, None) == dab.DAB_ERR_SHAPE
+    assert lib.dab_binarize_weights_multi(jobs, 17, None, 0, None) == dab.DAB_ERR_UNSUPPORTED
+    assert lib.dab_binarize_weights_multi_workspace_bytes(jobs, len(jobs)) > 0
+    assert lib.dab_binarize_weights_multi(jobs, len(jobs), None, 0, None) == dab.DAB_ERR_WORKSPACE   # long rows need the flags
+    assert lib.dab_binarize_weights_multi_workspace_bytes(jobs, 3) == 0                            # short rows only
+    torch.cuda.synchronize()

@@ -53,6 +53,31 @@ def test_pack_activations_fc_and_ragged_sizes():
         assert np.array_equal(gu.u32(A).reshape(ref.shape), ref)
 
 
+def test_pack_activations_multi():
+    """Several tensors in one launch: bit for bit the oracle's packing of each (and so the separate calls')."""
+    rng = np.random.default_rng(99)
+    shapes = [(3, 5, 7, 64), (2, 9, 4, 128), (5, 3, 3, 256), (1, 2, 2, 512), (4, 6, 5, 1024), (7, 1, 1, 70), (130, 1, 1, 4096),
+              (2, 4, 4, 1), (3, 2, 5, 96), (1, 1, 1, 2048)]
+    items, refs = [], []
+    for k, (B, H, W, C) in enumerate(shapes):
+        x = rng.standard_normal((B, C, H, W)).astype(np.float32)
+        tau = None if k % 3 == 0 else (rng.standard_normal(C) * 0.5).astype(np.float32)
+        refs.append(opk.pack_activations(olay.binarize_activations(x, tau)))
+        X = gu.to_gpu(np.transpose(x, (0, 2, 3, 1)))
+        items.append((X, gu.to_gpu(tau) if tau is not None else None,
+                      torch.full((B, H, W, dab.words_per_pixel(C)), -1, dtype=torch.int32, device=gu.DEV)))
+    dab.dab_pack_activations_multi(dab.pack_jobs(items))
+    torch.cuda.synchronize()
+    for (X, tau, A), ref in zip(items, refs):
+        assert np.array_equal(gu.u32(A), ref)
+    # a single job, and too many jobs
+    dab.dab_pack_activations_multi(dab.pack_jobs(items[:1]))
+    with pytest.raises(dab.DabError) as ei:
+        dab.dab_pack_activations_multi(dab.pack_jobs(items * 2))
+    assert ei.value.status == 5
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ dab_estimate_alpha_beta
 def weight_rows(rng, F, n, kind):
     if kind == "gauss":
