@@ -8,14 +8,18 @@ path over the batch: for every layer, alpha/beta estimation of its filters, weig
 packing, activation bit packing and the binary convolution / fully-connected product.  The
 fp32 inputs of all layers and the fp32 weights are resident in HBM before the timed region.
 
-A step is launched as one captured HIP graph: the weight sides of all layers (they depend on
-no activation) run on side streams while the main stream packs the activations of all layers;
-the products follow on two streams (each on the one with less product time so far).  The timed
-region is K graph launches.
+A step is a handful of launches, captured as one HIP graph: one launch packs the activations of
+all six layers; the weight sides (estimation + mask packing; they depend on no activation) are
+two grouped calls on two side streams (the five layers with short filters in one launch, conv6
+with its 12544-element filters in its own); each binary product is a single launch that reads
+the packed bits and writes fp32.  The timed region is K graph launches.
 
 Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
-call (the binary product of the largest layer) from HIP-event timings of an eager pass over
-the same kernels, and the CPU oracle timed on the same workload.
+kernel (the binary product of the largest layer), a table of every stage against the HBM
+roofline, and the CPU oracle timed on the same workload.  Device times of single calls are
+taken from graphs that hold the call several times back to back on one stream, the replay
+bracketed by HIP events on that stream: the host cannot enqueue small kernels as fast as the
+chip runs them, so an event pair around eager launches would time the host.
 """
 from __future__ import annotations
 
@@ -32,16 +36,18 @@ if ROOT not in sys.path:
 
 # Rooflines of the binary product on MI355X.
 #   MFMA, fp4 operands (the kernel that ships): published dense peak 10.1 PFLOP/s = 5.05e15 MAC/s.
-#   Vector ALU popcount form, for comparison: 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s and
-#   one AND + one BCNT per 32 binary MACs of a lane, i.e. at most 6.29e14 binary MAC/s.
-#   HBM: 8 TB/s; a layer writes 4 bytes per output and reads its packed/expanded operands.
+#   Vector ALU popcount form, for comparison: 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s;
+#   P_bcnt counts the popcount alone (32 MACs per lane-op), P_pair the AND + popcount a product needs (16).
+#   HBM: 8 TB/s; a layer writes 4 bytes per output and reads its packed operands.
 MFMA_FP4_FLOPS = 10.1e15
 MFMA_BF16_FLOPS = 2.5e15
-VALU_PAIR_MACS = 256 * 64 * 2.4e9 * 16
+VALU_LANE_OPS = 256 * 64 * 2.4e9
+P_BCNT_SPEC = VALU_LANE_OPS * 32
+P_PAIR_SPEC = VALU_LANE_OPS * 16
 HBM_BYTES_PER_S = 8.0e12
-# HBM bytes of one conv2 call at batch 256 (prepare + main kernel), from the FETCH_SIZE and WRITE_SIZE
-# counter runs summarised in profiles/bench_config3_hbm_counters.md
-CONV2_CALL_HBM_BYTES = 157136400
+# HBM byte counters of the dominant kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file,
+# scaled by a copy of known size); the file records the commit it was measured at.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
 def parse():
@@ -51,22 +57,52 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=256, help="images per step (the metric is quoted at 256)")
     ap.add_argument("--cpu-batch", type=int, default=256, help="images of the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--product-streams", type=int, default=2,
-                    help="streams the binary products alternate over (1 = all on the main stream)")
-    ap.add_argument("--side-streams", type=int, default=2,
-                    help="HIP streams for the weight side (estimation + weight packing) of the layers; 0 = one stream")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of one captured HIP graph per step")
-    ap.add_argument("--wait-all", action="store_true",
-                    help="let the first product wait for the weight sides of all layers (default: each product waits "
-                         "only for its own layer's weights, so later layers' weight sides run beside earlier products)")
-    ap.add_argument("--no-fused", action="store_true", help="skip the measurements beside the headline (fused chain, training side, weights-only layers)")
+    ap.add_argument("--one-stream", action="store_true", help="put the weight sides on the main stream as well")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the measurements beside the headline (stage table, other configs, fused chain, "
+                         "training side, weights-only layers, small batch)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies (a known-size kernel that scales the "
                          "HBM byte counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
+# ------------------------------------------------------------------------------------------------
+# device timing
+def device_us(torch, fn, reps=10, replays=5):
+    """Average device time of one fn() in microseconds: `reps` calls captured back to back on one stream,
+    the graph replayed `replays` times, each replay bracketed by HIP events on the replaying stream."""
+    q = torch.cuda.Stream()
+    with torch.cuda.stream(q):
+        fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=q):
+        for _ in range(reps):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total = 0.0
+    for _ in range(replays):
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        total += e0.elapsed_time(e1)
+    return 1e3 * total / (replays * reps)
+
+
+def hbm_row(us, nbytes, launches):
+    return {"us": round(us, 2), "launches": launches, "algorithmic_bytes": int(nbytes),
+            "gb_per_s": round(nbytes / (us * 1e-6) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (us * 1e-6) / HBM_BYTES_PER_S, 4)}
+
+
+# ------------------------------------------------------------------------------------------------
+# one binarized layer and the calls on it
 class LayerState:
     """Device buffers of one binarized layer, allocated once."""
 
@@ -87,15 +123,26 @@ class LayerState:
         self.macs = L.macs(B)
         nbytes = (dab.lib().dab_binfc_workspace_bytes(B, L.C, L.F) if L.is_fc
                   else dab.lib().dab_binconv2d_workspace_bytes(ctypes.byref(self.desc)))
+        self.ws_bytes = nbytes
         self.ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=dev)
         self.est = dab.estimate_outputs(L.F, dev)
         self.EW = dab.pack_weights_outputs(L.F, W.shape[1], W.shape[2], W.shape[3], dev)
         self.est_ws = torch.empty(max(dab.lib().dab_estimate_workspace_bytes(L.F, self.W2.shape[1]), 1),
                                   dtype=torch.uint8, device=dev)
 
+    # algorithmic bytes of the three stages
+    def pack_bytes(self):
+        return self.X.numel() * 4 + self.A.numel() * 4 + (self.tau.numel() * 4 if self.tau is not None else 0)
+
+    def weight_bytes(self):
+        return self.W.numel() * 4 + self.EW[0].numel() * 4 + 8 * self.L.F
+
+    def product_bytes(self):
+        return self.Y.numel() * 4 + self.A.numel() * 4 + self.EW[0].numel() * 4 + 8 * self.L.F
+
 
 def weight_side(s, dab):
-    """alpha/beta estimation and weight bit packing of one layer (independent of the activations)."""
+    """alpha/beta estimation and weight bit packing of one layer as two calls."""
     est = dab.dab_estimate_alpha_beta(s.W2, out=s.est, ws=s.est_ws)
     dab.dab_pack_weights(s.W, est["thr_val"], est["thr_idx"], est["alpha_is_upper"], out=s.EW)
 
@@ -111,116 +158,84 @@ def product(s, dab):
         dab.dab_binconv2d(s.desc, s.A, s.EW[0], s.est["alpha"], s.est["beta"], out=s.Y, ws=s.ws)
 
 
-def run_layer(s, dab, events=None):
-    """estimate -> pack weights -> pack activations -> binary product, all on the current stream."""
+def run_layer(s, dab):
     weight_side(s, dab)
     activation_side(s, dab)
-    if events is not None:
-        events[0].record()
     product(s, dab)
-    if events is not None:
-        events[1].record()
     return s.Y
 
 
-class Schedule:
-    """One step of all layers over HIP streams of equal (default) priority.
+class GroupedStep:
+    """One step of a set of independent layers through the grouped entry points.
 
-    The weight side of a layer (estimation, weight packing) depends on no activation, so the
-    weight sides run on side streams (the heaviest layer alone, the others dealt out in layer order) while the current
-    stream packs the activations of all layers (every input is resident when the step starts;
-    memory-bound work beside the LDS-bound estimation).  The binary products then go, in layer
-    order, to the current stream and one more (to the one with less product time so far, or
-    alternating when the durations are not given): a product waits for its own layer's weights only
-    (an event per layer), so the weight sides of later layers run beside the products of earlier
-    ones, and with two product streams the prepare kernel of the next layer runs beside the
-    main kernel of this one, whose last workgroups hand their compute units straight to the next
-    main kernel.  A step forks from and joins back into the current stream, so steps never
-    overlap, and the whole step can be captured into one HIP graph.
+    main stream : one launch packs the activations of every layer, then the products in layer order
+    side stream : dab_binarize_weights_multi over the layers with short filters (one launch)
+    side stream : dab_binarize_weights_multi over the layers with long filters (conv6)
+    A product waits for the weight group of its own layer only.  A step forks from and joins back
+    into the current stream, so steps never overlap and the step can be captured into one HIP graph.
     """
 
-    def __init__(self, states, n_side, torch, per_layer=True, n_product=2, product_ms=None):
-        self.torch = torch
-        self.states = states
-        self.side = [torch.cuda.Stream() for _ in range(n_side)]
-        self.extra = [torch.cuda.Stream() for _ in range(max(n_product, 1) - 1)] if n_side > 0 else []
-        # the layer with by far the most weights (conv6) has a side stream to itself; the others are
-        # dealt out in layer order over the remaining side streams, so that their weights become
-        # ready in the order the products need them
-        self.assign = [[] for _ in range(max(n_side, 1))]
-        heavy = max(range(len(states)), key=lambda i: states[i].W2.numel())
-        if n_side >= 2:
-            self.assign[0].append(heavy)
-            rest = [i for i in range(len(states)) if i != heavy]
-            for k, i in enumerate(rest):
-                self.assign[1 + k % (n_side - 1)].append(i)
-        else:
-            self.assign[0] = list(range(len(states)))
-        # products: in layer order, each on the product stream with the least work so far when the
-        # durations of the products are known (the small late layers then run beside a large one
-        # instead of alone at the end), else alternating
-        n_q = 1 + len(self.extra)
-        self.product_on = [i % n_q for i in range(len(states))]
-        if product_ms is not None and n_q > 1:
-            load = [0.0] * n_q
-            for i, ms in enumerate(product_ms):
-                q = min(range(n_q), key=lambda j: load[j])
-                self.product_on[i] = q
-                load[q] += ms
-        self.fork = torch.cuda.Event()
-        self.packed = torch.cuda.Event()
-        self.ready = [torch.cuda.Event() for _ in self.side]
-        self.joined = [torch.cuda.Event() for _ in self.extra]
-        self.layer_ready = [torch.cuda.Event() for _ in states]
-        self.per_layer = per_layer
+    SHORT_MAX_N = 4608
 
-    def step(self, dab):
-        torch, states = self.torch, self.states
-        if not self.side:
-            for s in states:
-                run_layer(s, dab)
-            return
+    def __init__(self, states, dab, torch, one_stream=False):
+        self.states, self.torch, self.dab = states, torch, dab
+        self.pack = dab.pack_jobs([(s.X, s.tau, s.A) for s in states])
+        groups = [[i for i, s in enumerate(states) if s.W2.shape[1] <= self.SHORT_MAX_N],
+                  [i for i, s in enumerate(states) if s.W2.shape[1] > self.SHORT_MAX_N]]
+        self.groups = [g for g in groups if g]
+        self.jobs, self.ws = [], []
+        for g in self.groups:
+            jobs = dab.weight_jobs([dict(W=states[i].W, est=states[i].est, packed=states[i].EW) for i in g])
+            nbytes = dab.lib().dab_binarize_weights_multi_workspace_bytes(jobs, len(jobs))
+            self.jobs.append(jobs)
+            self.ws.append(torch.empty(max(nbytes, 1), dtype=torch.uint8, device=states[0].X.device))
+        self.group_of = {i: k for k, g in enumerate(self.groups) for i in g}
+        self.side = [] if one_stream else [torch.cuda.Stream() for _ in self.groups]
+        self.fork = torch.cuda.Event()
+        self.ready = [torch.cuda.Event() for _ in self.groups]
+        # products whose weights come from the short group first: the long group's estimation is the
+        # longest single piece of the step and runs beside them
+        self.order = sorted(range(len(states)), key=lambda i: (self.group_of[i], i))
+
+    def weights(self, k):
+        self.dab.dab_binarize_weights_multi(self.jobs[k], ws=self.ws[k])
+
+    def pack_all(self):
+        self.dab.dab_pack_activations_multi(self.pack)
+
+    def step(self):
+        torch, dab, states = self.torch, self.dab, self.states
         main = torch.cuda.current_stream()
+        if not self.side:
+            self.pack_all()
+            for k in range(len(self.groups)):
+                self.weights(k)
+            for i in self.order:
+                product(states[i], dab)
+            return
         self.fork.record(main)
-        # the main stream's first kernel is enqueued (and captured) before the side work, so that a
-        # graph launch starts the main chain at once instead of behind the longest weight side
-        activation_side(states[0], dab)
-        for q, idxs, done in zip(self.side, self.assign, self.ready):
+        self.pack_all()
+        for k, q in enumerate(self.side):
             q.wait_event(self.fork)
             with torch.cuda.stream(q):
-                for i in idxs:
-                    weight_side(states[i], dab)
-                    if self.per_layer:
-                        self.layer_ready[i].record(q)
-            done.record(q)
-        for s in states[1:]:
-            activation_side(s, dab)
-        self.packed.record(main)
-        streams = [main] + self.extra
-        for q in self.extra:
-            q.wait_event(self.packed)
-        if not self.per_layer:
-            for q in streams:
-                for done in self.ready:
-                    q.wait_event(done)
-        for i, s in enumerate(states):
-            q = streams[self.product_on[i]]
-            if self.per_layer:
-                q.wait_event(self.layer_ready[i])
-            with torch.cuda.stream(q):
-                product(s, dab)
-        for q, done in zip(self.extra, self.joined):
-            done.record(q)
-            main.wait_event(done)
-        for done in self.ready:
-            main.wait_event(done)
+                self.weights(k)
+                self.ready[k].record(q)
+        waited = set()
+        for i in self.order:
+            k = self.group_of[i]
+            if k not in waited:
+                main.wait_event(self.ready[k])
+                waited.add(k)
+            product(states[i], dab)
+        for k in range(len(self.groups)):
+            if k not in waited:
+                main.wait_event(self.ready[k])
 
-    def capture(self, dab):
-        """The step as one HIP graph (kernel launches and stream dependencies only)."""
+    def capture(self):
         torch = self.torch
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
-            self.step(dab)
+            self.step()
         return graph
 
 
@@ -229,10 +244,10 @@ class FusedChain:
     (3/2 max-pooling as an OR on the bits after conv2 and conv5), so between conv2 and fc7 no fp32
     activation is written or read.  conv2 packs its fp32 input as in the plain step and fc7 writes
     fp32.  Thresholds of the hand-over are the per-channel means the plain step uses.  The weight
-    sides run on the side streams of the schedule it is given (bench.py: one, in layer order)."""
+    sides are the two grouped calls of the plain step on its side streams."""
 
-    def __init__(self, states, sched, dab, torch):
-        self.states, self.sched, self.torch = states, sched, torch
+    def __init__(self, states, grouped, dab, torch):
+        self.states, self.grouped, self.torch = states, grouped, torch
         self.bits = []
         for s in states:
             L = s.L
@@ -246,37 +261,49 @@ class FusedChain:
                                      dtype=torch.int32, device=s.X.device)
             self.bits.append((out, pooled))
 
-    def step(self, dab, events=None):
-        torch, states, sched = self.torch, self.states, self.sched
+    def product(self, i, A, dab):
+        """Layer i on packed input A; returns the packed input of the next layer."""
+        s = self.states[i]
+        if s.desc is None:
+            dab.dab_binfc(A.view(s.B, -1), s.EW[0], s.est["alpha"], s.est["beta"], s.L.C, out=s.Y, ws=s.ws)
+            return None
+        out, pooled = self.bits[i]
+        dab.dab_binconv2d_bits(s.desc, A, s.EW[0], s.est["alpha"], s.est["beta"], self.states[i + 1].tau, out=out,
+                               ws=s.ws)
+        if pooled is None:
+            return out
+        dab.dab_pool_bits(out, s.L.F, 3, 3, 2, 2, out=pooled)
+        return pooled
+
+    def inputs(self, dab):
+        """The packed input of every layer of the chain (for timing one layer alone)."""
+        A, res = self.states[0].A, []
+        for i in range(len(self.states)):
+            res.append(A)
+            A = self.product(i, A, dab)
+        return res
+
+    def step(self, dab):
+        torch, states, g = self.torch, self.states, self.grouped
         main = torch.cuda.current_stream()
-        sched.fork.record(main)
+        g.fork.record(main)
         activation_side(states[0], dab)
-        for q, idxs, done in zip(sched.side, sched.assign, sched.ready):
-            q.wait_event(sched.fork)
+        for k, q in enumerate(g.side):
+            q.wait_event(g.fork)
             with torch.cuda.stream(q):
-                for i in idxs:
-                    weight_side(states[i], dab)
-                    sched.layer_ready[i].record(q)
-            done.record(q)
+                g.weights(k)
+                g.ready[k].record(q)
+        if not g.side:
+            for k in range(len(g.groups)):
+                g.weights(k)
         A = states[0].A
-        for i, s in enumerate(states):
-            main.wait_event(sched.layer_ready[i])
-            if events is not None:
-                events[i][0].record()
-            if s.desc is None:
-                dab.dab_binfc(A.view(s.B, -1), s.EW[0], s.est["alpha"], s.est["beta"], s.L.C, out=s.Y, ws=s.ws)
-            else:
-                out, pooled = self.bits[i]
-                dab.dab_binconv2d_bits(s.desc, A, s.EW[0], s.est["alpha"], s.est["beta"], states[i + 1].tau, out=out,
-                                       ws=s.ws)
-                A = out
-                if pooled is not None:
-                    dab.dab_pool_bits(out, s.L.F, 3, 3, 2, 2, out=pooled)
-                    A = pooled
-            if events is not None:
-                events[i][1].record()
-        for done in sched.ready:
-            main.wait_event(done)
+        waited = set()
+        for i in range(len(states)):
+            k = g.group_of[i]
+            if g.side and k not in waited:
+                main.wait_event(g.ready[k])
+                waited.add(k)
+            A = self.product(i, A, dab)
 
     def capture(self, dab):
         torch = self.torch
@@ -308,6 +335,112 @@ def build_states(batch, dab, torch, wl):
         x = y
     torch.cuda.synchronize()
     return states
+
+
+def time_graph(torch, graph, steps, warmup):
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+# ------------------------------------------------------------------------------------------------
+# measurements beside the headline
+def stage_table(states, grouped, dab, torch):
+    """Every stage of the step alone on the chip, against the HBM roofline (algorithmic bytes: what the
+    stage must read and write once)."""
+    rows = {}
+    rows["pack_activations: all layers, one launch"] = hbm_row(
+        device_us(torch, grouped.pack_all), sum(s.pack_bytes() for s in states), 1)
+    for k, g in enumerate(grouped.groups):
+        names = "+".join(states[i].L.name for i in g)
+        rows[f"estimate + pack_weights: {names}, one grouped call"] = hbm_row(
+            device_us(torch, lambda k=k: grouped.weights(k)), sum(states[i].weight_bytes() for i in g), None)
+    for s in states:
+        rows[f"pack_activations: {s.L.name}"] = hbm_row(device_us(torch, lambda s=s: activation_side(s, dab)),
+                                                        s.pack_bytes(), 1)
+        rows[f"estimate: {s.L.name}"] = hbm_row(
+            device_us(torch, lambda s=s: dab.dab_estimate_alpha_beta(s.W2, out=s.est, ws=s.est_ws)),
+            s.W.numel() * 4 + 24 * s.L.F, None)
+        rows[f"pack_weights: {s.L.name}"] = hbm_row(
+            device_us(torch, lambda s=s: dab.dab_pack_weights(s.W, s.est["thr_val"], s.est["thr_idx"],
+                                                              s.est["alpha_is_upper"], out=s.EW)),
+            s.W.numel() * 4 + s.EW[0].numel() * 4 + 9 * s.L.F, 1)
+    return rows
+
+
+def product_rows(states, dab, torch):
+    rows = {}
+    for s in states:
+        us = device_us(torch, lambda s=s: product(s, dab))
+        r = hbm_row(us, s.product_bytes(), 1 if s.ws_bytes == 0 else None)
+        r.update({"ms": round(us * 1e-3, 5), "gmacs": round(s.macs / 1e9, 3),
+                  "tflops": round(2 * s.macs / (us * 1e-6) / 1e12, 1),
+                  "frac_of_mfma_fp4_peak": round(2 * s.macs / (us * 1e-6) / MFMA_FP4_FLOPS, 4)})
+        rows[s.L.name] = r
+    return rows
+
+
+def popcount_ceiling(dab, torch):
+    """P_bcnt and P_pair of the vector-ALU form of the product (Section 3.2) from the measured issue rate
+    of the popcount instruction and the shader clock sustained under that load."""
+    grid, iters = 256 * 16, 512
+    out = torch.empty(grid * 256, dtype=torch.int32, device="cuda:0")
+    clocks = torch.zeros(grid * 2, dtype=torch.int64, device="cuda:0")
+    res = {}
+    for pair, key in ((0, "bcnt"), (1, "and_bcnt_pair")):
+        ops, khz = dab.dab_probe_popcount(pair, iters, grid, out, clocks)
+        us = device_us(torch, lambda pair=pair: dab.dab_probe_popcount(pair, iters, grid, out, clocks), reps=4)
+        c = clocks.view(grid, 2).double()
+        mhz = float((c[:, 0] / c[:, 1]).median()) * khz / 1e3
+        res[key] = {"lane_ops_per_s": ops / (us * 1e-6), "sustained_shader_mhz": round(mhz, 1)}
+    rate = res["bcnt"]["lane_ops_per_s"]
+    pair_rate = res["and_bcnt_pair"]["lane_ops_per_s"]
+    return {"spec": {"P_bcnt": P_BCNT_SPEC, "P_pair": P_PAIR_SPEC, "clock_mhz": 2400},
+            "measured": {"P_bcnt": rate * 32, "P_pair": pair_rate * 32,
+                         "popcounts_per_lane_per_clock": round(rate / (256 * 64 * res["bcnt"]["sustained_shader_mhz"] * 1e6), 3),
+                         "sustained_shader_mhz": res["bcnt"]["sustained_shader_mhz"],
+                         "sustained_shader_mhz_pair": res["and_bcnt_pair"]["sustained_shader_mhz"]},
+            "what": "P_bcnt = lane-popcounts/s x 32 MACs; P_pair = AND+popcount pairs/s x 32 MACs (spec: half of P_bcnt); "
+                    "measured with %d workgroups x 256 lanes x %d x 64 back-to-back instructions" % (grid, iters)}
+
+
+def other_configs(dab, torch, wl):
+    """Per-call device times of the other workload configurations of the benchmark spec (2: one Sketch-A-Net
+    conv2 at batch 128; 4: the four ResNet-18-style 3x3 stages at batch 64; 5: the two wide
+    fully-connected layers at batch 1024).  Every stage alone on the chip."""
+    dev = torch.device("cuda:0")
+    cases = [("config2", wl.config2(128))]
+    cases += [(f"config4/{wl.CFG4_LAYERS[i].name}", wl.config4(i, 64)) for i in range(4)]
+    cases += [(f"config5/{wl.CFG5_LAYERS[i].name}", wl.config5(i, 1024)) for i in range(2)]
+    res = {}
+    for name, (L, x, w) in cases:
+        if L.is_fc:
+            X = torch.from_numpy(x).to(dev)
+        else:
+            X = torch.from_numpy(wl.nchw_to_nhwc(x)).to(dev)
+        s = LayerState(L, torch.from_numpy(w).to(dev), X, None, dab, torch)
+        jobs = dab.weight_jobs([dict(W=s.W, est=s.est, packed=s.EW)])
+        wsb = dab.lib().dab_binarize_weights_multi_workspace_bytes(jobs, 1)
+        wws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=dev)
+        rows = {"pack_activations": hbm_row(device_us(torch, lambda: activation_side(s, dab)), s.pack_bytes(), 1),
+                "estimate + pack_weights (grouped call)": hbm_row(
+                    device_us(torch, lambda: dab.dab_binarize_weights_multi(jobs, ws=wws)), s.weight_bytes(), None)}
+        us = device_us(torch, lambda: product(s, dab))
+        r = hbm_row(us, s.product_bytes(), 1 if s.ws_bytes == 0 else None)
+        r.update({"gmacs": round(s.macs / 1e9, 3), "tflops": round(2 * s.macs / (us * 1e-6) / 1e12, 1),
+                  "frac_of_mfma_fp4_peak": round(2 * s.macs / (us * 1e-6) / MFMA_FP4_FLOPS, 4),
+                  "vs_P_pair_spec": round(s.macs / (us * 1e-6) / P_PAIR_SPEC, 3)})
+        rows["binary product"] = r
+        rows["sum_us"] = round(sum(v["us"] for v in rows.values() if isinstance(v, dict)), 2)
+        res[name] = rows
+        del s, X, jobs, wws
+        torch.cuda.empty_cache()
+    return res
 
 
 def training_weight_side(states, dab, torch, args):
@@ -355,20 +488,13 @@ def training_weight_side(states, dab, torch, args):
         for done in joined:
             main.wait_event(done)
 
-    for _ in range(args.warmup):
+    for _ in range(min(args.warmup, 3)):
         step()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
         step()
-    for _ in range(args.warmup):
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        graph.replay()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt = time_graph(torch, graph, args.steps, args.warmup)
     weights = sum(s.W.numel() for s in states)
     nbytes = weights * 4 * 9 + sum(s.EW[0].numel() * 4 for s in states)
     # leave the plain step's packed weights as they were
@@ -381,17 +507,16 @@ def training_weight_side(states, dab, torch, args):
             "gb_per_s": round(nbytes / (dt / args.steps) / 1e9, 1)}
 
 
-def weights_only_products(states, dab, torch, args):
+def weights_only_products(states, dab, torch):
     """The six layers as weights-only binarized layers (WBin of Section 5.1) on their real-valued inputs,
-    one call after the other on one stream: HIP events around each dab_wbin_conv2d / dab_wbin_fc.
-    Each input element becomes three bf16 pieces, so a binary MAC costs three bf16 MACs (6 FLOP)."""
-    import ctypes as ct
+    each call alone on the chip.  Each input element becomes three bf16 pieces, so a binary MAC costs
+    three bf16 MACs (6 FLOP)."""
     out = {}
-    total_ms, total_macs = 0.0, 0
+    total_us, total_macs = 0.0, 0
     for s in states:
         L = s.L
         nbytes = (dab.lib().dab_wbin_fc_workspace_bytes(s.B, L.C, L.F) if L.is_fc
-                  else dab.lib().dab_wbin_conv2d_workspace_bytes(ct.byref(s.desc)))
+                  else dab.lib().dab_wbin_conv2d_workspace_bytes(ctypes.byref(s.desc)))
         ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=s.X.device)
         Y = torch.empty_like(s.Y)
 
@@ -401,65 +526,86 @@ def weights_only_products(states, dab, torch, args):
             else:
                 dab.dab_wbin_conv2d(s.desc, s.X, s.EW[0], s.est["alpha"], s.est["beta"], out=Y, ws=ws)
 
-        for _ in range(args.warmup):
-            run()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = max(1, min(args.steps, 20))
-        e0.record()
-        for _ in range(reps):
-            run()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        total_ms += ms
+        us = device_us(torch, run, reps=5)
+        total_us += us
         total_macs += s.macs
-        out[L.name] = {"ms": round(ms, 4), "bf16_tflops": round(6 * s.macs / (ms * 1e-3) / 1e12, 1),
-                       "frac_of_mfma_bf16_peak": round(6 * s.macs / (ms * 1e-3) / MFMA_BF16_FLOPS, 4)}
+        out[L.name] = {"ms": round(us * 1e-3, 4), "bf16_tflops": round(6 * s.macs / (us * 1e-6) / 1e12, 1),
+                       "frac_of_mfma_bf16_peak": round(6 * s.macs / (us * 1e-6) / MFMA_BF16_FLOPS, 4)}
         del ws, Y
     return {"what": "dab_wbin_conv2d / dab_wbin_fc (prepare + product) per layer, fp32 inputs as three bf16 pieces, "
-                    "one stream",
-            "ms_per_step": round(total_ms, 4), "macs_per_s": total_macs / (total_ms * 1e-3), "per_layer": out}
+                    "each call alone on the chip",
+            "ms_per_step": round(total_us * 1e-3, 4), "macs_per_s": total_macs / (total_us * 1e-6), "per_layer": out}
 
 
 def cpu_oracle_baseline(batch, wl):
-    """The float64 CPU oracle, as it stands, on a small slice of the same workload."""
+    """The float64 CPU oracle, as it stands, on the same workload: all six layers incl. estimation.
+    Timed twice: with the host's default thread count, then (one pass over a smaller batch) on one thread."""
     import numpy as np
     import torch
     from oracle import estimate as oest
     from oracle import layers as olay
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
+        threadpool_limits = None
         threads = os.cpu_count() or 1
-    imgs = wl.sketch_images(batch)
     w1, ws = wl.config3_weights()
-    x0 = wl.config3_conv1_features(imgs, w1).numpy()
-    macs = 0
-    passes = 3                                                   # about a dozen seconds on the GPU box's host cores
-    t0 = time.perf_counter()
-    for _ in range(passes):
-        x = x0
-        for L, W in zip(wl.CFG3_LAYERS, ws):
-            if L.is_fc:
-                x = x.reshape(batch, -1)
-            x4 = x if x.ndim == 4 else x[:, :, None, None]
-            tau = x4.mean(axis=(0, 2, 3)).astype(np.float32)
-            r = oest.estimate_alpha_beta(W)
-            a = olay.binarize_activations(x4, tau)
-            y = olay.conv2d(a, olay.two_valued_filters(r["e"], r["alpha"], r["beta"]), (L.pad, L.pad),
-                            (L.stride, L.stride))
-            macs += L.macs(batch)
-            y = torch.from_numpy(y.astype(np.float32)).permute(0, 3, 1, 2)
-            if L.pool_after:
-                y = torch.nn.functional.max_pool2d(y, 3, 2)
-            x = y.numpy()
-    dt = time.perf_counter() - t0
-    return {"value": macs / dt, "unit": "binary MAC/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"config 3, all six layers incl. alpha/beta estimation, batch {batch} of 256, {passes} passes, {dt:.1f} s"}
+
+    def run(n, passes):
+        imgs = wl.sketch_images(n)
+        x0 = wl.config3_conv1_features(imgs, w1).numpy()
+        macs = 0
+        t0 = time.perf_counter()
+        for _ in range(passes):
+            x = x0
+            for L, W in zip(wl.CFG3_LAYERS, ws):
+                if L.is_fc:
+                    x = x.reshape(n, -1)
+                x4 = x if x.ndim == 4 else x[:, :, None, None]
+                tau = x4.mean(axis=(0, 2, 3)).astype(np.float32)
+                r = oest.estimate_alpha_beta(W)
+                a = olay.binarize_activations(x4, tau)
+                y = olay.conv2d(a, olay.two_valued_filters(r["e"], r["alpha"], r["beta"]), (L.pad, L.pad),
+                                (L.stride, L.stride))
+                macs += L.macs(n)
+                y = torch.from_numpy(y.astype(np.float32)).permute(0, 3, 1, 2)
+                if L.pool_after:
+                    y = torch.nn.functional.max_pool2d(y, 3, 2)
+                x = y.numpy()
+        return macs, time.perf_counter() - t0
+
+    passes = 2
+    macs, dt = run(batch, passes)
+    res = {"value": macs / dt, "unit": "binary MAC/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"config 3, all six layers incl. alpha/beta estimation, batch {batch} of 256, {passes} passes, {dt:.1f} s"}
+    if threadpool_limits is not None:
+        n1 = max(1, batch // 16)
+        old = torch.get_num_threads()
+        torch.set_num_threads(1)
+        try:
+            with threadpool_limits(limits=1):
+                macs1, dt1 = run(n1, 1)
+        finally:
+            torch.set_num_threads(old)
+        res["single_thread"] = {"value": macs1 / dt1, "cores": 1,
+                                "sample": f"same path, batch {n1}, one pass, {dt1:.1f} s"}
+    return res
 
 
+def load_traffic(layer, batch):
+    """HBM bytes per launch of the dominant kernel from the tracked counter summary, or None."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None, None
+    if t.get("layer") != layer or t.get("batch") != batch:
+        return None, None
+    return t.get("traffic_bytes"), {k: t.get(k) for k in ("commit", "kernel", "fetch_bytes", "write_bytes", "source")}
+
+
+# ------------------------------------------------------------------------------------------------
 def main():
     args = parse()
     if args.gpus != 1:
@@ -475,6 +621,7 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    dab.dab_init()
 
     states = build_states(args.batch, dab, torch, wl)
     total_macs = sum(s.macs for s in states)
@@ -485,34 +632,15 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    # Kernel timing pass: every layer launched eagerly on one stream with a HIP event pair around its
-    # binary product (events cannot be recorded inside a captured graph on this platform, and with
-    # several streams the eager launches are host-bound, which would put launch gaps between the
-    # product's kernels).  In the schedule the products have the chip to themselves, as they do here.
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in states]
-          for _ in range(args.steps)]
-    torch.cuda.synchronize()
+    grouped = GroupedStep(states, dab, torch, one_stream=args.one_stream)
     for _ in range(min(args.warmup, 3)):
-        for s in states:
-            run_layer(s, dab)
-    for k in range(args.steps):
-        for s, e in zip(states, ev[k]):
-            run_layer(s, dab, e)
-    torch.cuda.synchronize()
-    product_ms = [sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
-                  for i in range(len(states))]
-
-    sched = Schedule(states, args.side_streams, torch, per_layer=not args.wait_all, n_product=args.product_streams,
-                     product_ms=product_ms)
-    for _ in range(args.warmup):
-        sched.step(dab)
+        grouped.step()
     torch.cuda.synchronize()
 
-    # The schedule launched eagerly (host-bound with side streams; reported for comparison)
+    # The step launched eagerly (host-bound: the host needs longer to enqueue a step than the chip to run it)
     t0 = time.perf_counter()
     for k in range(args.steps):
-        sched.step(dab)
-    t_enqueued = time.perf_counter() - t0
+        grouped.step()
     torch.cuda.synchronize()
     dt_eager = time.perf_counter() - t0
 
@@ -520,91 +648,78 @@ def main():
     if args.no_graph:
         dt = dt_eager
     else:
-        graph = sched.capture(dab)
-        for _ in range(args.warmup):
-            graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        graph = grouped.capture()
+        dt = time_graph(torch, graph, args.steps, args.warmup)
 
     ms_per_step = 1e3 * dt / args.steps
     value = total_macs * args.steps / dt
-    # binary product: per layer and aggregate, from the events of the kernel timing pass.  With fp32
-    # outputs every large layer sits below the ridge of the fp4 matrix cores (conv2: 784 FLOP per
-    # algorithmic byte against 10.1e15 / 8e12 = 1262), so the bound that applies is HBM; the MFMA view
-    # is printed beside it.  Algorithmic bytes of a call = fp32 outputs + activation bits + weight bits
-    # + alpha and beta.
-    per_layer = {}
-    conv_ms = 0.0
-    algo_bytes = 0
-    for i, s in enumerate(states):
-        ms = product_ms[i]
-        conv_ms += ms
-        nbytes = s.Y.numel() * 4 + s.A.numel() * 4 + s.EW[0].numel() * 4 + 8 * s.L.F
-        algo_bytes += nbytes
-        per_layer[s.L.name] = {"ms": round(ms, 4), "gmacs": round(s.macs / 1e9, 3),
-                               "algorithmic_bytes": nbytes,
-                               "gb_per_s": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                               "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / HBM_BYTES_PER_S, 4),
-                               "tflops": round(2 * s.macs / (ms * 1e-3) / 1e12, 1),
-                               "frac_of_mfma_fp4_peak": round(2 * s.macs / (ms * 1e-3) / MFMA_FP4_FLOPS, 4)}
-    dom = max(per_layer, key=lambda k: per_layer[k]["ms"])         # the dominant call (conv2 at batch 256)
+
+    # Roofline of the dominant kernel: the binary product of the layer with the longest launch.  With
+    # fp32 outputs every large layer sits below the ridge of the fp4 matrix cores (conv2: 784 FLOP per
+    # algorithmic byte against 10.1e15 / 8e12 = 1262), so the bound that applies is HBM; the MFMA view is
+    # printed beside it.  Algorithmic bytes of a launch = fp32 outputs + activation bits + weight bits +
+    # alpha and beta.
+    per_layer = product_rows(states, dab, torch)
+    conv_us = sum(r["us"] for r in per_layer.values())
+    algo_bytes = sum(r["algorithmic_bytes"] for r in per_layer.values())
+    dom = max(per_layer, key=lambda k: per_layer[k]["us"])
     d = per_layer[dom]
-    traffic = CONV2_CALL_HBM_BYTES if (dom == "conv2" and args.batch == 256) else None
+    traffic, traffic_src = load_traffic(dom, args.batch)
     roofline = {"bound": "hbm",
-                "kernel": "dab_binconv2d of %s: binconv_prepare_kernel + binconv_mfma_kernel, bracketed by HIP events "
-                          "on the launch stream" % dom,
+                "kernel": "binconv_direct_kernel (the one launch of dab_binconv2d) of %s; average over graphs of 10 "
+                          "back-to-back launches on one stream, each replay bracketed by HIP events on that stream" % dom,
                 "achieved": d["gb_per_s"], "peak": HBM_BYTES_PER_S / 1e9, "unit": "GB/s",
-                "frac": d["frac_of_hbm_peak"], "traffic": traffic,
+                "frac": d["frac_of_hbm_peak"], "traffic": traffic, "traffic_source": traffic_src,
                 "algorithmic_bytes": d["algorithmic_bytes"], "launch_ms": d["ms"],
                 "mfma_view": {"achieved": d["tflops"], "peak": MFMA_FP4_FLOPS / 1e12, "unit": "TFLOP/s",
                               "frac": d["frac_of_mfma_fp4_peak"]},
-                "all_layers": {"kernel_ms_per_step": round(conv_ms, 4), "algorithmic_bytes": algo_bytes,
-                               "gb_per_s": round(algo_bytes / (conv_ms * 1e-3) / 1e9, 1),
-                               "frac_of_hbm_peak": round(algo_bytes / (conv_ms * 1e-3) / HBM_BYTES_PER_S, 4),
-                               "tflops": round(2 * total_macs / (conv_ms * 1e-3) / 1e12, 1),
-                               "frac_of_mfma_fp4_peak": round(2 * total_macs / (conv_ms * 1e-3) / MFMA_FP4_FLOPS, 4),
-                               "binary_macs_per_s": total_macs / (conv_ms * 1e-3),
-                               "vs_valu_popcount_peak": round(total_macs / (conv_ms * 1e-3) / VALU_PAIR_MACS, 3)},
-                "kernel_ms_per_step": round(conv_ms, 4),
+                "all_layers": {"kernel_ms_per_step": round(conv_us * 1e-3, 4), "algorithmic_bytes": algo_bytes,
+                               "gb_per_s": round(algo_bytes / (conv_us * 1e-6) / 1e9, 1),
+                               "frac_of_hbm_peak": round(algo_bytes / (conv_us * 1e-6) / HBM_BYTES_PER_S, 4),
+                               "tflops": round(2 * total_macs / (conv_us * 1e-6) / 1e12, 1),
+                               "frac_of_mfma_fp4_peak": round(2 * total_macs / (conv_us * 1e-6) / MFMA_FP4_FLOPS, 4),
+                               "binary_macs_per_s": total_macs / (conv_us * 1e-6)},
                 "per_layer": per_layer}
 
-    # The next row of the scope table, measured beside the headline: the fused chain
-    fused = None
-    if args.side_streams > 0 and not args.no_fused:
-        # its products form one dependent chain, so one side stream (weight sides in layer order) delivers
-        # every layer's weights in time, and every further branch of the graph only costs launch overhead
-        chain = FusedChain(states, Schedule(states, 1, torch), dab, torch)
-        for _ in range(args.warmup):
-            chain.step(dab)
-        torch.cuda.synchronize()
-        fev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in states]
-               for _ in range(args.steps)]
-        for k in range(args.steps):
-            chain.step(dab, fev[k])
-        torch.cuda.synchronize()
-        fgraph = chain.capture(dab)
-        for _ in range(args.warmup):
-            fgraph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            fgraph.replay()
-        torch.cuda.synchronize()
-        fdt = time.perf_counter() - t0
-        fused = {"what": "same layers, bits handed from layer to layer by dab_binconv2d_bits / dab_pool_bits "
-                         "(fp32 only into conv2 and out of fc7); one HIP graph per step",
-                 "ms_per_step": round(1e3 * fdt / args.steps, 4),
-                 "binary_macs_per_s": total_macs * args.steps / fdt,
-                 "product_ms_per_layer": {s.L.name: round(sum(fev[k][i][0].elapsed_time(fev[k][i][1])
-                                                              for k in range(args.steps)) / args.steps, 4)
-                                          for i, s in enumerate(states)}}
+    extras = {}
+    if not args.headline_only:
+        pc = popcount_ceiling(dab, torch)
+        rate = total_macs / (conv_us * 1e-6)
+        pc["products_alone"] = {"vs_P_pair_spec": round(rate / P_PAIR_SPEC, 3), "vs_P_bcnt_spec": round(rate / P_BCNT_SPEC, 3),
+                                "vs_P_pair_measured": round(rate / pc["measured"]["P_pair"], 3),
+                                "vs_P_bcnt_measured": round(rate / pc["measured"]["P_bcnt"], 3)}
+        pc["whole_step"] = {"vs_P_pair_spec": round(value / P_PAIR_SPEC, 3), "vs_P_bcnt_spec": round(value / P_BCNT_SPEC, 3),
+                            "vs_P_pair_measured": round(value / pc["measured"]["P_pair"], 3),
+                            "vs_P_bcnt_measured": round(value / pc["measured"]["P_bcnt"], 3)}
+        extras["valu_popcount_ceiling"] = pc
+        extras["stages"] = stage_table(states, grouped, dab, torch)
 
-    training = None if args.no_fused else training_weight_side(states, dab, torch, args)
-    wbin = None if args.no_fused else weights_only_products(states, dab, torch, args)
+        # the next row of the scope table: the chain that hands bits from layer to layer
+        chain = FusedChain(states, grouped, dab, torch)
+        chain.step(dab)
+        torch.cuda.synchronize()
+        fdt = time_graph(torch, chain.capture(dab), args.steps, args.warmup)
+        ins = chain.inputs(dab)
+        extras["rebinarized_chain"] = {
+            "what": "same layers, bits handed from layer to layer by dab_binconv2d_bits / dab_pool_bits "
+                    "(fp32 only into conv2 and out of fc7); one HIP graph per step",
+            "ms_per_step": round(1e3 * fdt / args.steps, 4), "binary_macs_per_s": total_macs * args.steps / fdt,
+            "product_us_per_layer": {s.L.name: round(device_us(torch, lambda i=i: chain.product(i, ins[i], dab)), 2)
+                                     for i, s in enumerate(states)}}
+        for s in states:                                          # the chain's fc7 wrote Y from the chain's bits
+            product(s, dab)
+        extras["training_weight_side"] = training_weight_side(states, dab, torch, args)
+        extras["weights_only_layers"] = weights_only_products(states, dab, torch)
+        extras["other_configs"] = other_configs(dab, torch, wl)
+        if args.batch != 32:
+            small = build_states(32, dab, torch, wl)
+            g32 = GroupedStep(small, dab, torch)
+            g32.step()
+            torch.cuda.synchronize()
+            dt32 = time_graph(torch, g32.capture(), args.steps, args.warmup)
+            extras["batch_32"] = {"ms_per_step": round(1e3 * dt32 / args.steps, 4),
+                                  "binary_macs_per_s": sum(s.macs for s in small) * args.steps / dt32}
+
     cpu = cpu_oracle_baseline(args.cpu_batch, wl) if args.cpu_batch > 0 else None
     line = {
         "metric": "effective binary MACs/s on Sketch-A-Net binarized layers",
@@ -614,14 +729,13 @@ def main():
         "config": {"workload": "config 3: Sketch-A-Net binarized trunk (conv2-conv6, fc7), batch %d, "
                                "estimate + pack weights + pack activations + binary product per layer" % args.batch,
                    "batch": args.batch, "binary_macs_per_step": total_macs,
-                   "streams": 1 + args.side_streams + (max(args.product_streams, 1) - 1 if args.side_streams else 0),
+                   "streams": 1 + len(grouped.side),
                    "launch": "eager" if args.no_graph else "one captured HIP graph per step",
-                   "product_stream_of_layer": sched.product_on,
-                   "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4),
-                   "eager_host_enqueue_ms_per_step": round(1e3 * t_enqueued / args.steps, 4)},
-        "roofline": roofline, "cpu_baseline": cpu, "rebinarized_chain": fused,
-        "training_weight_side": training, "weights_only_layers": wbin,
+                   "calls_per_step": 1 + len(grouped.groups) + len(states),
+                   "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4)},
+        "roofline": roofline, "cpu_baseline": cpu,
     }
+    line.update(extras)
     print(json.dumps(line))
 
 

@@ -208,7 +208,8 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
                      uint32_t* E_packed, uint32_t* ecnt, void* stream);
 
 /*
- * dab_binarize_weights_multi - the whole weight side of several layers in two or three launches:
+ * dab_binarize_weights_multi - the whole weight side of several layers in a few launches (one per
+ * class of row length present: up to 2304 weights, up to 4608, longer; plus one behind the longer rows):
  * for every job, dab_estimate_alpha_beta (or, with K_prev, dab_estimate_alpha_beta_bounded) of its
  * filters followed by dab_pack_weights of the resulting masks.  Section 4.3.1 handles all filters of
  * a layer together; filters of different layers are just as independent, so they share the
@@ -220,11 +221,11 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
  *             device pointer with the meaning it has in dab_estimate_alpha_beta / dab_pack_weights.
  *             E_packed and ecnt may both be NULL (estimation only); K_prev and alpha_is_upper_prev
  *             may both be NULL (unrestricted search), else max_change >= 0 bounds the split's move.
- *   ws        scratch of dab_binarize_weights_multi_workspace_bytes(jobs, n_jobs) bytes (one flag per
- *             filter of the jobs with long rows; 0 when every row has at most 4608 weights)
+ *   ws        scratch of dab_binarize_weights_multi_workspace_bytes(jobs, n_jobs) bytes, 8-byte aligned
+ *             (one flag per filter of the jobs with long rows; 0 when every row has at most 4608 weights)
  * Errors: per job as in the separate calls (rows above dab_estimate_max_n(), more than 128 taps with
  * packing -> DAB_ERR_UNSUPPORTED); more than 16 jobs -> DAB_ERR_UNSUPPORTED; ws missing or too
- * small -> DAB_ERR_WORKSPACE.
+ * small -> DAB_ERR_WORKSPACE; ws not 8-byte aligned -> DAB_ERR_ALIGN.
  */
 typedef struct dab_weight_job {
     const float* W;                       /* [F][C][kh][kw] fp32 */

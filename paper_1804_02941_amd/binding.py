@@ -47,6 +47,8 @@ _SIGNATURES = {
     "dab_strerror": (c_char_p, [c_int]),
     "dab_last_hip_error": (c_int, []),
     "dab_init": (c_int, []),
+    "dab_probe_popcount": (c_int, [c_int, c_int, c_int, c_void_p, c_void_p, ctypes.POINTER(ctypes.c_int64),
+                                   ctypes.POINTER(c_int32), c_void_p]),
     "dab_estimate_alpha_beta": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_estimate_alpha_beta_bounded": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, c_void_p,
@@ -228,6 +230,20 @@ def dab_pack_activations(X, layout=DAB_LAYOUT_NHWC, tau=None, out=None):
         _ptr(X, torch.float32, "X"), layout, B, C, H, W, _ptr(tau, torch.float32, "tau"),
         _ptr(A, torch.int32, "A_packed"), _stream()))
     return A
+
+
+def dab_init():
+    """One-time set-up of the current device (every entry point does it on first use as well)."""
+    _check("dab_init", lib().dab_init())
+
+
+def dab_probe_popcount(pair, iters, grid, out, clocks):
+    """One launch of the popcount-rate probe; returns (lane-popcounts issued, constant-rate clock in kHz)."""
+    ops, khz = ctypes.c_int64(0), c_int32(0)
+    _check("dab_probe_popcount", lib().dab_probe_popcount(
+        int(bool(pair)), iters, grid, _ptr(out, torch.int32, "out"), _ptr(clocks, torch.int64, "clocks"),
+        ctypes.byref(ops), ctypes.byref(khz), _stream()))
+    return ops.value, khz.value
 
 
 class dab_weight_job(ctypes.Structure):

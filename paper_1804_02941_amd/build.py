@@ -15,7 +15,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdab_hip.so")
-SOURCES = ("api.hip", "binconv.hip", "direct.hip", "pack.hip", "estimate.hip", "training.hip")
+SOURCES = ("api.hip", "binconv.hip", "direct.hip", "pack.hip", "estimate.hip", "training.hip", "probe.hip")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

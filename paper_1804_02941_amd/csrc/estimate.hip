@@ -354,14 +354,22 @@ __global__ __launch_bounds__(THREADS) void estimate_kernel(const float* __restri
 // which is exact for every element within 2^-24 of the row's largest magnitude (smaller ones are
 // rounded at 2^-49 of it), and integer atomics make the result independent of their order.
 constexpr int kFastBigBucket = 96;      // buckets above this size are candidates without a bound
+constexpr int kMaxCandBuckets = 255;    // candidate buckets of a row (more: the row is left to the sort)
 
-// THREADS threads with up to ITEMS elements each, NB value buckets, at most CAP candidate elements.
-// The row is read once, every load in flight at once, and stays in registers (element j of thread t
-// is row[t + j * THREADS]); little LDS is needed and several workgroups share a compute unit:
+// The row is read once, every load in flight at once, and stays in registers: element j of thread t
+// is row[t + j * THREADS] (positions past the end repeat the last element).
+template <int THREADS, int ITEMS>
+__device__ __forceinline__ void load_row(const float* __restrict__ row, int n, float (&x)[ITEMS]) {
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) x[j] = row[min(static_cast<int>(threadIdx.x) + j * THREADS, n - 1)];
+}
+
+// THREADS threads with up to ITEMS elements each (as load_row leaves them), NB value buckets, at most
+// CAP candidate elements.  Little LDS is needed and several workgroups share a compute unit:
 // every phase is a short latency chain between barriers.  The result says whether the row is done
 // (the same for every thread of the workgroup); nothing has been written when it is not.
 template <int THREADS, int ITEMS, int NB, int CAP>
-__device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, int f, float* __restrict__ alpha,
+__device__ __forceinline__ bool bucket_row(const float (&x)[ITEMS], int n, int f, float* __restrict__ alpha,
                                            float* __restrict__ beta, int32_t* Kout, float* __restrict__ thr_val,
                                            int32_t* __restrict__ thr_idx, uint8_t* alpha_is_upper, const int32_t* K_prev,
                                            const uint8_t* upper_prev, int max_change, SplitInfo* info = nullptr) {
@@ -369,23 +377,21 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
     constexpr int BPT = NB / THREADS;                              // buckets per thread
     __shared__ uint32_t cnt[NB + 1];                               // counts, then the exclusive prefix N_b (N_NB = n)
     __shared__ unsigned long long sum[NB + 1];                     // fixed-point sums, then the exclusive prefix S_b
-    __shared__ uint8_t cand[NB];
+    __shared__ uint8_t cand[NB];                                   // 0, or 1 + the bucket's entry of ctab
+    __shared__ uint32_t ctab[kMaxCandBuckets];                     // candidate bucket: first slot of its list segment (low half), elements filed (high half)
     __shared__ uint32_t lkey[CAP];
     __shared__ long long lq[CAP];
     __shared__ uint16_t lb[CAP], lidx[CAP];                         // bucket and index in the row of a candidate
     __shared__ float w_min[NW], w_max[NW];
-    __shared__ uint32_t w_cnt[NW], w_cnt2[NW];
+    __shared__ uint32_t w_cnt[NW];
     __shared__ long long w_sum[NW];
     __shared__ double w_d[NW];
     __shared__ Best wave_best[NW];
-    __shared__ uint32_t nlist_s, r_s, wkey_s;
-    static_assert(CAP <= THREADS && CAP < 1024 && THREADS * ITEMS <= 65536, "a candidate per thread, 10-bit counts, 16-bit indices");
+    __shared__ uint32_t nlist_s, ncb_s, r_s, wkey_s;
+    static_assert(CAP <= THREADS && CAP < 1024 && THREADS * ITEMS <= 65536 && ITEMS <= 32,
+                  "a candidate per thread, 10-bit counts, 16-bit indices, a flag bit per element");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float* row = Wt + static_cast<size_t>(f) * n;
-    float x[ITEMS];
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j) x[j] = row[min(tid + j * THREADS, n - 1)];
 
     // ---- range of the row
     float mn = INFINITY, mx = -INFINITY;
@@ -397,7 +403,7 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
     wave_min_max_f32(mn, mx);
     if (lane == 63) { w_min[wave] = mn; w_max[wave] = mx; }
     for (int b = tid; b < NB; b += THREADS) { cnt[b] = 0u; sum[b] = 0ull; cand[b] = 0; }
-    if (tid == 0) nlist_s = 0u;
+    if (tid == 0) { nlist_s = 0u; ncb_s = 0u; }
     __syncthreads();
     for (int w = 0; w < NW; ++w) { mn = fminf(mn, w_min[w]); mx = fmaxf(mx, w_max[w]); }
     if (!(mx > mn) || !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY)) return false;   // constant row (or not finite)
@@ -426,6 +432,7 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
                 atomicAdd(&cnt[b], 1u);
                 atomicAdd(&sum[b], static_cast<unsigned long long>(fixed_of(x[j])));
             }
+            if (j % 8 == 7) __builtin_amdgcn_sched_barrier(0);
         }
     }
     __syncthreads();
@@ -507,7 +514,6 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
     // U(j) = min(S_b + j hi, S_e - (c-j) lo): a convex region of the (i, P) plane, and D (a sum of
     // squares over linear terms) is jointly convex there, so it is largest at a vertex: at the two
     // ends of the j range or where the two lines of L or of U cross.
-    uint32_t ncand = 0;
 #pragma unroll
     for (int k = 0; k < BPT; ++k) {
         const int b = tid + k * THREADS;
@@ -552,96 +558,84 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
             }
         }
         if (is_cand) {
-            cand[b] = 1;
-            ncand += static_cast<uint32_t>(c);
+            // the bucket's elements get a segment of the list to themselves
+            const uint32_t entry = atomicAdd(&ncb_s, 1u);
+            const uint32_t start = atomicAdd(&nlist_s, static_cast<uint32_t>(c));
+            if (entry < kMaxCandBuckets) {
+                cand[b] = static_cast<uint8_t>(entry + 1u);
+                ctab[entry] = min(start, 0xFFFFu);
+            }
         }
     }
-    const uint32_t ninc = wave_inclusive_scan_u32(ncand);
-    if (lane == 63) w_cnt2[wave] = ninc;
     __syncthreads();
-    uint32_t nc = 0;
-    for (int w = 0; w < NW; ++w) nc += w_cnt2[w];
-    if (nc > CAP || nc == 0) return false;
+    const uint32_t nc = nlist_s;
+    if (nc > CAP || nc == 0 || ncb_s > kMaxCandBuckets) return false;
 
-    // ---- the candidates' elements
+    // ---- the candidates' elements, filed into the segment of their bucket: every thread flags its
+    // own first (the LDS reads in flight together), then files the few it has
     {
+        uint32_t flags = 0;
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
-            if (tid + j * THREADS < n) {
+            float xv = x[j];
+            asm volatile("" : "+v"(xv));                           // (the bucket is computed again, not kept since the histogram)
+            if (tid + j * THREADS < n && cand[bucket_of(xv)]) flags |= 1u << j;
+            if (j % 8 == 7) __builtin_amdgcn_sched_barrier(0);     // eight reads in flight are enough
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if ((flags >> j) & 1u) {
                 const int b = bucket_of(x[j]);
-                if (cand[b]) {
-                    const uint32_t slot = atomicAdd(&nlist_s, 1u);
-                    lkey[slot] = float_to_key(x[j]);
-                    lq[slot] = fixed_of(x[j]);
-                    lb[slot] = static_cast<uint16_t>(b);
-                    lidx[slot] = static_cast<uint16_t>(tid + j * THREADS);
-                }
+                const uint32_t old = atomicAdd(&ctab[cand[b] - 1], 1u << 16);
+                const uint32_t slot = (old & 0xFFFFu) + (old >> 16);
+                lkey[slot] = float_to_key(x[j]);
+                lq[slot] = fixed_of(x[j]);
+                lb[slot] = static_cast<uint16_t>(b);
+                lidx[slot] = static_cast<uint16_t>(tid + j * THREADS);
             }
         }
     }
     __syncthreads();
 
-    // ---- exact position and prefix sum of every candidate: elements of its bucket that precede it
-    // (among equal values it also counts those that come first in the row).  P neighbouring threads
-    // share candidate e = tid / P: each scans every P-th entry of the list, and the partial counts
-    // (packed, 10 bits each) and sums are added across the P lanes by DPP moves.
-    int pshift = 0;
-    while (pshift < 4 && (2 << pshift) * static_cast<int>(nc) <= THREADS) ++pshift;
-    const int P = 1 << pshift;
-    const int e = tid >> pshift, part = tid & (P - 1);
+    // ---- exact position and prefix sum of every candidate (thread e has the e-th entry of the
+    // list): the elements of its bucket that precede it, which are the entries of its segment
+    // (among equal values the earlier entry precedes; the count of equal values that come first in
+    // the row serves the split descriptor below).  Counts are packed, 10 bits each.
+    const int e = tid;
     const bool has = e < static_cast<int>(nc);
     Best best{-1.0, 1.0, 0.0, 0};
     uint32_t my_key = 0, my_less = 0, my_first = 0, my_idx = 0;
-    {
-        uint32_t key = 0, counts = 0;
-        int b = 0;
+    if (has) {
+        const uint32_t key = lkey[e];
+        const int b = lb[e];
+        my_idx = lidx[e];
+        const int q0 = static_cast<int>(ctab[cand[b] - 1] & 0xFFFFu);
+        const int q1 = q0 + static_cast<int>(cnt[b + 1] - cnt[b]);
+        uint32_t counts = 0;
         long long ps = 0;
-        if (has) {
-            key = lkey[e];
-            b = lb[e];
-            my_idx = lidx[e];
-#pragma unroll 4
-            for (int q = part; q < static_cast<int>(nc); q += P) {    // branch-free: the LDS reads pipeline
-                const uint32_t kq = lkey[q];
-                const bool same = lb[q] == b;
-                const bool lt = same && kq < key;
-                const bool eq = same && kq == key;
-                const bool le = lt || (eq && q <= e);
-                counts += (le ? 1u : 0u) + (lt ? 1u << 10 : 0u) + ((eq && lidx[q] < my_idx) ? 1u << 20 : 0u);
-                ps += le ? lq[q] : 0ll;
-            }
+        for (int q = q0; q < q1; ++q) {
+            const uint32_t kq = lkey[q];
+            const bool lt = kq < key;
+            const bool eq = kq == key;
+            const bool le = lt || (eq && q <= e);
+            counts += (le ? 1u : 0u) + (lt ? 1u << 10 : 0u) + ((eq && lidx[q] < my_idx) ? 1u << 20 : 0u);
+            ps += le ? lq[q] : 0ll;
         }
-#define DAB_GROUP_ADD(CTRL) \
-        { \
-            counts += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(counts), CTRL, 0xf, 0xf, false)); \
-            const uint32_t lo = static_cast<uint32_t>( \
-                __builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(ps)), CTRL, 0xf, 0xf, false)); \
-            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_update_dpp( \
-                0, static_cast<int>(static_cast<unsigned long long>(ps) >> 32), CTRL, 0xf, 0xf, false)); \
-            ps += static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo); \
-        }
-        if (P >= 2) DAB_GROUP_ADD(0xB1)      // lanes 1 0 3 2 of every four
-        if (P >= 4) DAB_GROUP_ADD(0x4E)      // lanes 2 3 0 1
-        if (P >= 8) DAB_GROUP_ADD(0x141)     // the eight lanes of a half row mirrored
-        if (P >= 16) DAB_GROUP_ADD(0x140)    // the sixteen lanes of a row mirrored
-#undef DAB_GROUP_ADD
-        if (has && part == 0) {
-            const uint32_t within = counts & 1023u, less = (counts >> 10) & 1023u;
-            my_key = key;
-            my_less = cnt[b] + less;
-            my_first = counts >> 20;
-            const int i = static_cast<int>(cnt[b] + within);
-            if (i >= wlo && i <= whi) {
-                const double Pi = static_cast<double>(static_cast<long long>(sum[b]) + ps);
-                const double rest = T - Pi;
-                const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
-                best = Best{Pi * Pi * fr + rest * rest * fi, fi * fr, Pi, i};
-            }
+        const uint32_t within = counts & 1023u, less = (counts >> 10) & 1023u;
+        my_key = key;
+        my_less = cnt[b] + less;
+        my_first = counts >> 20;
+        const int i = static_cast<int>(cnt[b] + within);
+        if (i >= wlo && i <= whi) {
+            const double Pi = static_cast<double>(static_cast<long long>(sum[b]) + ps);
+            const double rest = T - Pi;
+            const double fi = static_cast<double>(i), fr = static_cast<double>(n - i);
+            best = Best{Pi * Pi * fr + rest * rest * fi, fi * fr, Pi, i};
         }
     }
     const int my_i = best.i;
     // only the wavefronts that hold candidates (the first one, as a rule) reduce
-    const int nwr = min(NW, static_cast<int>((nc << pshift) + 63) >> 6);
+    const int nwr = min(NW, static_cast<int>(nc + 63) >> 6);
     if (wave < nwr) {
         const Best wb = wave_best_of(best);
         if (lane == 63) wave_best[wave] = wb;
@@ -672,7 +666,7 @@ __device__ __forceinline__ bool bucket_row(const float* __restrict__ Wt, int n, 
 
     // ---- the split descriptor's index: the r-th copy of the split value in the order of the row.
     // Every copy is a candidate (equal values share a bucket) and knows how many copies precede it.
-    if (has && part == 0 && my_key == wkey && my_first + 1 == r_s) {
+    if (has && my_key == wkey && my_first + 1 == r_s) {
         thr_idx[f] = static_cast<int32_t>(my_idx);
         if (info) info->thr_idx = static_cast<int>(my_idx);
     }
@@ -689,8 +683,10 @@ __global__ __launch_bounds__(THREADS) void estimate_bucket_kernel(const float* _
                                                                   int max_change, uint8_t* __restrict__ fallback) {
     DAB_RESERVE_VGPRS();
     const int f = static_cast<int>(blockIdx.x);
-    const bool done = bucket_row<THREADS, ITEMS, NB, CAP>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper,
-                                                                 K_prev, upper_prev, max_change);
+    float x[ITEMS];
+    load_row<THREADS, ITEMS>(Wt + static_cast<size_t>(f) * n, n, x);
+    const bool done = bucket_row<THREADS, ITEMS, NB, CAP>(x, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper,
+                                                          K_prev, upper_prev, max_change);
     if (threadIdx.x == 0) fallback[f] = done ? 0 : 1;
 }
 
@@ -705,8 +701,10 @@ __global__ __launch_bounds__(THREADS) void estimate_short_kernel(const float* __
                                                                  int max_change) {
     DAB_RESERVE_VGPRS();
     const int f = static_cast<int>(blockIdx.x);
-    if (bucket_row<THREADS, ITEMS, NB, CAP>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev,
-                                                  upper_prev, max_change))
+    float x[ITEMS];
+    load_row<THREADS, ITEMS>(Wt + static_cast<size_t>(f) * n, n, x);
+    if (bucket_row<THREADS, ITEMS, NB, CAP>(x, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev, upper_prev,
+                                            max_change))
         return;
     __syncthreads();
     sort_row<THREADS, ITEMS>(Wt, n, f, alpha, beta, Kout, thr_val, thr_idx, alpha_is_upper, K_prev, upper_prev, max_change);
@@ -718,6 +716,7 @@ __global__ __launch_bounds__(THREADS) void estimate_short_kernel(const float* __
 // by the workgroup that has just found its split, while the row is still in L2: the weights are
 // read from memory once, and a network's weight side is two or three launches whatever its depth.
 constexpr int kMaxEstJobs = 16;
+constexpr int kSortRowsPerGroup = 8;               // rows a workgroup of the sort kernel looks after
 constexpr int kPackMaxTaps = 128;
 struct EstJob {
     const float* W;
@@ -743,40 +742,54 @@ __device__ __forceinline__ int job_column(unsigned r, int Fp) {
 }
 
 // The mask of filter column f as bits (Corollary 1, by stable rank: the split descriptor), by the
-// whole workgroup: a byte per weight into LDS (the row is re-read, from L2), then one thread per
-// packed word gathers its 32 channels (stride T), writes the word into column f of E and adds its
-// ones to the tap's count.  Columns past F are written as zeros.
-template <int THREADS, int MAXN>
-__device__ __forceinline__ void pack_row(const EstJob& q, int f, const SplitInfo* info) {
-    __shared__ uint8_t maskb[MAXN];
+// whole workgroup, from the row as load_row left it in registers: a byte per weight into LDS, then
+// one thread per packed word gathers its 32 channels (stride T), writes the word into column f of E
+// and adds its ones to the tap's count.  (A wavefront per word pair with a ballot is slower: its
+// address arithmetic is per word instead of per lane.)  Columns past F are written as zeros.
+template <int THREADS, int ITEMS>
+__device__ __forceinline__ void pack_row(const EstJob& job, int f, const SplitInfo* info, const float (&x)[ITEMS]) {
+    __shared__ uint8_t maskb[THREADS * ITEMS];
     __shared__ uint32_t tapcnt[kPackMaxTaps];
     const int tid = threadIdx.x;
-    const int R = q.T * q.Cw;
-    if (f >= q.F) {
-        for (int r = tid; r < R; r += THREADS) q.E[static_cast<size_t>(r) * q.Fp + f] = 0u;
+    // the job's fields by value: behind a reference into the kernel's arguments every store below
+    // would make the compiler read them again
+    uint32_t* const E = job.E;
+    uint32_t* const ecnt = job.ecnt;
+    const int n = job.n, F = job.F, C = job.C, T = job.T, Cw = job.Cw, Fp = job.Fp;
+    const int R = T * Cw;
+    if (f >= F) {
+        for (int r = tid; r < R; r += THREADS) E[static_cast<size_t>(r) * Fp + f] = 0u;
         return;
     }
     const float tv = info->thr_val;
     const int ti = info->thr_idx;
     const bool upper = info->upper != 0;
-    const float* row = q.W + static_cast<size_t>(f) * q.n;
-    for (int i = tid; i < q.n; i += THREADS) {
-        const float w = row[i];
-        const bool lower = w < tv || (w == tv && i <= ti);
-        maskb[i] = lower != upper ? 1 : 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int i = tid + j * THREADS;
+        const bool lower = x[j] < tv || (x[j] == tv && i <= ti);
+        if (i < n) maskb[i] = lower != upper ? 1 : 0;
+        if (j % 8 == 7) __builtin_amdgcn_sched_barrier(0);
     }
-    for (int t = tid; t < q.T; t += THREADS) tapcnt[t] = 0u;
+    for (int t = tid; t < T; t += THREADS) tapcnt[t] = 0u;
     __syncthreads();
+    // one thread per packed word: its 32 channels sit T bytes apart (all reads in flight together)
     for (int r = tid; r < R; r += THREADS) {
-        const int tap = r / q.Cw, w = r - tap * q.Cw;
-        const int c0 = 32 * w, nc = min(32, q.C - c0);
+        const int tap = r / Cw, w = r - tap * Cw;
+        const int c0 = 32 * w, nc = min(32, C - c0);
+        const uint8_t* src = maskb + c0 * T + tap;
         uint32_t word = 0;
-        for (int k = 0; k < nc; ++k) word |= static_cast<uint32_t>(maskb[(c0 + k) * q.T + tap]) << k;
-        q.E[static_cast<size_t>(r) * q.Fp + f] = word;
+        if (nc == 32) {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) word |= static_cast<uint32_t>(src[k * T]) << k;
+        } else {
+            for (int k = 0; k < nc; ++k) word |= static_cast<uint32_t>(src[k * T]) << k;
+        }
+        E[static_cast<size_t>(r) * Fp + f] = word;
         atomicAdd(&tapcnt[tap], static_cast<uint32_t>(__builtin_popcount(word)));
     }
     __syncthreads();
-    for (int t = tid; t < q.T; t += THREADS) q.ecnt[static_cast<size_t>(f) * q.T + t] = tapcnt[t];
+    for (int t = tid; t < T; t += THREADS) ecnt[static_cast<size_t>(f) * T + t] = tapcnt[t];
 }
 
 __device__ __forceinline__ const EstJob& find_job(const EstJobs& jobs, unsigned* blk0) {
@@ -786,57 +799,67 @@ __device__ __forceinline__ const EstJob& find_job(const EstJobs& jobs, unsigned*
     return jobs.job[j];
 }
 
-// Rows of up to THREADS * ITEMS weights: buckets first, the sort by the same workgroup where they
-// cannot finish the row, then the packing.
-template <int THREADS, int ITEMS, int NB, int CAP>
-__global__ __launch_bounds__(THREADS) void binarize_short_kernel(const EstJobs jobs) {
+// Rows of up to THREADS * ITEMS weights, one per workgroup: buckets first; where they cannot finish
+// the row, the sort by the same workgroup (SORT_HERE) or a flag for the sort kernel launched
+// behind; then the packing.
+template <int THREADS, int ITEMS, int NB, int CAP, bool SORT_HERE, int MIN_WAVES>
+__global__ __launch_bounds__(THREADS, MIN_WAVES) void binarize_rows_kernel(const EstJobs jobs) {
     DAB_RESERVE_VGPRS();
     __shared__ SplitInfo info;
     unsigned blk0;
     const EstJob& q = find_job(jobs, &blk0);
     const int f = job_column(blockIdx.x - blk0, q.Fp);
     if (f >= q.Fp) return;
+    float x[ITEMS];
+    bool done = true;
     if (f < q.F) {
-        if (!bucket_row<THREADS, ITEMS, NB, CAP>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev,
-                                                 q.upper_prev, q.max_change, &info)) {
-            __syncthreads();
-            sort_row<THREADS, ITEMS>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev, q.upper_prev,
-                                     q.max_change, &info);
+        load_row<THREADS, ITEMS>(q.W + static_cast<size_t>(f) * q.n, q.n, x);
+        done = bucket_row<THREADS, ITEMS, NB, CAP>(x, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev,
+                                                   q.upper_prev, q.max_change, &info);
+        if constexpr (SORT_HERE) {
+            if (!done) {
+                __syncthreads();
+                sort_row<THREADS, ITEMS>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev, q.upper_prev,
+                                         q.max_change, &info);
+                done = true;
+            }
+        } else if (threadIdx.x == 0) {
+            q.flags[f] = done ? 0 : 1;
         }
         __syncthreads();
     }
-    if (q.E) pack_row<THREADS, THREADS * ITEMS>(q, f, &info);
+    if (q.E && done) {
+        // many elements per thread: read them again (from L2) rather than hold them through the estimation
+        if (ITEMS > 16 && f < q.F) load_row<THREADS, ITEMS>(q.W + static_cast<size_t>(f) * q.n, q.n, x);
+        pack_row<THREADS, ITEMS>(q, f, &info, x);
+    }
 }
 
-// Longer rows: buckets; a row they cannot finish is flagged for the sort kernel launched behind.
-template <int THREADS, int ITEMS, int NB, int CAP>
-__global__ __launch_bounds__(THREADS) void binarize_long_kernel(const EstJobs jobs) {
-    DAB_RESERVE_VGPRS();
-    __shared__ SplitInfo info;
-    unsigned blk0;
-    const EstJob& q = find_job(jobs, &blk0);
-    const int f = job_column(blockIdx.x - blk0, q.Fp);
-    if (f >= q.Fp) return;
-    bool done = true;
-    if (f < q.F) {
-        done = bucket_row<THREADS, ITEMS, NB, CAP>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev,
-                                                   q.upper_prev, q.max_change, &info);
-        if (threadIdx.x == 0) q.flags[f] = done ? 0 : 1;
-        __syncthreads();
-    }
-    if (q.E && done) pack_row<THREADS, THREADS * ITEMS>(q, f, &info);
-}
+// The rows the kernel above has flagged, kSortRowsPerGroup per workgroup (their flags are one
+// aligned 8-byte read: the flag array of a job is padded to a multiple of 256 bytes).
 template <int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void binarize_sort_kernel(const EstJobs jobs) {
+    static_assert(kSortRowsPerGroup == 8, "the flags of a workgroup's rows are read as one 64-bit word");
     __shared__ SplitInfo info;
     unsigned blk0;
     const EstJob& q = find_job(jobs, &blk0);
-    const int f = static_cast<int>(blockIdx.x - blk0);
-    if (f >= q.F || !q.flags[f]) return;            // the bucket kernel has finished this row
-    sort_row<THREADS, ITEMS>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev, q.upper_prev, q.max_change,
-                             &info);
-    __syncthreads();
-    if (q.E) pack_row<THREADS, THREADS * ITEMS>(q, f, &info);
+    const int f0 = static_cast<int>(blockIdx.x - blk0) * kSortRowsPerGroup;
+    unsigned long long fl = *reinterpret_cast<const unsigned long long*>(q.flags + f0);
+    if (f0 + kSortRowsPerGroup > q.F) fl &= (1ull << (8 * (q.F - f0))) - 1ull;     // rows past the last one are not ours
+    if (fl == 0ull) return;                         // the bucket kernel has finished all of them
+    for (int k = 0; k < kSortRowsPerGroup; ++k) {
+        if (((fl >> (8 * k)) & 0xFFull) == 0ull) continue;
+        const int f = f0 + k;
+        sort_row<THREADS, ITEMS>(q.W, q.n, f, q.alpha, q.beta, q.K, q.thr_val, q.thr_idx, q.aiu, q.K_prev, q.upper_prev,
+                                 q.max_change, &info);
+        __syncthreads();
+        if (q.E) {
+            float x[ITEMS];
+            load_row<THREADS, ITEMS>(q.W + static_cast<size_t>(f) * q.n, q.n, x);
+            pack_row<THREADS, ITEMS>(q, f, &info, x);
+        }
+        __syncthreads();
+    }
 }
 
 // ---------------------------------------------------------------- sign split (XNOR-Net / BWN)
@@ -952,7 +975,8 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
 }
 
 // ---------------------------------------------------------------- host side of the multi-layer call
-constexpr int kShortMaxN = 512 * 9;                // rows up to here: binarize_short_kernel (one configuration for all)
+constexpr int kSmallMaxN = 256 * 9;                // rows up to here: 256 threads and 512 buckets per row
+constexpr int kShortMaxN = 512 * 9;                // rows up to here: 512 threads and 2048 buckets, sorted in the same kernel if need be
 
 static int check_weight_job(const dab_weight_job& j) {
     if (!j.W || !j.alpha || !j.beta || !j.K || !j.thr_val || !j.thr_idx || !j.alpha_is_upper) return DAB_ERR_NULL;
@@ -977,9 +1001,10 @@ static size_t weight_jobs_ws_bytes(const dab_weight_job* jobs, int n_jobs) {
 }
 
 static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, size_t ws_bytes, hipStream_t st) {
-    EstJobs shortj, longj, sortj;
-    shortj.n = longj.n = sortj.n = 0;
-    unsigned short_end = 0, long_end = 0, sort_end = 0;
+    // three classes of rows, a launch each where present (a fourth, behind the long rows, for the rows they flag)
+    EstJobs smallj, shortj, longj, sortj;
+    smallj.n = shortj.n = longj.n = sortj.n = 0;
+    unsigned small_end = 0, short_end = 0, long_end = 0, sort_end = 0;
     uint8_t* flags = static_cast<uint8_t*>(ws);
     for (int i = 0; i < n_jobs; ++i) {
         const dab_weight_job& in = jobs[i];
@@ -989,7 +1014,11 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
         q.E = in.E_packed; q.ecnt = in.ecnt;
         q.F = in.F; q.C = in.C; q.T = in.kh * in.kw; q.n = in.C * q.T; q.Cw = ceil_div(in.C, 32); q.Fp = 64 * ceil_div(in.F, 64);
         const unsigned columns = static_cast<unsigned>(kNumXCD * ceil_div(q.Fp, kNumXCD));
-        if (q.n <= kShortMaxN) {
+        if (q.n <= kSmallMaxN) {
+            small_end += columns;
+            q.blk_end = small_end;
+            smallj.job[smallj.n++] = q;
+        } else if (q.n <= kShortMaxN) {
             short_end += columns;
             q.blk_end = short_end;
             shortj.job[shortj.n++] = q;
@@ -999,16 +1028,18 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
             long_end += columns;
             q.blk_end = long_end;
             longj.job[longj.n++] = q;
-            sort_end += static_cast<unsigned>(in.F);
+            sort_end += static_cast<unsigned>(ceil_div(in.F, kSortRowsPerGroup));
             q.blk_end = sort_end;
             sortj.job[sortj.n++] = q;
         }
     }
     (void)ws_bytes;
+    if (smallj.n)
+        if (int rc = launch(binarize_rows_kernel<256, 9, 512, 256, true, 5>, dim3(small_end), dim3(256), 0, st, smallj)) return rc;
     if (shortj.n)
-        if (int rc = launch(binarize_short_kernel<512, 9, 2048, 256>, dim3(short_end), dim3(512), 0, st, shortj)) return rc;
+        if (int rc = launch(binarize_rows_kernel<512, 9, 2048, 256, true, 4>, dim3(short_end), dim3(512), 0, st, shortj)) return rc;
     if (longj.n) {
-        if (int rc = launch(binarize_long_kernel<512, 26, 2048, 512>, dim3(long_end), dim3(512), 0, st, longj)) return rc;
+        if (int rc = launch(binarize_rows_kernel<512, 26, 2048, 512, false, 4>, dim3(long_end), dim3(512), 0, st, longj)) return rc;
         if (int rc = launch(binarize_sort_kernel<1024, 13>, dim3(sort_end), dim3(1024), 0, st, sortj)) return rc;
     }
     return DAB_OK;
@@ -1066,6 +1097,7 @@ int dab_binarize_weights_multi(const dab_weight_job* jobs, int32_t n_jobs, void*
         if (int rc = check_weight_job(jobs[i])) return rc;
     const size_t need = weight_jobs_ws_bytes(jobs, n_jobs);
     if (need && (!ws || ws_bytes < need)) return DAB_ERR_WORKSPACE;
+    if (need && misaligned(ws, 8)) return DAB_ERR_ALIGN;
     return run_weight_jobs(jobs, n_jobs, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 

@@ -86,23 +86,26 @@ def test_config3_full_chain():
         torch.cuda.synchronize()
         assert torch.equal(y_bench.reshape(-1), g["Y_gpu"].reshape(-1))
         check_full_layer(L, x_nchw, W, tau, g, count=64)
-    # the benchmark's multi-stream step (weight side on side streams) reproduces every layer bit for bit
+    # the benchmark's step (grouped calls, weight sides on side streams) reproduces every layer bit for bit
     want = [s.Y.clone() for s in states]
-    sched = bench.Schedule(states, 2, torch)
+    bits = [s.A.clone() for s in states]
+    sched = bench.GroupedStep(states, dab, torch)
     graph = None
     for it in range(7):
         if it == 3:
-            graph = sched.capture(dab)       # the step as one HIP graph, replayed with eager work in between
+            graph = sched.capture()          # the step as one HIP graph, replayed with eager work in between
         for s in states:
             s.Y.zero_()
+            s.A.zero_()
             s.EW[0].zero_()
             s.est["alpha"].zero_()
         if graph is None:
-            sched.step(dab)
+            sched.step()
         else:
             graph.replay()
         torch.cuda.synchronize()
-        for s, y in zip(states, want):
+        for s, y, a in zip(states, want, bits):
+            assert torch.equal(s.A, a), (it, s.L.name)
             assert torch.equal(s.Y, y), (it, s.L.name)
 
 
