@@ -1060,15 +1060,17 @@ int init_binconv() {
 static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t* E, const float* alpha,
                        const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits,
                        void* ws, size_t ws_bytes, hipStream_t st) {
-    // layers with enough tiles and a reduction whose B fragments fit in LDS: one launch, no workspace
+    // layers of a few hundred output blocks: one workgroup per block, straight from the bits, no workspace
+    BlockPlan bp;
+    if (plan_block(d, &bp, false)) return launch_block(bp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
+    // a reduction whose B fragments fit in LDS: one launch of the persistent kernel, no workspace
     DirectPlan dp;
     if (plan_direct(d, &dp)) {
         if (int rc = ensure_device_ready()) return rc;
         return launch_direct(dp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
     }
-    // layers of a few hundred output blocks: one workgroup per block, also from the bits, no workspace
-    BlockPlan bp;
-    if (plan_block(d, &bp)) return launch_block(bp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
+    // longer reductions over up to 2048 blocks: the block kernel again
+    if (plan_block(d, &bp, true)) return launch_block(bp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl)) return rc;
     if (!ws || ws_bytes < pl.ws_bytes || misaligned(ws, 256)) return DAB_ERR_WORKSPACE;
@@ -1181,7 +1183,7 @@ size_t dab_binconv2d_workspace_bytes(const dab_conv_desc* d) {
     dab::DirectPlan dp;
     if (!d || dab::check_desc(d) != DAB_OK) return 0;
     dab::BlockPlan bp;
-    if (dab::plan_direct(*d, &dp) || dab::plan_block(*d, &bp)) return 0;
+    if (dab::plan_block(*d, &bp, false) || dab::plan_direct(*d, &dp) || dab::plan_block(*d, &bp, true)) return 0;
     if (dab::plan_binconv(*d, &pl) != DAB_OK) return 0;
     return pl.ws_bytes;
 }

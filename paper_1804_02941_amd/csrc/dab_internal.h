@@ -102,7 +102,7 @@ struct BlockPlan {
     bool pad;
     unsigned grid;
 };
-bool plan_block(const dab_conv_desc& d, BlockPlan* pl);
+bool plan_block(const dab_conv_desc& d, BlockPlan* pl, bool large);
 int launch_block(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
                  const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits);
 bool plan_direct(const dab_conv_desc& d, DirectPlan* pl);

@@ -669,11 +669,10 @@ bool plan_direct(const dab_conv_desc& d, DirectPlan* pl) {
     if (g.n_ent > kDirMaxSteps + 1) return false;
     g.d_HoWo = make_fastdiv(g.HoWo); g.d_Wo = make_fastdiv(g.Wo); g.d_WH = make_fastdiv(g.WH);
     // eight wavefronts (512 pixels per tile) when that still gives most compute units a tile, else four
+    // (layers with fewer tiles than compute units leave some idle, and are still done in one launch)
     const int n_ntiles = ceil_div(d.F, kDirNTile);
     pl->waves = 1ll * ceil_div(g.M, 512) * n_ntiles >= kNumCU * 3 / 4 ? 8 : 4;
     g.n_mtiles = ceil_div(g.M, 64 * pl->waves);
-    // too few tiles to fill the chip: another kernel's case
-    if (1ll * g.n_mtiles * n_ntiles * 2 <= kNumCU) return false;
     g.wg_per_ntile = kNumCU / n_ntiles;
     if (g.wg_per_ntile < 1) g.wg_per_ntile = 1;
     if (g.wg_per_ntile > g.n_mtiles) g.wg_per_ntile = g.n_mtiles;
@@ -682,8 +681,11 @@ bool plan_direct(const dab_conv_desc& d, DirectPlan* pl) {
     return true;
 }
 
-// Layers for the block kernel: too few tiles for the persistent kernel, at most 512 blocks of 32 x 32.
-bool plan_block(const dab_conv_desc& d, BlockPlan* pl) {
+// Layers for the block kernel.  Small ones (at most 512 blocks of 32 x 32 and too few tiles to give
+// half the compute units one of the persistent kernel's): it is the fastest form.  With `large`,
+// up to 2048 blocks: for layers whose reduction is too long for the persistent kernel's panel it
+// still beats the kernels that go through a workspace.
+bool plan_block(const dab_conv_desc& d, BlockPlan* pl, bool large) {
     DirectGeom& g = pl->g;
     g = DirectGeom{};
     g.H = d.H; g.W = d.W; g.C = d.C; g.F = d.F; g.kh = d.kh; g.kw = d.kw;
@@ -715,7 +717,7 @@ bool plan_block(const dab_conv_desc& d, BlockPlan* pl) {
     bg.d_kw = make_fastdiv(d.kw);
     const long long blocks = 1ll * ceil_div(g.M, 32) * bg.n_fblocks;
     const int tiles256 = ceil_div(g.M, 256) * ceil_div(d.F, kDirNTile);
-    if (tiles256 * 2 > kNumCU || blocks > 512) return false;
+    if (large ? blocks > 2048 : (tiles256 * 2 > kNumCU || blocks > 512)) return false;
     pl->grid = static_cast<unsigned>(ceil_div(g.M, 32) * bg.fb_per_xcd * kNumXCD);
     // enough wavefronts per block that each keeps a few k-steps of the reduction
     pl->waves = g.nk >= 32 ? 8 : 2;

@@ -135,12 +135,12 @@ def test_config3_fused_chain_matches_fp32_chain():
 
 
 def test_error_codes_of_the_new_entry_points():
-    d = dab.dab_conv_desc(2048, 64, 1, 1, 512, 1, 1, 0, 0, 1, 1)     # a mid-sized layer: its operands are expanded into a workspace
-    A = torch.zeros((2048, 1, 1, 2), dtype=torch.int32, device="cuda:0")
-    E = torch.zeros((2, 512), dtype=torch.int32, device="cuda:0")
+    d = dab.dab_conv_desc(8192, 4096, 1, 1, 512, 1, 1, 0, 0, 1, 1)   # a long reduction over many rows: operands are expanded into a workspace
+    A = torch.zeros((8192, 1, 1, 128), dtype=torch.int32, device="cuda:0")
+    E = torch.zeros((128, 512), dtype=torch.int32, device="cuda:0")
     ab = torch.ones(512, dtype=torch.float32, device="cuda:0")
     import ctypes
-    out = torch.zeros((2048, 1, 1, 16), dtype=torch.int32, device="cuda:0")
+    out = torch.zeros((8192, 1, 1, 16), dtype=torch.int32, device="cuda:0")
     small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
     rc = dab.lib().dab_binconv2d_bits(ctypes.byref(d), A.data_ptr(), E.data_ptr(), ab.data_ptr(), ab.data_ptr(), None,
                                       out.data_ptr(), small.data_ptr(), 256, None)
