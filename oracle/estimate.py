@@ -20,7 +20,7 @@ the design notes of the repository):
   i = n, where n - i = 0; Theorem 2 excludes e = 1, so i = n is not a split.
 * One ascending pass suffices: the descending pass of Algorithm 1 scores the
   same partitions (D_desc(j) = D_asc(n-j)) with the complementary labelling.
-  ``alg1_two_pass`` keeps the literal two-pass form for the tests.
+  ``two_pass_choice`` states what taking both passes yields, for the tests.
 * Ties in D are resolved towards the largest i (the ">=" of Algorithm 1).
 * Which group is called alpha: Section 4.1 says alpha captures the value of
   greater magnitude.  On equal magnitudes the upper group is alpha.
@@ -196,32 +196,29 @@ def group_means(w: np.ndarray, e: np.ndarray):
     return float(w @ e / K), float(w @ (1.0 - e) / (n - K))
 
 
-def alg1_two_pass(w: np.ndarray) -> dict:
-    """Algorithm 1 as printed, two passes, with the loop cut at i = n-1.
+def two_pass_choice(w: np.ndarray) -> dict:
+    """The outcome of Algorithm 1 when both of its passes are taken.
 
-    Returns optK_1/maxD_1 of the ascending pass, optK_2/maxD_2 of the
-    descending pass, the final K and which pass supplied it.  The e the paper
-    attaches to the returned K is "the first K of that pass's order".
+    The descending order scores the same partitions as the ascending one, read
+    backwards: its split of size j is the ascending split of size n - j with
+    the two groups' roles exchanged, and D is symmetric in the groups.  So the
+    scores of the second pass are ``split_scores``' D reversed.  Each pass
+    keeps the largest index among the maxima of its own scores, and the second
+    pass replaces the first only with a strictly greater score.  Returns both
+    passes' (K, D), the K that is kept and whether the second pass supplied it
+    (its mask would then be the K largest weights).
     """
-    w = np.asarray(w, dtype=np.float64).ravel()
-    n = w.size
-    asc = np.sort(w + 0.0, kind="stable")
-    T = float(np.sum(asc))
+    _, _, D = split_scores(w)
+    D_desc = D[::-1]
 
-    def one_pass(v):
-        optK, maxD, P = 0, 0.0, 0.0
-        for i in range(1, n):
-            P = P + v[i - 1]
-            D = P * P / i + (T - P) * (T - P) / (n - i)
-            if D >= maxD:
-                maxD, optK = D, i
-        return optK, maxD
+    def last_argmax(scores):
+        return int(scores.size - 1 - np.argmax(scores[::-1]))
 
-    k1, d1 = one_pass(asc)
-    k2, d2 = one_pass(asc[::-1])
-    if d2 > d1:
-        return dict(optK_1=k1, maxD_1=d1, optK_2=k2, maxD_2=d2, K=k2, descending=True)
-    return dict(optK_1=k1, maxD_1=d1, optK_2=k2, maxD_2=d2, K=k1, descending=False)
+    k_asc, k_desc = last_argmax(D) + 1, last_argmax(D_desc) + 1
+    d_asc, d_desc = float(D[k_asc - 1]), float(D_desc[k_desc - 1])
+    descending = d_desc > d_asc
+    return dict(K_ascending=k_asc, D_ascending=d_asc, K_descending=k_desc, D_descending=d_desc,
+                K=k_desc if descending else k_asc, descending=descending)
 
 
 def brute_force(w) -> dict:

@@ -165,23 +165,30 @@ def test_symmetric_filter_is_xnor():
 
 
 @pytest.mark.parametrize("seed", range(6))
-def test_two_pass_listing_gives_same_partition(seed):
-    """Algorithm 1 with its descending pass: the same two groups, whichever pass wins."""
+def test_both_passes_give_the_same_partition(seed):
+    """Algorithm 1 with its descending pass taken as well: the same two groups, whichever pass is kept."""
     rng = np.random.default_rng(100 + seed)
     n = int(rng.integers(5, 300))
     w = (rng.standard_normal(n) * 0.05 + rng.uniform(-0.05, 0.05)).astype(np.float32)
     r = est.estimate_filter(w)
-    tp = est.alg1_two_pass(w)
-    assert tp["optK_1"] + tp["optK_2"] == n or tp["maxD_1"] != tp["maxD_2"]
-    order = est.stable_order(w)
-    if tp["descending"]:
-        chosen = frozenset(order[::-1][: tp["K"]].tolist())
-    else:
-        chosen = frozenset(order[: tp["K"]].tolist())
+    tp = est.two_pass_choice(w)
+    # the second pass sees the first one's scores backwards: equal maxima, and with a single maximiser mirrored positions
+    assert tp["D_ascending"] == tp["D_descending"] and not tp["descending"]
+    order, _, D = est.split_scores(w)
+    if np.count_nonzero(D == D.max()) == 1:
+        assert tp["K_ascending"] + tp["K_descending"] == n
+    # brute force over the descending order itself: running sums of the weights taken from the top
+    desc = w.astype(np.float64)[order][::-1]
+    T = desc.sum()
+    P = np.cumsum(desc)[: n - 1]
+    j = np.arange(1, n)
+    D_top = P * P / j + (T - P) * (T - P) / (n - j)
+    assert np.allclose(D_top, D[::-1], rtol=1e-9, atol=1e-12)
+    chosen = frozenset(order[: tp["K"]].tolist())
     ones = frozenset(np.flatnonzero(r["e"]).tolist())
     zeros = frozenset(np.flatnonzero(1 - r["e"]).tolist())
     assert chosen in (ones, zeros)
-    assert max(tp["maxD_1"], tp["maxD_2"]) == pytest.approx(r["maxD"], rel=1e-12)
+    assert tp["D_ascending"] == pytest.approx(r["maxD"], rel=1e-12)
 
 
 def test_labelling_and_ties():
