@@ -57,7 +57,12 @@ __device__ __forceinline__ int fdiv(int n, FastDiv d) {
 // else).  Measured on MI355X: an estimation kernel that the compiler fitted into exactly 64 VGPRs
 // returned wrong results as soon as two of its workgroups shared a compute unit, the identical
 // instructions were right with a 72-register allocation; the build refuses 64-VGPR kernels.
+// (DAB_NO_RESERVE_VGPRS builds the kernels without it, for looking at the allocations only.)
+#ifndef DAB_NO_RESERVE_VGPRS
 #define DAB_RESERVE_VGPRS() asm volatile("" ::: "v71")
+#else
+#define DAB_RESERVE_VGPRS() do { } while (0)
+#endif
 
 // One-time set-up of the current device (api.hip); the pieces live beside the kernels they prepare.
 constexpr int kMaxDevices = 64;

@@ -41,6 +41,7 @@ void run_block(int threads, int f, Body body) {
     emu::g_block_barrier = &bar;
     emu::g_waves = waves.data();
     blockDim.x = static_cast<unsigned>(threads);
+    emu_poison_lds();
     std::vector<std::thread> pool;
     for (int t = 0; t < threads; ++t)
         pool.emplace_back([=] {
@@ -156,6 +157,9 @@ int main(int argc, char** argv) {
     else if (which == "bucket256x9") run_bucket<256, 9, 512, 256>(W, F, n, o);
     else if (which == "bucket512x9") run_bucket<512, 9, 2048, 256>(W, F, n, o);
     else run_bucket<512, 26, 2048, 512>(W, F, n, o);
+#ifdef EMU_POISON_LDS
+    std::printf("LDS section marked uninitialised before every workgroup: %zu bytes\n", static_cast<size_t>(__stop_emu_lds - __start_emu_lds));
+#endif
     int bad = 0;
     for (int f = 0; f < F; ++f) {
         const float* row = W.data() + static_cast<size_t>(f) * n;

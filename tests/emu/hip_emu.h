@@ -19,9 +19,19 @@
 #define __device__
 #define __global__
 #define __forceinline__ inline
+// With EMU_POISON_LDS (MemorySanitizer builds) every LDS array sits in one linker section, which a
+// workgroup marks uninitialised before it starts: LDS holds whatever the previous workgroup left.
+#ifdef EMU_POISON_LDS
+#include <sanitizer/msan_interface.h>
+#define __shared__ static __attribute__((section("emu_lds")))
+extern "C" char __start_emu_lds[], __stop_emu_lds[];
+inline void emu_poison_lds() { __msan_poison(__start_emu_lds, static_cast<size_t>(__stop_emu_lds - __start_emu_lds)); }
+#else
 #define __shared__ static
+inline void emu_poison_lds() {}
+#endif
 #define __launch_bounds__(...)
-#define __align__(n) alignas(n)
+#define __align__(n) __attribute__((aligned(n)))
 #define DAB_RESERVE_VGPRS() do { } while (0)
 
 struct alignas(16) uint4 { uint32_t x, y, z, w; };
