@@ -47,7 +47,8 @@ def kernel_resources(log: str) -> dict:
 
 
 def check_resources(res: dict) -> None:
-    """Refuse a build with a kernel whose register allocation is exactly 64 VGPRs (granule 8, no AGPRs).
+    """Refuse a build with a kernel whose register allocation is exactly 64 VGPRs (granule 8, no AGPRs),
+    or with any kernel that spills to scratch memory.
 
     Measured on MI355X with the estimation kernel: such an allocation gave wrong results whenever two
     workgroups shared a compute unit, the same instructions with a 72-register allocation did not."""
@@ -55,6 +56,8 @@ def check_resources(res: dict) -> None:
         v, a = r.get("VGPRs", 0), r.get("AGPRs", 0)
         if a == 0 and 56 < v <= 64:
             raise RuntimeError(f"kernel {name} is allocated exactly 64 VGPRs; reserve one more register in it")
+        if r.get("ScratchSize [bytes/lane]", 0) != 0:
+            raise RuntimeError(f"kernel {name} spills to scratch memory ({r['ScratchSize [bytes/lane]']} bytes per lane)")
 
 
 def _without_remarks(text: str) -> str:
