@@ -8,11 +8,11 @@ path over the batch: for every layer, alpha/beta estimation of its filters, weig
 packing, activation bit packing and the binary convolution / fully-connected product.  The
 fp32 inputs of all layers and the fp32 weights are resident in HBM before the timed region.
 
-A step is a handful of launches, captured as one HIP graph: one launch packs the activations of
-all six layers; the weight sides (estimation + mask packing; they depend on no activation) are
-two grouped calls on two side streams (the five layers with short filters in one launch, conv6
-with its 12544-element filters in its own); each binary product is a single launch that reads
-the packed bits and writes fp32.  The timed region is K graph launches.
+A step is seven calls on one stream, captured as one HIP graph: dab_prepare_layers does the weight
+sides of all six layers (estimation + mask packing: one launch for the five layers with short
+filters, one for conv6 with its 12544-element filters, one behind it for rows handed to the sort)
+and, inside the same launches, packs the activations of all six layers; each binary product is a
+single launch that reads the packed bits and writes fp32.  The timed region is K graph launches.
 
 Prints one JSON line: the metric (effective binary MACs/s), the roofline of the dominant
 kernel (the binary product of the largest layer), a table of every stage against the HBM
@@ -59,7 +59,8 @@ def parse():
     ap.add_argument("--cpu-batch", type=int, default=256, help="images of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of one captured HIP graph per step")
-    ap.add_argument("--one-stream", action="store_true", help="put the weight sides on the main stream as well")
+    ap.add_argument("--separate", action="store_true",
+                    help="weight sides and activation packing as two calls instead of dab_prepare_layers")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the measurements beside the headline (stage table, other configs, fused chain, "
                          "training side, weights-only layers, small batch)")
@@ -166,70 +167,35 @@ def run_layer(s, dab):
 
 
 class GroupedStep:
-    """One step of a set of independent layers through the grouped entry points.
+    """One step of a set of independent layers through the grouped entry points, on one stream:
+    dab_prepare_layers (the weight sides of all layers and, in the same launches, the activation
+    packing of all layers), then the binary products in layer order.  `separate` issues the weight
+    sides and the packing as two calls instead (for comparison)."""
 
-    main stream : one launch packs the activations of every layer, then the products in layer order
-    side stream : dab_binarize_weights_multi over the layers with short filters (one launch)
-    side stream : dab_binarize_weights_multi over the layers with long filters (conv6)
-    A product waits for the weight group of its own layer only.  A step forks from and joins back
-    into the current stream, so steps never overlap and the step can be captured into one HIP graph.
-    """
-
-    SHORT_MAX_N = 4608
-
-    def __init__(self, states, dab, torch, one_stream=False):
-        self.states, self.torch, self.dab = states, torch, dab
+    def __init__(self, states, dab, torch, separate=False):
+        self.states, self.torch, self.dab, self.separate = states, torch, dab, separate
         self.pack = dab.pack_jobs([(s.X, s.tau, s.A) for s in states])
-        groups = [[i for i, s in enumerate(states) if s.W2.shape[1] <= self.SHORT_MAX_N],
-                  [i for i, s in enumerate(states) if s.W2.shape[1] > self.SHORT_MAX_N]]
-        self.groups = [g for g in groups if g]
-        self.jobs, self.ws = [], []
-        for g in self.groups:
-            jobs = dab.weight_jobs([dict(W=states[i].W, est=states[i].est, packed=states[i].EW) for i in g])
-            nbytes = dab.lib().dab_binarize_weights_multi_workspace_bytes(jobs, len(jobs))
-            self.jobs.append(jobs)
-            self.ws.append(torch.empty(max(nbytes, 1), dtype=torch.uint8, device=states[0].X.device))
-        self.group_of = {i: k for k, g in enumerate(self.groups) for i in g}
-        self.side = [] if one_stream else [torch.cuda.Stream() for _ in self.groups]
-        self.fork = torch.cuda.Event()
-        self.ready = [torch.cuda.Event() for _ in self.groups]
-        # products whose weights come from the short group first: the long group's estimation is the
-        # longest single piece of the step and runs beside them
-        self.order = sorted(range(len(states)), key=lambda i: (self.group_of[i], i))
+        self.jobs = dab.weight_jobs([dict(W=s.W, est=s.est, packed=s.EW) for s in states])
+        nbytes = dab.lib().dab_binarize_weights_multi_workspace_bytes(self.jobs, len(self.jobs))
+        self.ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=states[0].X.device)
 
-    def weights(self, k):
-        self.dab.dab_binarize_weights_multi(self.jobs[k], ws=self.ws[k])
+    def weights(self):
+        self.dab.dab_binarize_weights_multi(self.jobs, ws=self.ws)
 
     def pack_all(self):
         self.dab.dab_pack_activations_multi(self.pack)
 
+    def prepare(self):
+        self.dab.dab_prepare_layers(self.jobs, self.pack, ws=self.ws)
+
     def step(self):
-        torch, dab, states = self.torch, self.dab, self.states
-        main = torch.cuda.current_stream()
-        if not self.side:
+        if self.separate:
+            self.weights()
             self.pack_all()
-            for k in range(len(self.groups)):
-                self.weights(k)
-            for i in self.order:
-                product(states[i], dab)
-            return
-        self.fork.record(main)
-        self.pack_all()
-        for k, q in enumerate(self.side):
-            q.wait_event(self.fork)
-            with torch.cuda.stream(q):
-                self.weights(k)
-                self.ready[k].record(q)
-        waited = set()
-        for i in self.order:
-            k = self.group_of[i]
-            if k not in waited:
-                main.wait_event(self.ready[k])
-                waited.add(k)
-            product(states[i], dab)
-        for k in range(len(self.groups)):
-            if k not in waited:
-                main.wait_event(self.ready[k])
+        else:
+            self.prepare()
+        for s in self.states:
+            product(s, self.dab)
 
     def capture(self):
         torch = self.torch
@@ -242,12 +208,13 @@ class GroupedStep:
 class FusedChain:
     """The same six layers with the re-binarizing epilogue: bits are handed from layer to layer
     (3/2 max-pooling as an OR on the bits after conv2 and conv5), so between conv2 and fc7 no fp32
-    activation is written or read.  conv2 packs its fp32 input as in the plain step and fc7 writes
-    fp32.  Thresholds of the hand-over are the per-channel means the plain step uses.  The weight
-    sides are the two grouped calls of the plain step on its side streams."""
+    activation is written or read.  conv2 packs its fp32 input (in the launches of the weight sides,
+    as in the plain step) and fc7 writes fp32.  Thresholds of the hand-over are the per-channel
+    means the plain step uses.  One stream."""
 
     def __init__(self, states, grouped, dab, torch):
         self.states, self.grouped, self.torch = states, grouped, torch
+        self.pack_first = dab.pack_jobs([(states[0].X, states[0].tau, states[0].A)])
         self.bits = []
         for s in states:
             L = s.L
@@ -284,25 +251,10 @@ class FusedChain:
         return res
 
     def step(self, dab):
-        torch, states, g = self.torch, self.states, self.grouped
-        main = torch.cuda.current_stream()
-        g.fork.record(main)
-        activation_side(states[0], dab)
-        for k, q in enumerate(g.side):
-            q.wait_event(g.fork)
-            with torch.cuda.stream(q):
-                g.weights(k)
-                g.ready[k].record(q)
-        if not g.side:
-            for k in range(len(g.groups)):
-                g.weights(k)
-        A = states[0].A
-        waited = set()
-        for i in range(len(states)):
-            k = g.group_of[i]
-            if g.side and k not in waited:
-                main.wait_event(g.ready[k])
-                waited.add(k)
+        g = self.grouped
+        dab.dab_prepare_layers(g.jobs, self.pack_first, ws=g.ws)
+        A = self.states[0].A
+        for i in range(len(self.states)):
             A = self.product(i, A, dab)
 
     def capture(self, dab):
@@ -354,12 +306,12 @@ def stage_table(states, grouped, dab, torch):
     """Every stage of the step alone on the chip, against the HBM roofline (algorithmic bytes: what the
     stage must read and write once)."""
     rows = {}
+    rows["prepare_layers: weight sides and activation packing of all layers, one call"] = hbm_row(
+        device_us(torch, grouped.prepare), sum(s.pack_bytes() + s.weight_bytes() for s in states), 3)
     rows["pack_activations: all layers, one launch"] = hbm_row(
         device_us(torch, grouped.pack_all), sum(s.pack_bytes() for s in states), 1)
-    for k, g in enumerate(grouped.groups):
-        names = "+".join(states[i].L.name for i in g)
-        rows[f"estimate + pack_weights: {names}, one grouped call"] = hbm_row(
-            device_us(torch, lambda k=k: grouped.weights(k)), sum(states[i].weight_bytes() for i in g), None)
+    rows["estimate + pack_weights: all layers, one grouped call"] = hbm_row(
+        device_us(torch, grouped.weights), sum(s.weight_bytes() for s in states), 3)
     for s in states:
         rows[f"pack_activations: {s.L.name}"] = hbm_row(device_us(torch, lambda s=s: activation_side(s, dab)),
                                                         s.pack_bytes(), 1)
@@ -632,7 +584,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    grouped = GroupedStep(states, dab, torch, one_stream=args.one_stream)
+    grouped = GroupedStep(states, dab, torch, separate=args.separate)
     for _ in range(min(args.warmup, 3)):
         grouped.step()
     torch.cuda.synchronize()
@@ -729,9 +681,9 @@ def main():
         "config": {"workload": "config 3: Sketch-A-Net binarized trunk (conv2-conv6, fc7), batch %d, "
                                "estimate + pack weights + pack activations + binary product per layer" % args.batch,
                    "batch": args.batch, "binary_macs_per_step": total_macs,
-                   "streams": 1 + len(grouped.side),
+                   "streams": 1,
                    "launch": "eager" if args.no_graph else "one captured HIP graph per step",
-                   "calls_per_step": 1 + len(grouped.groups) + len(states),
+                   "calls_per_step": (2 if args.separate else 1) + len(states),
                    "eager_ms_per_step": round(1e3 * dt_eager / args.steps, 4)},
         "roofline": roofline, "cpu_baseline": cpu,
     }

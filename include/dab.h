@@ -267,6 +267,19 @@ typedef struct dab_pack_job {
 int dab_pack_activations_multi(const dab_pack_job* jobs /* host */, int32_t n_jobs, void* stream);
 
 /*
+ * dab_prepare_layers - everything that precedes the binary products of a set of resident layers:
+ * dab_binarize_weights_multi(wjobs) and dab_pack_activations_multi(pjobs) in the launches of the
+ * former.  The weight side (Section 4.3.1, Corollary 1) and the binarization of the inputs (Section 4)
+ * do not depend on each other and load different parts of the chip (vector instructions and LDS
+ * against memory), so every workgroup of the weight-side launches also packs a share of the
+ * activations, and the two overlap inside one launch.  Results are, bit for bit, those of the two
+ * separate calls; arguments, workspace and errors are theirs.  In addition: fewer filters in all
+ * wjobs together than tensors in pjobs -> DAB_ERR_UNSUPPORTED (call the two separately).
+ */
+int dab_prepare_layers(const dab_weight_job* wjobs /* host */, int32_t n_wjobs, const dab_pack_job* pjobs /* host */,
+                       int32_t n_pjobs, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * dab_binconv2d - binarized convolution, Section 4.3.2's I (*) W~ on packed
  * operands: cross-correlation, zero padding (a padded tap contributes 0),
  * no bias.  For every output pixel p and filter f, over the taps inside the image,

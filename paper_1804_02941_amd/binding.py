@@ -68,6 +68,7 @@ _SIGNATURES = {
     "dab_pack_activations_multi": (c_int, [c_void_p, c_int32, c_void_p]),
     "dab_binarize_weights_multi": (c_int, [c_void_p, c_int32, c_void_p, c_size_t, c_void_p]),
     "dab_binarize_weights_multi_workspace_bytes": (c_size_t, [c_void_p, c_int32]),
+    "dab_prepare_layers": (c_int, [c_void_p, c_int32, c_void_p, c_int32, c_void_p, c_size_t, c_void_p]),
     "dab_binconv2d": (c_int, [ctypes.POINTER(dab_conv_desc), c_void_p, c_void_p, c_void_p, c_void_p,
                               c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "dab_binconv2d_workspace_bytes": (c_size_t, [ctypes.POINTER(dab_conv_desc)]),
@@ -302,6 +303,15 @@ def pack_jobs(items):
 def dab_pack_activations_multi(jobs):
     """dab_pack_activations for every job of pack_jobs() in one launch."""
     _check("dab_pack_activations_multi", lib().dab_pack_activations_multi(jobs, len(jobs), _stream()))
+
+
+def dab_prepare_layers(wjobs, pjobs, ws=None):
+    """dab_binarize_weights_multi(wjobs) and dab_pack_activations_multi(pjobs) in the same launches."""
+    nbytes = lib().dab_binarize_weights_multi_workspace_bytes(wjobs, len(wjobs))
+    if nbytes and (ws is None or ws.numel() * ws.element_size() < nbytes):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    _check("dab_prepare_layers", lib().dab_prepare_layers(
+        wjobs, len(wjobs), pjobs, len(pjobs), ws.data_ptr() if nbytes else None, nbytes, _stream()))
 
 
 def dab_binconv2d(desc, A_packed, E_packed, alpha, beta, want_s1=False, out=None, ws=None):

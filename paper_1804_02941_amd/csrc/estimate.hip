@@ -31,6 +31,7 @@
 #include "dab_internal.h"
 
 #include "estimate_rows.h"
+#include "pack_act.h"
 
 namespace dab {
 
@@ -163,9 +164,8 @@ __device__ __forceinline__ const EstJob& find_job(const EstJobs& jobs, unsigned*
 // Rows of up to THREADS * ITEMS weights, one per workgroup: buckets first; where they cannot finish
 // the row, the sort by the same workgroup (SORT_HERE) or a flag for the sort kernel launched
 // behind; then the packing.
-template <int THREADS, int ITEMS, int NB, int CAP, bool SORT_HERE, int MIN_WAVES>
-__global__ __launch_bounds__(THREADS, MIN_WAVES) void binarize_rows_kernel(const EstJobs jobs) {
-    DAB_RESERVE_VGPRS();
+template <int THREADS, int ITEMS, int NB, int CAP, bool SORT_HERE>
+__device__ __forceinline__ void binarize_row_of_block(const EstJobs& jobs) {
     __shared__ SplitInfo info;
     unsigned blk0;
     const EstJob& q = find_job(jobs, &blk0);
@@ -194,6 +194,23 @@ __global__ __launch_bounds__(THREADS, MIN_WAVES) void binarize_rows_kernel(const
         if (ITEMS > 16 && f < q.F) load_row<THREADS, ITEMS>(q.W + static_cast<size_t>(f) * q.n, q.n, x);
         pack_row<THREADS, ITEMS>(q, f, &info, x);
     }
+}
+
+// The weight side of the layers in `jobs`, and beside it a share of the activation packing in
+// `packs` (none when packs.n == 0).  The two do not depend on each other and load different parts
+// of the chip: the estimation is bound by vector instructions and LDS, the packing by memory, and the
+// workgroups of one launch that share a compute unit are at different points of their work (half of
+// them pack first), so the memory stream of some runs under the arithmetic of the others.
+// Across launches on different streams this overlap does not happen (measured: the times add up).
+template <int THREADS, int ITEMS, int NB, int CAP, bool SORT_HERE, int MIN_WAVES>
+__global__ __launch_bounds__(THREADS, MIN_WAVES) void binarize_rows_kernel(const EstJobs jobs, const PackJobs packs) {
+    DAB_RESERVE_VGPRS();
+    // consecutive workgroups go to consecutive XCDs and, inside one, to consecutive compute units:
+    // the workgroups that meet on a compute unit are 256 apart, and every other one of them packs first
+    const bool pack_first = ((blockIdx.x >> 8) & 1u) != 0;
+    if (pack_first) pack_share<THREADS / 64>(packs, blockIdx.x);
+    binarize_row_of_block<THREADS, ITEMS, NB, CAP, SORT_HERE>(jobs);
+    if (!pack_first) pack_share<THREADS / 64>(packs, blockIdx.x);
 }
 
 // The rows the kernel above has flagged, kSortRowsPerGroup per workgroup (their flags are one
@@ -361,11 +378,20 @@ static size_t weight_jobs_ws_bytes(const dab_weight_job* jobs, int n_jobs) {
     return total;
 }
 
-static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, size_t ws_bytes, hipStream_t st) {
+// Relative duration of a row in its launch (measured on MI355X: 14 ns a row of the 256-thread kernel,
+// 30 of the 512-thread one, 20 + 2.2 per thousand weights of the long rows), for dealing the
+// activation packing out over the launches.
+static double row_cost(int n) {
+    return n <= kSmallMaxN ? 14.0 : (n <= kShortMaxN ? 30.0 : 20.0 + 2.2e-3 * n);
+}
+
+static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, size_t ws_bytes, hipStream_t st,
+                           const dab_pack_job* packs = nullptr, int n_packs = 0) {
     // three classes of rows, a launch each where present (a fourth, behind the long rows, for the rows they flag)
-    EstJobs smallj, shortj, longj, sortj;
-    smallj.n = shortj.n = longj.n = sortj.n = 0;
-    unsigned small_end = 0, short_end = 0, long_end = 0, sort_end = 0;
+    EstJobs cls[3], sortj;
+    unsigned end[3] = {0, 0, 0}, sort_end = 0;
+    double cost[3] = {0.0, 0.0, 0.0};
+    cls[0].n = cls[1].n = cls[2].n = sortj.n = 0;
     uint8_t* flags = static_cast<uint8_t*>(ws);
     for (int i = 0; i < n_jobs; ++i) {
         const dab_weight_job& in = jobs[i];
@@ -375,32 +401,53 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
         q.E = in.E_packed; q.ecnt = in.ecnt;
         q.F = in.F; q.C = in.C; q.T = in.kh * in.kw; q.n = in.C * q.T; q.Cw = ceil_div(in.C, 32); q.Fp = 64 * ceil_div(in.F, 64);
         const unsigned columns = static_cast<unsigned>(kNumXCD * ceil_div(q.Fp, kNumXCD));
-        if (q.n <= kSmallMaxN) {
-            small_end += columns;
-            q.blk_end = small_end;
-            smallj.job[smallj.n++] = q;
-        } else if (q.n <= kShortMaxN) {
-            short_end += columns;
-            q.blk_end = short_end;
-            shortj.job[shortj.n++] = q;
-        } else {
+        const int c = q.n <= kSmallMaxN ? 0 : (q.n <= kShortMaxN ? 1 : 2);
+        if (c == 2) {
             q.flags = flags;
             flags += (static_cast<size_t>(in.F) + 255) & ~static_cast<size_t>(255);
-            long_end += columns;
-            q.blk_end = long_end;
-            longj.job[longj.n++] = q;
+        }
+        end[c] += columns;
+        cost[c] += row_cost(q.n) * in.F;
+        q.blk_end = end[c];
+        cls[c].job[cls[c].n++] = q;
+        if (c == 2) {
             sort_end += static_cast<unsigned>(ceil_div(in.F, kSortRowsPerGroup));
             q.blk_end = sort_end;
             sortj.job[sortj.n++] = q;
         }
     }
     (void)ws_bytes;
-    if (smallj.n)
-        if (int rc = launch(binarize_rows_kernel<256, 9, 512, 256, true, 5>, dim3(small_end), dim3(256), 0, st, smallj)) return rc;
-    if (shortj.n)
-        if (int rc = launch(binarize_rows_kernel<512, 9, 2048, 256, true, 4>, dim3(short_end), dim3(512), 0, st, shortj)) return rc;
-    if (longj.n) {
-        if (int rc = launch(binarize_rows_kernel<512, 26, 2048, 512, false, 4>, dim3(long_end), dim3(512), 0, st, longj)) return rc;
+    // the activation packing, dealt out over the launches in proportion to their duration: every tensor's
+    // pixels are cut at the same fractions (a launch with fewer workgroups than tensors takes none)
+    PackJobs pk[3];
+    pk[0].n = pk[1].n = pk[2].n = 0;
+    if (n_packs > 0) {
+        double total = 0.0;
+        for (int c = 0; c < 3; ++c) {
+            if (end[c] < static_cast<unsigned>(n_packs)) cost[c] = 0.0;
+            total += cost[c];
+        }
+        if (total <= 0.0) return DAB_ERR_UNSUPPORTED;             // (the caller packs separately then)
+        double done = 0.0;
+        for (int c = 0; c < 3; ++c) {
+            if (cost[c] <= 0.0) continue;
+            const double lo = done / total, hi = (done + cost[c]) / total;
+            done += cost[c];
+            for (int i = 0; i < n_packs; ++i) {
+                const long long pixels = 1ll * packs[i].B * packs[i].H * packs[i].W;
+                const long long p0 = static_cast<long long>(lo * static_cast<double>(pixels));
+                const long long p1 = done >= total ? pixels : static_cast<long long>(hi * static_cast<double>(pixels));
+                if (p1 > p0) pk[c].job[pk[c].n++] = make_pack_job(packs[i], p0, p1);
+            }
+            if (pk[c].n) share_pack_blocks(&pk[c], end[c], c == 0 ? 4 : 8);
+        }
+    }
+    if (cls[0].n)
+        if (int rc = launch(binarize_rows_kernel<256, 9, 512, 256, true, 5>, dim3(end[0]), dim3(256), 0, st, cls[0], pk[0])) return rc;
+    if (cls[1].n)
+        if (int rc = launch(binarize_rows_kernel<512, 9, 2048, 256, true, 4>, dim3(end[1]), dim3(512), 0, st, cls[1], pk[1])) return rc;
+    if (cls[2].n) {
+        if (int rc = launch(binarize_rows_kernel<512, 26, 2048, 512, false, 4>, dim3(end[2]), dim3(512), 0, st, cls[2], pk[2])) return rc;
         if (int rc = launch(binarize_sort_kernel<1024, 13>, dim3(sort_end), dim3(1024), 0, st, sortj)) return rc;
     }
     return DAB_OK;
@@ -460,6 +507,25 @@ int dab_binarize_weights_multi(const dab_weight_job* jobs, int32_t n_jobs, void*
     if (need && (!ws || ws_bytes < need)) return DAB_ERR_WORKSPACE;
     if (need && misaligned(ws, 8)) return DAB_ERR_ALIGN;
     return run_weight_jobs(jobs, n_jobs, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int dab_prepare_layers(const dab_weight_job* wjobs, int32_t n_wjobs, const dab_pack_job* pjobs, int32_t n_pjobs, void* ws,
+                       size_t ws_bytes, void* stream) {
+    using namespace dab;
+    if (!wjobs || !pjobs) return DAB_ERR_NULL;
+    if (n_wjobs < 1 || n_pjobs < 1) return DAB_ERR_SHAPE;
+    if (n_wjobs > kMaxEstJobs || n_pjobs > kMaxPackJobs) return DAB_ERR_UNSUPPORTED;
+    for (int i = 0; i < n_wjobs; ++i)
+        if (int rc = check_weight_job(wjobs[i])) return rc;
+    for (int i = 0; i < n_pjobs; ++i)
+        if (int rc = check_pack_job(pjobs[i])) return rc;
+    const size_t need = weight_jobs_ws_bytes(wjobs, n_wjobs);
+    if (need && (!ws || ws_bytes < need)) return DAB_ERR_WORKSPACE;
+    if (need && misaligned(ws, 8)) return DAB_ERR_ALIGN;
+    long long filters = 0;
+    for (int i = 0; i < n_wjobs; ++i) filters += wjobs[i].F;
+    if (filters < n_pjobs) return DAB_ERR_UNSUPPORTED;            // fewer weight workgroups than tensors to pack
+    return run_weight_jobs(wjobs, n_wjobs, ws, ws_bytes, static_cast<hipStream_t>(stream), pjobs, n_pjobs);
 }
 
 int32_t dab_estimate_noalloc_max_filters(void) { return dab::kNoAllocMaxFilters; }

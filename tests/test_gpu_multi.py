@@ -102,3 +102,60 @@ def test_binarize_weights_multi_errors():
     assert lib.dab_binarize_weights_multi(jobs, len(jobs), None, 0, None) == dab.DAB_ERR_WORKSPACE   # long rows need the flags
     assert lib.dab_binarize_weights_multi_workspace_bytes(jobs, 3) == 0                            # short rows only
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- weight side and activation packing in the same launches
+# (B, C, H, W, with thresholds): channel counts on the aligned fast path and off it, one tensor smaller than a batch
+PACK_SHAPES = [(7, 64, 9, 11, True), (3, 37, 5, 6, True), (16, 256, 6, 6, False), (5, 100, 4, 4, True), (33, 512, 1, 1, False),
+               (2, 1024, 3, 3, True), (1, 64, 1, 1, False)]
+
+
+def make_pack_items(rng):
+    items = []
+    for (B, C, H, W, thr) in PACK_SHAPES:
+        x = rng.standard_normal((B, H, W, C)).astype(np.float32)
+        X = gu.to_gpu(x if H * W > 1 else x.reshape(B, C))
+        tau = gu.to_gpu(rng.standard_normal(C).astype(np.float32) * 0.3) if thr else None
+        A = torch.full((B, H, W, dab.words_per_pixel(C)), -1, dtype=torch.int32, device=X.device)
+        items.append((X, tau, A if H * W > 1 else A.reshape(B, -1)))
+    return items
+
+
+@pytest.mark.parametrize("subset", ["all", "short rows only", "long rows only"])
+def test_prepare_layers_equals_the_two_separate_calls(subset):
+    rng = np.random.default_rng(77)
+    w_all, _ = make_items(rng)
+    keep = {"all": lambda n: True, "short rows only": lambda n: n <= 2304, "long rows only": lambda n: n > 4608}[subset]
+    w_items = [it for it in w_all if keep(it["W"][0].numel())]
+    p_items = make_pack_items(rng)
+    dab.dab_prepare_layers(dab.weight_jobs(w_items), dab.pack_jobs(p_items))
+    torch.cuda.synchronize()
+    # the same inputs through the two separate calls
+    w_ref = [dict(W=it["W"], est=dab.estimate_outputs(it["W"].shape[0], it["W"].device),
+                  packed=dab.pack_weights_outputs(*it["W"].shape, it["W"].device)) for it in w_items]
+    p_ref = [(X, tau, torch.empty_like(A)) for (X, tau, A) in p_items]
+    dab.dab_binarize_weights_multi(dab.weight_jobs(w_ref))
+    dab.dab_pack_activations_multi(dab.pack_jobs(p_ref))
+    torch.cuda.synchronize()
+    for a, b in zip(w_items, w_ref):
+        for k in a["est"]:
+            assert torch.equal(a["est"][k], b["est"][k]), k
+        assert torch.equal(a["packed"][0], b["packed"][0]) and torch.equal(a["packed"][1], b["packed"][1])
+    for (_, _, A), (_, _, R), shape in zip(p_items, p_ref, PACK_SHAPES):
+        assert torch.equal(A, R), shape
+
+
+def test_prepare_layers_errors():
+    lib = dab.lib()
+    rng = np.random.default_rng(3)
+    w_items, _ = make_items(rng)
+    p_items = make_pack_items(rng)
+    wj, pj = dab.weight_jobs(w_items), dab.pack_jobs(p_items)
+    assert lib.dab_prepare_layers(None, 1, pj, 1, None, 0, None) == dab.DAB_ERR_NULL
+    assert lib.dab_prepare_layers(wj, 1, None, 1, None, 0, None) == dab.DAB_ERR_NULL
+    assert lib.dab_prepare_layers(wj, 0, pj, 1, None, 0, None) == dab.DAB_ERR_SHAPE
+    assert lib.dab_prepare_layers(wj, len(wj), pj, 17, None, 0, None) == dab.DAB_ERR_UNSUPPORTED
+    assert lib.dab_prepare_layers(wj, len(wj), pj, len(pj), None, 0, None) == dab.DAB_ERR_WORKSPACE   # long rows need the flags
+    few = dab.weight_jobs([dict(W=gu.to_gpu(np.ones((2, 3, 1, 1), np.float32)), est=dab.estimate_outputs(2, "cuda:0"), packed=None)])
+    assert lib.dab_prepare_layers(few, 1, pj, len(pj), None, 0, None) == dab.DAB_ERR_UNSUPPORTED    # fewer filters than tensors
+    torch.cuda.synchronize()
