@@ -203,7 +203,12 @@ __device__ __forceinline__ void binarize_row_of_block(const EstJobs& jobs) {
 // them pack first), so the memory stream of some runs under the arithmetic of the others.
 // Across launches on different streams this overlap does not happen (measured: the times add up).
 template <int THREADS, int ITEMS, int NB, int CAP, bool SORT_HERE, int MIN_WAVES>
-__global__ __launch_bounds__(THREADS, MIN_WAVES) void binarize_rows_kernel(const EstJobs jobs, const PackJobs packs) {
+__global__ __launch_bounds__(THREADS, MIN_WAVES) void binarize_rows_kernel(const EstJobs jobs) {
+    DAB_RESERVE_VGPRS();
+    binarize_row_of_block<THREADS, ITEMS, NB, CAP, SORT_HERE>(jobs);
+}
+template <int THREADS, int ITEMS, int NB, int CAP, bool SORT_HERE, int MIN_WAVES>
+__global__ __launch_bounds__(THREADS, MIN_WAVES) void prepare_rows_kernel(const EstJobs jobs, const PackJobs packs) {
     DAB_RESERVE_VGPRS();
     // consecutive workgroups go to consecutive XCDs and, inside one, to consecutive compute units:
     // the workgroups that meet on a compute unit are 256 apart, and every other one of them packs first
@@ -442,14 +447,18 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
             if (pk[c].n) share_pack_blocks(&pk[c], end[c], c == 0 ? 4 : 8);
         }
     }
+#define DAB_ROWS(C, T, I, NB, CAP, SORT, MINW) \
+    (pk[C].n ? launch(prepare_rows_kernel<T, I, NB, CAP, SORT, MINW>, dim3(end[C]), dim3(T), 0, st, cls[C], pk[C]) \
+             : launch(binarize_rows_kernel<T, I, NB, CAP, SORT, MINW>, dim3(end[C]), dim3(T), 0, st, cls[C]))
     if (cls[0].n)
-        if (int rc = launch(binarize_rows_kernel<256, 9, 512, 256, true, 5>, dim3(end[0]), dim3(256), 0, st, cls[0], pk[0])) return rc;
+        if (int rc = DAB_ROWS(0, 256, 9, 512, 256, true, 5)) return rc;
     if (cls[1].n)
-        if (int rc = launch(binarize_rows_kernel<512, 9, 2048, 256, true, 4>, dim3(end[1]), dim3(512), 0, st, cls[1], pk[1])) return rc;
+        if (int rc = DAB_ROWS(1, 512, 9, 2048, 256, true, 4)) return rc;
     if (cls[2].n) {
-        if (int rc = launch(binarize_rows_kernel<512, 26, 2048, 512, false, 4>, dim3(end[2]), dim3(512), 0, st, cls[2], pk[2])) return rc;
+        if (int rc = DAB_ROWS(2, 512, 26, 2048, 512, false, 4)) return rc;
         if (int rc = launch(binarize_sort_kernel<1024, 13>, dim3(sort_end), dim3(1024), 0, st, sortj)) return rc;
     }
+#undef DAB_ROWS
     return DAB_OK;
 }
 
