@@ -296,11 +296,13 @@ int dab_prepare_layers(const dab_weight_job* wjobs /* host */, int32_t n_wjobs, 
  *   dbg_s1     optional int32 [B][Ho][Wo][F] out: the integer s1 of every output
  *              (NULL to skip); this is what bit-exact tests compare
  *   ws         scratch of at least dab_binconv2d_workspace_bytes(d) bytes, 256-byte
- *              aligned; it holds the operands expanded for the matrix cores and is
+ *              aligned (0 bytes for most layers: the kernels then read the packed bits
+ *              directly; long reductions over many rows expand their operands into it);
  *              dead when the call's work has completed (DAB_ERR_WORKSPACE if NULL,
  *              too small or misaligned)
+ * Padding may reach or exceed the kernel extent (windows entirely in the border give 0).
  * Errors: |s1| can reach C*kh*kw, which must stay below 2^24 -> DAB_ERR_UNSUPPORTED
- * beyond (also for padding >= the kernel extent and tensors past 2^31 bytes expanded).
+ * beyond (also for tensors past 2^31 bytes expanded).
  */
 int dab_binconv2d(const dab_conv_desc* d /* host */, const uint32_t* A_packed, const uint32_t* E_packed,
                   const float* alpha, const float* beta,

@@ -1170,7 +1170,7 @@ static int check_desc(const dab_conv_desc* d) {
         return DAB_ERR_SHAPE;
     if (d->H + 2 * d->pad_h < d->kh || d->W + 2 * d->pad_w < d->kw) return DAB_ERR_SHAPE;
     if (1ll * d->C * d->kh * d->kw < 2) return DAB_ERR_SHAPE;
-    if (d->pad_h >= d->kh || d->pad_w >= d->kw) return DAB_ERR_UNSUPPORTED;   // windows entirely in the border
+    // (pad >= kernel extent: windows entirely in the border are allowed; they give s1 = sA = 0)
     return DAB_OK;
 }
 

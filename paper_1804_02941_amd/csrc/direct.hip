@@ -151,23 +151,38 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
     // so that the ballot of a block is a packed word.  Item = (k-step, half): lane n reads the mask
     // words of its four filters (fp32 output: sixteen contiguous bytes).
     {
+        // five entries of a wavefront at a time: their loads are in flight together (with eight
+        // wavefronts that is the whole panel in one round trip)
+        constexpr int kBatch = 5;
         const int n_items = g.n_ent;
-        for (int ks = wave; ks < n_items; ks += waves) {
-            const int tap = fdiv(ks, g.d_WH);
-            const int wd = h * g.WH + (ks - tap * g.WH);
-            uint32_t bits[4] = {0u, 0u, 0u, 0u};
-            if (ks < g.nk && wd < g.Cw) {
-                const uint32_t* row = E + static_cast<size_t>(tap * g.Cw + wd) * g.Fp;
-                if (BITS) {
+        for (int ks0 = wave; ks0 < n_items; ks0 += kBatch * waves) {
+            uint32_t bits[kBatch][4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) bits[j] = f0 + j * 32 + p < g.Fp ? row[f0 + j * 32 + p] : 0u;
-                } else if (f0 + 4 * p < g.Fp) {                      // (Fp is a multiple of 64: all four or none)
-                    const uint4 v = *reinterpret_cast<const uint4*>(row + f0 + 4 * p);
-                    bits[0] = v.x; bits[1] = v.y; bits[2] = v.z; bits[3] = v.w;
+            for (int u = 0; u < kBatch; ++u) {
+                const int ks = ks0 + u * waves;
+                const int tap = fdiv(min(ks, n_items - 1), g.d_WH);
+                const int wd = h * g.WH + (ks - tap * g.WH);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bits[u][j] = 0u;
+                if (ks < g.nk && wd < g.Cw) {
+                    const uint32_t* row = E + static_cast<size_t>(tap * g.Cw + wd) * g.Fp;
+                    if (BITS) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) bits[u][j] = f0 + j * 32 + p < g.Fp ? row[f0 + j * 32 + p] : 0u;
+                    } else if (f0 + 4 * p < g.Fp) {                  // (Fp is a multiple of 64: all four or none)
+                        const uint4 v = *reinterpret_cast<const uint4*>(row + f0 + 4 * p);
+                        bits[u][0] = v.x; bits[u][1] = v.y; bits[u][2] = v.z; bits[u][3] = v.w;
+                    }
                 }
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) panel[(ks * 4 + j) * 64 + lane] = expand_e(bits[j]);
+            for (int u = 0; u < kBatch; ++u) {
+                const int ks = ks0 + u * waves;
+                if (ks < n_items) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) panel[(ks * 4 + j) * 64 + lane] = expand_e(bits[u][j]);
+                }
+            }
         }
     }
 

@@ -109,12 +109,12 @@ int main(int argc, char** argv) {
         } else {
             d.H = pick(1, 70); d.W = pick(1, 70);
             d.kh = pick(1, 7); d.kw = pick(1, 7);
-            d.pad_h = pick(0, 3); d.pad_w = pick(0, 3);
+            d.pad_h = pick(0, 4); d.pad_w = pick(0, 4);             // (also beyond the kernel extent)
             d.stride_h = pick(1, 3); d.stride_w = pick(1, 3);
         }
         if (rnd(50) == 0) d.B = 0;               // an invalid descriptor now and then
         if (rnd(50) == 0) d.kh = d.H + 2 * d.pad_h + 1;
-        const bool valid = d.B >= 1 && d.kh <= d.H + 2 * d.pad_h && d.kw <= d.W + 2 * d.pad_w && d.pad_h < d.kh && d.pad_w < d.kw &&
+        const bool valid = d.B >= 1 && d.kh <= d.H + 2 * d.pad_h && d.kw <= d.W + 2 * d.pad_w &&
                            1ll * d.C * d.kh * d.kw >= 2;
         if (!valid) {
             // entry points must refuse it, whatever else

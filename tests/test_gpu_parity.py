@@ -425,3 +425,22 @@ def test_sign_split_estimate_and_layer(n):
     y_ref = got["alpha"].astype(np.float64)[None, :] * (2 * agree - n)
     tol = gu.Y_RTOL * np.maximum(np.abs(y_ref), got["alpha"].astype(np.float64)[None, :] * n)
     assert np.all(np.abs(Y.cpu().numpy() - y_ref) <= tol)
+
+
+# (name, B, C, H, W, F, k, pad, stride): padding as wide as the kernel or wider, on each of the product kernels
+BORDER_LAYERS = [("persistent k1p1", 6, 64, 12, 13, 64, 1, 1, 1), ("persistent k2p2", 6, 64, 12, 13, 64, 2, 2, 1),
+                 ("persistent k3p3", 5, 96, 9, 8, 100, 3, 3, 1), ("persistent k1p2s2", 40, 128, 9, 9, 130, 1, 2, 2),
+                 ("block k1p1", 1, 64, 6, 6, 32, 1, 1, 1), ("block k2p3", 2, 33, 5, 5, 7, 2, 3, 1),
+                 ("workspace k1p1", 64, 4096, 8, 8, 512, 1, 1, 1)]
+
+
+@pytest.mark.parametrize("case", BORDER_LAYERS, ids=lambda c: c[0])
+def test_padding_that_reaches_the_kernel_extent(case):
+    """Windows that lie entirely in the zero border: s1 = sA = 0 there, everything else as usual."""
+    import zlib
+    name, B, C, H, W, F, k, p, s = case
+    L = Layer(name, C=C, H=H, W=W, F=F, kh=k, kw=k, pad=p, stride=s)
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    x = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    w = (0.05 * rng.standard_normal((F, C, k, k)) + 0.01).astype(np.float32)
+    gu.check_layer(L, x, w, tau=None)

@@ -149,3 +149,14 @@ def test_errors():
     assert lib.dab_wbin_conv2d(ctypes.byref(d), None, p, p, p, p, p, 1 << 20, None) == dab.DAB_ERR_NULL
     assert lib.dab_wbin_fc(0, 16, 8, p, p, p, p, p, p, 1 << 20, None) == dab.DAB_ERR_SHAPE
     assert lib.dab_wbin_conv2d_workspace_bytes(ctypes.byref(d)) > 0
+
+
+@pytest.mark.parametrize("k,pad,stride", [(1, 1, 1), (2, 2, 1), (3, 3, 2)])
+def test_padding_that_reaches_the_kernel_extent(k, pad, stride):
+    """Windows that lie entirely in the zero border give zero."""
+    import zlib
+    L = Layer(f"wbin_k{k}p{pad}", C=96, H=9, W=8, F=70, kh=k, kw=k, pad=pad, stride=stride)
+    rng = np.random.default_rng(zlib.crc32(L.name.encode()))
+    x = real_inputs(rng, (4, L.C, L.H, L.W))
+    W = weight_rows(rng, L.F, L.n, "gauss").reshape(L.F, L.C, k, k)
+    check_wbin(L, x, W)
