@@ -209,7 +209,8 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
 
 /*
  * dab_binarize_weights_multi - the whole weight side of several layers in a few launches (one per
- * class of row length present: up to 2304 weights, up to 4608, longer; plus one behind the longer rows):
+ * class of row length present: up to 2304 weights, up to 4608, up to 9216, longer; plus one behind them
+ * for the rows handed to the sort):
  * for every job, dab_estimate_alpha_beta (or, with K_prev, dab_estimate_alpha_beta_bounded) of its
  * filters followed by dab_pack_weights of the resulting masks.  Section 4.3.1 handles all filters of
  * a layer together; filters of different layers are just as independent, so they share the
@@ -222,7 +223,8 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
  *             E_packed and ecnt may both be NULL (estimation only); K_prev and alpha_is_upper_prev
  *             may both be NULL (unrestricted search), else max_change >= 0 bounds the split's move.
  *   ws        scratch of dab_binarize_weights_multi_workspace_bytes(jobs, n_jobs) bytes, 8-byte aligned
- *             (one flag per filter of the jobs with long rows; 0 when every row has at most 4608 weights)
+ *             (one flag per filter of the jobs whose unfinished rows go to the sort kernel; 0 for a
+ *             few layers with rows of at most 4608 weights, which are finished in their own launch)
  * Errors: per job as in the separate calls (rows above dab_estimate_max_n(), more than 128 taps with
  * packing -> DAB_ERR_UNSUPPORTED); more than 16 jobs -> DAB_ERR_UNSUPPORTED; ws missing or too
  * small -> DAB_ERR_WORKSPACE; ws not 8-byte aligned -> DAB_ERR_ALIGN.

@@ -360,6 +360,7 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
 // ---------------------------------------------------------------- host side of the multi-layer call
 constexpr int kSmallMaxN = 256 * 9;                // rows up to here: 256 threads and 512 buckets per row
 constexpr int kShortMaxN = 512 * 9;                // rows up to here: 512 threads and 2048 buckets, sorted in the same kernel if need be
+constexpr int kMidMaxN = 512 * 18;                 // rows up to here: 18 weights per thread, longer ones 26; both hand rows over to the sort kernel
 
 static int check_weight_job(const dab_weight_job& j) {
     if (!j.W || !j.alpha || !j.beta || !j.K || !j.thr_val || !j.thr_idx || !j.alpha_is_upper) return DAB_ERR_NULL;
@@ -376,10 +377,34 @@ static int check_weight_job(const dab_weight_job& j) {
     return DAB_OK;
 }
 
+// Rows up to 4608 weights can be finished in one launch: the workgroup that cannot finish a row with
+// the buckets sorts it itself.  Flagging such rows for the sort kernel instead frees the LDS of the
+// in-kernel sort, and more workgroups share a compute unit (seven instead of five of the 256-thread
+// kernel, three instead of two of the 512-thread one).  That is done where it pays for the extra launch:
+// for a class with many rows, and for the short rows whenever the sort kernel is launched anyway.
+struct HandOver {
+    bool small, medium;        // rows up to 2304 weights, rows of 2305 .. 4608
+};
+static HandOver hand_over_plan(const dab_weight_job* jobs, int n_jobs) {
+    long long small = 0, medium = 0, longer = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const long long n = 1ll * jobs[i].C * jobs[i].kh * jobs[i].kw;
+        (n <= kSmallMaxN ? small : (n <= kShortMaxN ? medium : longer)) += jobs[i].F;
+    }
+    HandOver h;
+    h.medium = medium >= 6 * kNumCU;
+    h.small = small >= 6 * kNumCU || (small > 0 && (longer > 0 || h.medium));
+    return h;
+}
+
 static size_t weight_jobs_ws_bytes(const dab_weight_job* jobs, int n_jobs) {
     size_t total = 0;
-    for (int i = 0; i < n_jobs; ++i)
-        if (1ll * jobs[i].C * jobs[i].kh * jobs[i].kw > kShortMaxN) total += (static_cast<size_t>(jobs[i].F) + 255) & ~static_cast<size_t>(255);
+    const HandOver h = hand_over_plan(jobs, n_jobs);
+    for (int i = 0; i < n_jobs; ++i) {
+        const long long n = 1ll * jobs[i].C * jobs[i].kh * jobs[i].kw;
+        if (n > kShortMaxN || (n > kSmallMaxN ? h.medium : h.small))
+            total += (static_cast<size_t>(jobs[i].F) + 255) & ~static_cast<size_t>(255);
+    }
     return total;
 }
 
@@ -393,11 +418,14 @@ static double row_cost(int n) {
 static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, size_t ws_bytes, hipStream_t st,
                            const dab_pack_job* packs = nullptr, int n_packs = 0) {
     // three classes of rows, a launch each where present (a fourth, behind the long rows, for the rows they flag)
-    EstJobs cls[3], sortj;
-    unsigned end[3] = {0, 0, 0}, sort_end = 0;
-    double cost[3] = {0.0, 0.0, 0.0};
-    cls[0].n = cls[1].n = cls[2].n = sortj.n = 0;
+    constexpr int kClasses = 4;
+    EstJobs cls[kClasses], sortj;
+    unsigned end[kClasses] = {0, 0, 0, 0}, sort_end = 0;
+    double cost[kClasses] = {0.0, 0.0, 0.0, 0.0};
+    for (int c = 0; c < kClasses; ++c) cls[c].n = 0;
+    sortj.n = 0;
     uint8_t* flags = static_cast<uint8_t*>(ws);
+    const HandOver hand = hand_over_plan(jobs, n_jobs);
     for (int i = 0; i < n_jobs; ++i) {
         const dab_weight_job& in = jobs[i];
         EstJob q{};
@@ -406,8 +434,9 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
         q.E = in.E_packed; q.ecnt = in.ecnt;
         q.F = in.F; q.C = in.C; q.T = in.kh * in.kw; q.n = in.C * q.T; q.Cw = ceil_div(in.C, 32); q.Fp = 64 * ceil_div(in.F, 64);
         const unsigned columns = static_cast<unsigned>(kNumXCD * ceil_div(q.Fp, kNumXCD));
-        const int c = q.n <= kSmallMaxN ? 0 : (q.n <= kShortMaxN ? 1 : 2);
-        if (c == 2) {
+        const int c = q.n <= kSmallMaxN ? 0 : (q.n <= kShortMaxN ? 1 : (q.n <= kMidMaxN ? 2 : 3));
+        const bool flagged = c >= 2 || (c == 1 ? hand.medium : hand.small);
+        if (flagged) {
             q.flags = flags;
             flags += (static_cast<size_t>(in.F) + 255) & ~static_cast<size_t>(255);
         }
@@ -415,7 +444,7 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
         cost[c] += row_cost(q.n) * in.F;
         q.blk_end = end[c];
         cls[c].job[cls[c].n++] = q;
-        if (c == 2) {
+        if (flagged) {
             sort_end += static_cast<unsigned>(ceil_div(in.F, kSortRowsPerGroup));
             q.blk_end = sort_end;
             sortj.job[sortj.n++] = q;
@@ -424,17 +453,17 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
     (void)ws_bytes;
     // the activation packing, dealt out over the launches in proportion to their duration: every tensor's
     // pixels are cut at the same fractions (a launch with fewer workgroups than tensors takes none)
-    PackJobs pk[3];
-    pk[0].n = pk[1].n = pk[2].n = 0;
+    PackJobs pk[kClasses];
+    for (int c = 0; c < kClasses; ++c) pk[c].n = 0;
     if (n_packs > 0) {
         double total = 0.0;
-        for (int c = 0; c < 3; ++c) {
+        for (int c = 0; c < kClasses; ++c) {
             if (end[c] < static_cast<unsigned>(n_packs)) cost[c] = 0.0;
             total += cost[c];
         }
         if (total <= 0.0) return DAB_ERR_UNSUPPORTED;             // (the caller packs separately then)
         double done = 0.0;
-        for (int c = 0; c < 3; ++c) {
+        for (int c = 0; c < kClasses; ++c) {
             if (cost[c] <= 0.0) continue;
             const double lo = done / total, hi = (done + cost[c]) / total;
             done += cost[c];
@@ -451,11 +480,14 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
     (pk[C].n ? launch(prepare_rows_kernel<T, I, NB, CAP, SORT, MINW>, dim3(end[C]), dim3(T), 0, st, cls[C], pk[C]) \
              : launch(binarize_rows_kernel<T, I, NB, CAP, SORT, MINW>, dim3(end[C]), dim3(T), 0, st, cls[C]))
     if (cls[0].n)
-        if (int rc = DAB_ROWS(0, 256, 9, 512, 256, true, 5)) return rc;
+        if (int rc = hand.small ? DAB_ROWS(0, 256, 9, 512, 256, false, 7) : DAB_ROWS(0, 256, 9, 512, 256, true, 5)) return rc;
     if (cls[1].n)
-        if (int rc = DAB_ROWS(1, 512, 9, 2048, 256, true, 4)) return rc;
-    if (cls[2].n) {
-        if (int rc = DAB_ROWS(2, 512, 26, 2048, 512, false, 4)) return rc;
+        if (int rc = hand.medium ? DAB_ROWS(1, 512, 9, 2048, 256, false, 6) : DAB_ROWS(1, 512, 9, 2048, 256, true, 4)) return rc;
+    if (cls[2].n)
+        if (int rc = DAB_ROWS(2, 512, 18, 2048, 512, false, 6)) return rc;
+    if (cls[3].n)
+        if (int rc = DAB_ROWS(3, 512, 26, 2048, 512, false, 4)) return rc;
+    if (sortj.n) {
         if (int rc = launch(binarize_sort_kernel<1024, 13>, dim3(sort_end), dim3(1024), 0, st, sortj)) return rc;
     }
 #undef DAB_ROWS

@@ -159,3 +159,31 @@ def test_prepare_layers_errors():
     few = dab.weight_jobs([dict(W=gu.to_gpu(np.ones((2, 3, 1, 1), np.float32)), est=dab.estimate_outputs(2, "cuda:0"), packed=None)])
     assert lib.dab_prepare_layers(few, 1, pj, len(pj), None, 0, None) == dab.DAB_ERR_UNSUPPORTED    # fewer filters than tensors
     torch.cuda.synchronize()
+
+
+def test_many_medium_rows_are_handed_to_the_sort_kernel():
+    """From 1536 rows of 2305..4608 weights on, rows the buckets cannot finish are flagged for the sort kernel
+    instead of being sorted in place; results are those of the separate calls, degenerate rows included."""
+    rng = np.random.default_rng(99)
+    F, n = 1600, 2400
+    W = weight_rows(rng, F, n, "gauss")
+    W[3] = 0.5                                                     # a constant row
+    W[10::97] = np.round(W[10::97] * 8) / 8                        # rows with few distinct values
+    W2 = weight_rows(rng, 40, 4608, "mixture")
+    items = []
+    for w, shape in ((W, (F, 800, 1, 3)), (W2, (40, 512, 3, 3))):
+        Wt = gu.to_gpu(w.reshape(shape))
+        items.append(dict(W=Wt, est=dab.estimate_outputs(shape[0], Wt.device), packed=dab.pack_weights_outputs(*shape, Wt.device)))
+    jobs = dab.weight_jobs(items)
+    assert dab.lib().dab_binarize_weights_multi_workspace_bytes(jobs, len(jobs)) > 0
+    dab.dab_binarize_weights_multi(jobs)
+    torch.cuda.synchronize()
+    for it, w in zip(items, (W, W2)):
+        ref = dab.dab_estimate_alpha_beta(it["W"].reshape(it["W"].shape[0], -1))
+        E, ecnt = dab.dab_pack_weights(it["W"], ref["thr_val"], ref["thr_idx"], ref["alpha_is_upper"])
+        torch.cuda.synchronize()
+        for k in ref:
+            assert torch.equal(it["est"][k], ref[k]), k
+        assert torch.equal(E, it["packed"][0]) and torch.equal(ecnt, it["packed"][1])
+    got = {k: v.cpu().numpy() for k, v in items[0]["est"].items()}
+    gu.check_estimate(W[:64], {k: v[:64] for k, v in got.items()})
