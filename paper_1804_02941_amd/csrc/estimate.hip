@@ -22,12 +22,14 @@
 //      index up to which they belong to the lower group (recovered from the unsorted row,
 //      so the sort itself carries no indices).
 //
-// Rows of more than 256 weights first go through a search that needs no full sort (further down:
-// value buckets with exact sums, a bound on D inside every bucket, exact ranking of the few
-// elements that can hold the arg-max), and only rows it cannot finish are sorted: by the same
-// workgroup for rows below 4096 weights (one launch), and for longer rows by
+// Rows of more than 256 weights first go through a search that needs no full sort (bucket_row in
+// estimate_rows.h, beside the sort: value buckets with exact sums, a bound on D inside every bucket,
+// exact ranking of the few elements that can hold the arg-max), and only rows it cannot finish are
+// sorted: by the same workgroup for rows below 4096 weights (one launch), and for longer rows by
 // the sort kernel launched behind, which then only works on the rows handed over (and does every
-// row when the caller gives no workspace for the hand-over flags).
+// row when the caller gives no workspace for the hand-over flags).  This file holds the kernels
+// around the two row procedures, the calls that take the filters of several layers at once (and pack
+// each filter's mask, and a share of the layers' activations, in the same launches) and the host side.
 #include "dab_internal.h"
 
 #include "estimate_rows.h"
