@@ -193,7 +193,7 @@ __device__ __forceinline__ void binarize_row_of_block(const EstJobs& jobs) {
     }
     if (q.E && done) {
         // many elements per thread: read them again (from L2) rather than hold them through the estimation
-        if (ITEMS > 16 && f < q.F) load_row<THREADS, ITEMS>(q.W + static_cast<size_t>(f) * q.n, q.n, x);
+        if (ITEMS > 32 && f < q.F) load_row<THREADS, ITEMS>(q.W + static_cast<size_t>(f) * q.n, q.n, x);
         pack_row<THREADS, ITEMS>(q, f, &info, x);
     }
 }

@@ -369,6 +369,7 @@ __device__ __forceinline__ bool bucket_row(const float (&x)[ITEMS], int n, int f
     __shared__ double w_d[NW];
     __shared__ Best wave_best[NW];
     __shared__ uint32_t nlist_s, ncb_s, r_s, wkey_s;
+    __shared__ int cb_lo_s, cb_hi_s;                               // first and last candidate bucket
     static_assert(CAP <= THREADS && CAP < 1024 && THREADS * ITEMS <= 65536 && ITEMS <= 32,
                   "a candidate per thread, 10-bit counts, 16-bit indices, a flag bit per element");
 
@@ -384,7 +385,7 @@ __device__ __forceinline__ bool bucket_row(const float (&x)[ITEMS], int n, int f
     wave_min_max_f32(mn, mx);
     if (lane == 63) { w_min[wave] = mn; w_max[wave] = mx; }
     for (int b = tid; b < NB; b += THREADS) { cnt[b] = 0u; sum[b] = 0ull; cand[b] = 0; }
-    if (tid == 0) { nlist_s = 0u; ncb_s = 0u; }
+    if (tid == 0) { nlist_s = 0u; ncb_s = 0u; cb_lo_s = NB; cb_hi_s = -1; }
     __syncthreads();
     for (int w = 0; w < NW; ++w) { mn = fminf(mn, w_min[w]); mx = fmaxf(mx, w_max[w]); }
     if (!(mx > mn) || !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY)) return false;   // constant row (or not finite)
@@ -546,33 +547,43 @@ __device__ __forceinline__ bool bucket_row(const float (&x)[ITEMS], int n, int f
                 cand[b] = static_cast<uint8_t>(entry + 1u);
                 ctab[entry] = min(start, 0xFFFFu);
             }
+            atomicMin(&cb_lo_s, b);
+            atomicMax(&cb_hi_s, b);
         }
     }
     __syncthreads();
     const uint32_t nc = nlist_s;
     if (nc > CAP || nc == 0 || ncb_s > kMaxCandBuckets) return false;
 
-    // ---- the candidates' elements, filed into the segment of their bucket: every thread flags its
-    // own first (the LDS reads in flight together), then files the few it has
+    // ---- the candidates' elements, filed into the segment of their bucket.  The candidates are
+    // neighbours as a rule, so every thread first flags the elements whose bucket lies between the
+    // first and the last candidate (two compares on the bucket coordinate: for t >= 0 the
+    // truncation is the floor, so lo <= int(t) <= hi is lo <= t < hi + 1), then looks up the few
+    // it has flagged and files those whose bucket is a candidate
     {
+        const float tlo = static_cast<float>(cb_lo_s);
+        const float thi = cb_hi_s >= NB - 1 ? INFINITY : static_cast<float>(cb_hi_s + 1);   // (the last bucket also takes what rounds past it)
         uint32_t flags = 0;
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             float xv = x[j];
-            DAB_OPAQUE_F32(xv);                                    // (the bucket is computed again, not kept since the histogram)
-            if (tid + j * THREADS < n && cand[bucket_of(xv)]) flags |= 1u << j;
-            if (j % 8 == 7) __builtin_amdgcn_sched_barrier(0);     // eight reads in flight are enough
+            DAB_OPAQUE_F32(xv);                                    // (the coordinate is computed again, not kept since the histogram)
+            const float t = (xv - mn) * bscalef;
+            if (tid + j * THREADS < n && t >= tlo && t < thi) flags |= 1u << j;
         }
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             if ((flags >> j) & 1u) {
                 const int b = bucket_of(x[j]);
-                const uint32_t old = atomicAdd(&ctab[cand[b] - 1], 1u << 16);
-                const uint32_t slot = (old & 0xFFFFu) + (old >> 16);
-                lkey[slot] = float_to_key(x[j]);
-                lq[slot] = fixed_of(x[j]);
-                lb[slot] = static_cast<uint16_t>(b);
-                lidx[slot] = static_cast<uint16_t>(tid + j * THREADS);
+                const uint32_t cb = cand[b];
+                if (cb) {
+                    const uint32_t old = atomicAdd(&ctab[cb - 1], 1u << 16);
+                    const uint32_t slot = (old & 0xFFFFu) + (old >> 16);
+                    lkey[slot] = float_to_key(x[j]);
+                    lq[slot] = fixed_of(x[j]);
+                    lb[slot] = static_cast<uint16_t>(b);
+                    lidx[slot] = static_cast<uint16_t>(tid + j * THREADS);
+                }
             }
         }
     }
@@ -594,13 +605,26 @@ __device__ __forceinline__ bool bucket_row(const float (&x)[ITEMS], int n, int f
         const int q1 = q0 + static_cast<int>(cnt[b + 1] - cnt[b]);
         uint32_t counts = 0;
         long long ps = 0;
-        for (int q = q0; q < q1; ++q) {
-            const uint32_t kq = lkey[q];
-            const bool lt = kq < key;
-            const bool eq = kq == key;
-            const bool le = lt || (eq && q <= e);
-            counts += (le ? 1u : 0u) + (lt ? 1u << 10 : 0u) + ((eq && lidx[q] < my_idx) ? 1u << 20 : 0u);
-            ps += le ? lq[q] : 0ll;
+        // four entries per trip, their reads in flight together (a trip is one LDS round trip)
+        for (int q = q0; q < q1; q += 4) {
+            uint32_t kq[4], iq[4];
+            long long vq[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int qq = min(q + u, q1 - 1);
+                kq[u] = lkey[qq];
+                iq[u] = lidx[qq];
+                vq[u] = lq[qq];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool in = q + u < q1;
+                const bool lt = in && kq[u] < key;
+                const bool eq = in && kq[u] == key;
+                const bool le = lt || (eq && q + u <= e);
+                counts += (le ? 1u : 0u) + (lt ? 1u << 10 : 0u) + ((eq && iq[u] < my_idx) ? 1u << 20 : 0u);
+                ps += le ? vq[u] : 0ll;
+            }
         }
         const uint32_t within = counts & 1023u, less = (counts >> 10) & 1023u;
         my_key = key;
