@@ -103,7 +103,7 @@ struct BlockGeom {
 struct BlockPlan {
     DirectGeom g;
     BlockGeom bg;
-    int waves;
+    int waves, depth;   // wavefronts per block, k-steps per load burst
     bool pad;
     unsigned grid;
 };

@@ -493,13 +493,12 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
 // trunk, a late ResNet stage at small batch) are latency problems: too few tiles for the
 // persistent kernel above.  Here one workgroup owns one 32-pixel x 32-filter block and its
 // wavefronts take consecutive shares of the reduction.  Both operands are read as packed bits
-// straight from memory (L2), eight k-steps per burst into two register sets, expanded in
+// straight from memory (L2), DEPTH k-steps per burst into two register sets, expanded in
 // registers and multiplied; the wavefronts' exact partial sums (and their counts of ones for
 // sA) are added through LDS.  Workgroups that share a block of filters run on the same XCD, so
 // the filter words are fetched into one L2 only.
-constexpr int kBlkDepth = 8;
 
-template <bool PAD, bool BITS, int WAVES>
+template <bool PAD, bool BITS, int WAVES, int DEPTH>
 __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectGeom g, const BlockGeom bg,
                                                                    const uint32_t* __restrict__ A,
                                                                    const uint32_t* __restrict__ E,
@@ -551,11 +550,11 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectG
     // this wavefront's k-steps [k0, k1): k-step ks = tap * WH + j multiplies word h*WH + j of the tap
     const int per = (g.nk + WAVES - 1) / WAVES;
     const int k0 = min(wave * per, g.nk), k1 = min(k0 + per, g.nk);
-    uint32_t xa[2][kBlkDepth], xe[2][kBlkDepth];
-    bool va[2][kBlkDepth];
+    uint32_t xa[2][DEPTH], xe[2][DEPTH];
+    bool va[2][DEPTH];
     auto fetch = [&](int set, int first) {
 #pragma unroll
-        for (int d = 0; d < kBlkDepth; ++d) {
+        for (int d = 0; d < DEPTH; ++d) {
             const int ks = first + d;                              // (wavefront-uniform)
             const int tap = fdiv(min(ks, g.nk - 1), g.d_WH);
             const int j = min(ks, g.nk - 1) - tap * g.WH;
@@ -580,7 +579,7 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectG
     int ones = 0;
     auto multiply = [&](int set) {
 #pragma unroll
-        for (int d = 0; d < kBlkDepth; ++d) {
+        for (int d = 0; d < DEPTH; ++d) {
             const uint32_t x = xa[set][d];
             ones += __builtin_popcount(x);                         // (words that were not loaded are zero)
             const v4i a = expand_a(x, va[set][d] ? k8 : 0u, va[set][d] ? k2 : 0u);
@@ -590,10 +589,10 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectG
         }
     };
     fetch(0, k0);
-    for (int st = k0; st < k1; st += 2 * kBlkDepth) {
-        fetch(1, st + kBlkDepth);
+    for (int st = k0; st < k1; st += 2 * DEPTH) {
+        fetch(1, st + DEPTH);
         multiply(0);
-        fetch(0, st + 2 * kBlkDepth);
+        fetch(0, st + 2 * DEPTH);
         multiply(1);
     }
 #pragma unroll
@@ -734,26 +733,33 @@ bool plan_block(const dab_conv_desc& d, BlockPlan* pl, bool large) {
     const int tiles256 = ceil_div(g.M, 256) * ceil_div(d.F, kDirNTile);
     if (large ? blocks > 2048 : (tiles256 * 2 > kNumCU || blocks > 512)) return false;
     pl->grid = static_cast<unsigned>(ceil_div(g.M, 32) * bg.fb_per_xcd * kNumXCD);
-    // enough wavefronts per block that each keeps a few k-steps of the reduction
+    // enough wavefronts per block that each keeps a few k-steps of the reduction; the burst such that
+    // two of them hold a wavefront's whole share where that is short (one round trip to memory)
     pl->waves = g.nk >= 32 ? 8 : 2;
+    const int share = ceil_div(g.nk, pl->waves);
+    pl->depth = share <= 8 ? 4 : (share > 16 && share <= 26 ? 13 : 8);
     return true;
 }
 
-template <bool PAD, bool BITS, int WAVES>
+template <bool PAD, bool BITS, int WAVES, int DEPTH>
 static int launch_block_as(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
                            const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits) {
-    return launch(binconv_block_kernel<PAD, BITS, WAVES>, dim3(pl.grid), dim3(64 * WAVES), 0, st, pl.g, pl.bg, A, E, alpha,
+    return launch(binconv_block_kernel<PAD, BITS, WAVES, DEPTH>, dim3(pl.grid), dim3(64 * WAVES), 0, st, pl.g, pl.bg, A, E, alpha,
                   beta, Y, dbg_s1, tau_out, out_bits);
 }
 
 int launch_block(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
                  const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits) {
     const bool bits = Y == nullptr;
-#define DAB_X(PAD, BITS, WAVES) \
-    if (pl.pad == PAD && bits == BITS && pl.waves == WAVES) \
-        return launch_block_as<PAD, BITS, WAVES>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
-    DAB_X(false, false, 8) DAB_X(false, true, 8) DAB_X(true, false, 8) DAB_X(true, true, 8)
-    DAB_X(false, false, 2) DAB_X(false, true, 2) DAB_X(true, false, 2) DAB_X(true, true, 2)
+#define DAB_X(WAVES, DEPTH)                                                                                              \
+    if (pl.waves == WAVES && pl.depth == DEPTH) {                                                                        \
+        if (pl.pad)                                                                                                      \
+            return bits ? launch_block_as<true, true, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits)   \
+                        : launch_block_as<true, false, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits); \
+        return bits ? launch_block_as<false, true, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits)      \
+                    : launch_block_as<false, false, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);    \
+    }
+    DAB_X(8, 4) DAB_X(8, 8) DAB_X(8, 13) DAB_X(2, 4) DAB_X(2, 8)
 #undef DAB_X
     return DAB_ERR_UNSUPPORTED;
 }
