@@ -103,7 +103,7 @@ struct BlockGeom {
 struct BlockPlan {
     DirectGeom g;
     BlockGeom bg;
-    int waves, depth;   // wavefronts per block, k-steps per load burst
+    int waves, depth, lw;   // wavefronts per block, k-steps per load burst, activation words per load
     bool pad;
     unsigned grid;
 };

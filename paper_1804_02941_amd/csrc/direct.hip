@@ -498,7 +498,7 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
 // sA) are added through LDS.  Workgroups that share a block of filters run on the same XCD, so
 // the filter words are fetched into one L2 only.
 
-template <bool PAD, bool BITS, int WAVES, int DEPTH>
+template <bool PAD, bool BITS, int WAVES, int DEPTH, int LW>
 __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectGeom g, const BlockGeom bg,
                                                                    const uint32_t* __restrict__ A,
                                                                    const uint32_t* __restrict__ E,
@@ -547,27 +547,40 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectG
     const int fcol = fb * 32 + p;                                  // this lane's filter (as the B operand's column)
     const uint32_t ecol = fcol < g.Fp ? static_cast<uint32_t>(fcol * 4) : kOob;
 
-    // this wavefront's k-steps [k0, k1): k-step ks = tap * WH + j multiplies word h*WH + j of the tap
-    const int per = (g.nk + WAVES - 1) / WAVES;
+    // this wavefront's k-steps [k0, k1): k-step ks = tap * WH + j multiplies word h*WH + j of the tap.
+    // A lane's activation words of a tap are neighbours in memory: with LW = 4 (WH a multiple of four)
+    // one 16-byte load brings four k-steps, and a wavefront's load touches a quarter of the cache
+    // lines per k-step (its lanes read different pixels, a line each).
+    static_assert((LW == 1 || LW == 4) && DEPTH % LW == 0, "whole loads per burst");
+    constexpr int NL = DEPTH / LW;
+    const int per = (g.nk + WAVES * LW - 1) / (WAVES * LW) * LW;
     const int k0 = min(wave * per, g.nk), k1 = min(k0 + per, g.nk);
-    uint32_t xa[2][DEPTH], xe[2][DEPTH];
-    bool va[2][DEPTH];
+    typename WordsOf<LW>::type xa[2][NL];
+    uint32_t xe[2][DEPTH];
+    bool va[2][NL];
     auto fetch = [&](int set, int first) {
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-            const int ks = first + d;                              // (wavefront-uniform)
+        for (int l = 0; l < NL; ++l) {
+            const int ks = first + l * LW;                         // (wavefront-uniform; a multiple of LW)
             const int tap = fdiv(min(ks, g.nk - 1), g.d_WH);
-            const int j = min(ks, g.nk - 1) - tap * g.WH;
+            const int j = min(ks, g.nk - LW) - tap * g.WH;
             const int ky = fdiv(tap, bg.d_kw);
             const int kx = tap - ky * g.kw;
             const int wd = h * g.WH + j;
-            const bool live = ks < k1 && wd < g.Cw;
+            const bool live = ks < k1 && wd < g.Cw;                // (LW = 4: Cw = 2 WH, all four words or none)
             const bool in = live && (!PAD || ((tbits >> (tap & 31)) & 1u));
             const uint32_t aoff = base + static_cast<uint32_t>(((ky * g.W + kx) * g.Cw + j) * 4);
-            const uint32_t eoff = ecol + static_cast<uint32_t>((tap * g.Cw + wd) * g.Fp * 4);
-            xa[set][d] = __builtin_amdgcn_raw_buffer_load_b32(arsrc, static_cast<int>(in ? aoff : kOob), 0, 0);
-            xe[set][d] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, static_cast<int>(live ? eoff : kOob), 0, 0);
-            va[set][d] = in;
+            if constexpr (LW == 1) {
+                xa[set][l] = __builtin_amdgcn_raw_buffer_load_b32(arsrc, static_cast<int>(in ? aoff : kOob), 0, 0);
+            } else {
+                xa[set][l] = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(arsrc, static_cast<int>(in ? aoff : kOob), 0, 0));
+            }
+#pragma unroll
+            for (int u = 0; u < LW; ++u) {
+                const uint32_t eoff = ecol + static_cast<uint32_t>((tap * g.Cw + wd + u) * g.Fp * 4);
+                xe[set][l * LW + u] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, static_cast<int>(live ? eoff : kOob), 0, 0);
+            }
+            va[set][l] = in;
         }
     };
     uint32_t k8, k2;
@@ -580,9 +593,9 @@ __global__ __launch_bounds__(64 * WAVES) void binconv_block_kernel(const DirectG
     auto multiply = [&](int set) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            const uint32_t x = xa[set][d];
+            const uint32_t x = word_of<LW>(xa[set][d / LW], d % LW);
             ones += __builtin_popcount(x);                         // (words that were not loaded are zero)
-            const v4i a = expand_a(x, va[set][d] ? k8 : 0u, va[set][d] ? k2 : 0u);
+            const v4i a = expand_a(x, va[set][d / LW] ? k8 : 0u, va[set][d / LW] ? k2 : 0u);
             const uint4 e = expand_e(xe[set][d]);
             const v4i bv = {static_cast<int>(e.x), static_cast<int>(e.y), static_cast<int>(e.z), static_cast<int>(e.w)};
             acc = mfma_fp4(a, bv, acc);                            // (a k-step past k1 multiplies zeros)
@@ -736,30 +749,33 @@ bool plan_block(const dab_conv_desc& d, BlockPlan* pl, bool large) {
     // enough wavefronts per block that each keeps a few k-steps of the reduction; the burst such that
     // two of them hold a wavefront's whole share where that is short (one round trip to memory)
     pl->waves = g.nk >= 32 ? 8 : 2;
-    const int share = ceil_div(g.nk, pl->waves);
-    pl->depth = share <= 8 ? 4 : (share > 16 && share <= 26 ? 13 : 8);
+    pl->lw = (g.Cw % 2 == 0 && g.WH % 4 == 0) ? 4 : 1;
+    const int share = ceil_div(g.nk, pl->waves * pl->lw) * pl->lw;
+    if (pl->lw == 4) pl->depth = share <= 8 ? 4 : (share > 16 && share <= 32 ? 16 : 8);
+    else pl->depth = share <= 8 ? 4 : (share > 16 && share <= 26 ? 13 : 8);
     return true;
 }
 
-template <bool PAD, bool BITS, int WAVES, int DEPTH>
+template <bool PAD, bool BITS, int WAVES, int DEPTH, int LW>
 static int launch_block_as(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
                            const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits) {
-    return launch(binconv_block_kernel<PAD, BITS, WAVES, DEPTH>, dim3(pl.grid), dim3(64 * WAVES), 0, st, pl.g, pl.bg, A, E, alpha,
+    return launch(binconv_block_kernel<PAD, BITS, WAVES, DEPTH, LW>, dim3(pl.grid), dim3(64 * WAVES), 0, st, pl.g, pl.bg, A, E, alpha,
                   beta, Y, dbg_s1, tau_out, out_bits);
 }
 
 int launch_block(const BlockPlan& pl, hipStream_t st, const uint32_t* A, const uint32_t* E, const float* alpha,
                  const float* beta, float* Y, int32_t* dbg_s1, const float* tau_out, uint32_t* out_bits) {
     const bool bits = Y == nullptr;
-#define DAB_X(WAVES, DEPTH)                                                                                              \
-    if (pl.waves == WAVES && pl.depth == DEPTH) {                                                                        \
-        if (pl.pad)                                                                                                      \
-            return bits ? launch_block_as<true, true, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits)   \
-                        : launch_block_as<true, false, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits); \
-        return bits ? launch_block_as<false, true, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits)      \
-                    : launch_block_as<false, false, WAVES, DEPTH>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);    \
+#define DAB_X(WAVES, DEPTH, LW)                                                                                              \
+    if (pl.waves == WAVES && pl.depth == DEPTH && pl.lw == LW) {                                                             \
+        if (pl.pad)                                                                                                          \
+            return bits ? launch_block_as<true, true, WAVES, DEPTH, LW>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits)   \
+                        : launch_block_as<true, false, WAVES, DEPTH, LW>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits); \
+        return bits ? launch_block_as<false, true, WAVES, DEPTH, LW>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits)      \
+                    : launch_block_as<false, false, WAVES, DEPTH, LW>(pl, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);    \
     }
-    DAB_X(8, 4) DAB_X(8, 8) DAB_X(8, 13) DAB_X(2, 4) DAB_X(2, 8)
+    DAB_X(8, 4, 1) DAB_X(8, 8, 1) DAB_X(8, 13, 1) DAB_X(2, 4, 1) DAB_X(2, 8, 1)
+    DAB_X(8, 4, 4) DAB_X(8, 8, 4) DAB_X(8, 16, 4) DAB_X(2, 4, 4) DAB_X(2, 8, 4)
 #undef DAB_X
     return DAB_ERR_UNSUPPORTED;
 }
