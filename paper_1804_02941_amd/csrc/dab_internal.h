@@ -84,6 +84,7 @@ struct DirectGeom {
     int pix_bytes;                 // bytes of a pixel's packed words
     uint32_t a_bytes;              // bytes of the packed activation tensor
     uint32_t y_bytes;              // bytes of the fp32 output (below 2^31)
+    int stream_out;                // the fp32 output is far larger than the chip's caches: streaming stores
     FastDiv d_HoWo, d_Wo, d_WH;
 };
 struct DirectPlan {

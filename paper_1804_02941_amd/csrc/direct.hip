@@ -68,8 +68,18 @@ __device__ __forceinline__ void for_each_column(Fn&& f) {
         for_each_column<N, J + 1>(f);
     }
 }
-__device__ __forceinline__ void store_buffer_x4_stream(v4f v, uint32_t voff, v4s rsrc, uint32_t soff) {
-    asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 1" : : "v"(v), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+// Cache policy of the output stores (measured on MI355X; a policy changes only where the data waits
+// on its way to memory): streaming ("nt") is the fastest for an output of more than a hundred
+// megabytes (conv2 of the Sketch-A-Net trunk at batch 256: 126 MB), device-scope write-through
+// ("sc1") for the smaller ones, which the memory-side cache absorbs: their stores otherwise pile up
+// behind the end of the kernel (conv3: 17.7 us instead of 19-23, conv4 21.9 instead of 22.9).
+template <bool STREAM>
+__device__ __forceinline__ void store_buffer_x4(v4f v, uint32_t voff, v4s rsrc, uint32_t soff) {
+    if constexpr (STREAM) {
+        asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen nt\n\ts_nop 1" : : "v"(v), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+    } else {
+        asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen sc1\n\ts_nop 1" : : "v"(v), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+    }
 }
 __device__ __forceinline__ void store_buffer(float v, uint32_t voff, v4s rsrc, uint32_t soff) {
     asm volatile("buffer_store_dword %0, %1, %2, %3 offen" : : "v"(v), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
@@ -459,31 +469,35 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
             const int fl = f0 + 4 * p;                             // first of this lane's four filters
             const uint32_t lane_off = static_cast<uint32_t>(((m_base + h * 4) * g.F + fl) * 4);
             const bool wide = (g.F & 3) == 0 && !dbg_s1;
+            auto store_tile = [&](auto stream) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < 2; ++i) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
+                    for (int q = 0; q < 4; ++q) {
+                        const float sv[4] = {s4[i][q].x, s4[i][q].y, s4[i][q].z, s4[i][q].w};
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const uint32_t row_off = static_cast<uint32_t>((i * 32 + q * 8 + t) * g.F * 4);   // scalar
-                        float y[4];
+                        for (int t = 0; t < 4; ++t) {
+                            const uint32_t row_off = static_cast<uint32_t>((i * 32 + q * 8 + t) * g.F * 4);   // scalar
+                            float y[4];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) y[j] = fmaf(dv[j], acc[i][j][q * 4 + t], bv[j] * sv[t]);
-                        if (wide) {
-                            // written once and not read again by this kernel: streaming stores
-                            store_buffer_x4_stream(v4f{y[0], y[1], y[2], y[3]}, fl < g.F ? lane_off : kOob, yrsrc, row_off);
-                        } else {
+                            for (int j = 0; j < 4; ++j) y[j] = fmaf(dv[j], acc[i][j][q * 4 + t], bv[j] * sv[t]);
+                            if (wide) {
+                                store_buffer_x4<decltype(stream)::value>(v4f{y[0], y[1], y[2], y[3]}, fl < g.F ? lane_off : kOob, yrsrc,
+                                                                         row_off);
+                            } else {
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const uint32_t off = fl + j < g.F ? lane_off + 4 * j : kOob;
-                                store_buffer(y[j], off, yrsrc, row_off);
-                                if (dbg_s1) store_buffer(__int_as_float(-static_cast<int>(acc[i][j][q * 4 + t])), off, drsrc, row_off);
+                                for (int j = 0; j < 4; ++j) {
+                                    const uint32_t off = fl + j < g.F ? lane_off + 4 * j : kOob;
+                                    store_buffer(y[j], off, yrsrc, row_off);
+                                    if (dbg_s1) store_buffer(__int_as_float(-static_cast<int>(acc[i][j][q * 4 + t])), off, drsrc, row_off);
+                                }
                             }
                         }
                     }
                 }
-            }
+            };
+            if (g.stream_out) store_tile(std::true_type{});
+            else store_tile(std::false_type{});
         }
     }
 }
@@ -678,6 +692,7 @@ bool plan_direct(const dab_conv_desc& d, DirectPlan* pl) {
     g.M = static_cast<int>(M);
     g.a_bytes = static_cast<uint32_t>(a_bytes);
     g.y_bytes = static_cast<uint32_t>(M * d.F * 4);
+    g.stream_out = g.y_bytes > (96u << 20) ? 1 : 0;
     g.pix_bytes = g.Cw * 4;
     g.nk = static_cast<int>(nk);
     g.odd = g.Cw & 1;
