@@ -1069,7 +1069,7 @@ static int run_binconv(const dab_conv_desc& d, const uint32_t* A, const uint32_t
         if (int rc = ensure_device_ready()) return rc;
         return launch_direct(dp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
     }
-    // longer reductions over up to 2048 blocks: the block kernel again
+    // longer reductions over a few thousand blocks: the block kernel again
     if (plan_block(d, &bp, true)) return launch_block(bp, st, A, E, alpha, beta, Y, dbg_s1, tau_out, out_bits);
     MfmaPlan pl;
     if (int rc = plan_binconv(d, &pl)) return rc;

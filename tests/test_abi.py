@@ -55,7 +55,7 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert lib.dab_pack_weights(fake, 1, 1, 1, 1, fake, fake, fake, fake, fake, None) == 2
     assert lib.dab_binfc(0, 64, 1, fake, fake, fake, fake, fake, None, None, 0, None) == 2
     assert lib.dab_binfc(1, 64, 1, fake, ctypes.c_void_p(4100), fake, fake, fake, None, None, 0, None) == 3
-    assert lib.dab_binfc(8192, 4096, 512, fake, fake, fake, fake, fake, None, None, 0, None) == 4   # workspace missing
+    assert lib.dab_binfc(8192, 9216, 512, fake, fake, fake, fake, fake, None, None, 0, None) == 4   # workspace missing
     d = binding.dab_conv_desc(1, 8, 4, 4, 2, 5, 5, 0, 0, 1, 1)      # window larger than the image
     assert lib.dab_binconv2d(ctypes.byref(d), fake, fake, fake, fake, fake, None, None, 0, None) == 2
     d = binding.dab_conv_desc(1, 8, 4, 4, 2, 3, 3, 0, 0, 0, 1)      # zero stride
@@ -63,7 +63,7 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert lib.dab_estimate_workspace_bytes(4, 100) == 0
     assert lib.dab_binfc_workspace_bytes(4, 100, 4) == 0            # small layers run from the bits alone
     assert lib.dab_binfc_workspace_bytes(2048, 64, 512) == 0        # and so do all whose filter bits fit in LDS
-    assert lib.dab_binfc_workspace_bytes(8192, 4096, 512) > 0       # a long reduction over many rows expands its operands
+    assert lib.dab_binfc_workspace_bytes(8192, 9216, 512) > 0       # a long reduction over many rows expands its operands
     assert lib.dab_binfc_workspace_bytes(0, 100, 4) == 0
 
 

@@ -137,9 +137,9 @@ def test_config3_fused_chain_matches_fp32_chain():
 
 
 def test_error_codes_of_the_new_entry_points():
-    d = dab.dab_conv_desc(8192, 4096, 1, 1, 512, 1, 1, 0, 0, 1, 1)   # a long reduction over many rows: operands are expanded into a workspace
-    A = torch.zeros((8192, 1, 1, 128), dtype=torch.int32, device="cuda:0")
-    E = torch.zeros((128, 512), dtype=torch.int32, device="cuda:0")
+    d = dab.dab_conv_desc(8192, 9216, 1, 1, 512, 1, 1, 0, 0, 1, 1)   # a long reduction over many rows: operands are expanded into a workspace
+    A = torch.zeros((8192, 1, 1, 288), dtype=torch.int32, device="cuda:0")
+    E = torch.zeros((288, 512), dtype=torch.int32, device="cuda:0")
     ab = torch.ones(512, dtype=torch.float32, device="cuda:0")
     import ctypes
     out = torch.zeros((8192, 1, 1, 16), dtype=torch.int32, device="cuda:0")
