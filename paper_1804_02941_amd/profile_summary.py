@@ -98,11 +98,11 @@ def main():
              f"Tree: {commit}", "",
              "One row per kernel, grid (threads) and workgroup size, in the order of first launch.  The headline step is",
              "prepare_rows_kernel<256,...> (five layers' weight sides + a share of all activation packing),",
-             "prepare_rows_kernel<512, 26,...> (conv6's weight side + the rest of the packing), binarize_sort_kernel grid 65536, then",
+             "prepare_rows_kernel<512, 26,...> (conv6's weight side + the rest of the packing), binarize_sort_kernel (the rows they flag: none here), then",
              "the six products: binconv_direct_kernel<1, 5, false, false> grid 131072 is conv2, <2, 3, true, false> conv3,",
-             "<4, 3, true, false> grid 115712 conv4 and conv5, binconv_block_kernel<false, false, 8> grid 65536 conv6 and",
-             "<false, false, 2> grid 16384 fc7.  The other rows belong to the measurements beside the headline: the separate",
-             "calls of the stage table, the chain that hands bits on (kernels ending in `true>`), the training side, the",
+             "<4, 3, true, false> grid 115712 conv4 and conv5, binconv_block_kernel<false, false, 8, 16, 4> grid 65536 conv6 and",
+             "<false, false, 2, 4, 4> grid 16384 fc7.  The other rows belong to the measurements beside the headline: the separate",
+             "calls of the stage table, the chain that hands bits on (product kernels whose BITS argument is true), the training side, the",
              "weights-only layers (wbin_prepare_kernel, binconv_mfma_kernel<8, 0, 1>), configurations 2, 4 and 5 (config 5's",
              "weight sides are the launches with grid 2097152), batch 32, and the popcount-rate probe.", "",
              "| kernel | grid | workgroup | launches | average us | min us | max us |", "|---|---|---|---|---|---|---|"]

@@ -53,7 +53,13 @@ int check_one(const dab_conv_desc& d) {
             REQUIRE(bp.g.M == M);
             REQUIRE(bp.bg.n_fblocks == (d.F + 31) / 32 && bp.bg.fb_per_xcd * 8 >= bp.bg.n_fblocks);
             REQUIRE(1ull * bp.grid == 1ull * ((M + 31) / 32) * bp.bg.fb_per_xcd * 8);
-            REQUIRE(1ll * ((M + 31) / 32) * bp.bg.n_fblocks <= (large ? 2048 : 512));
+            const long long blocks = 1ll * ((M + 31) / 32) * bp.bg.n_fblocks;
+            REQUIRE(blocks <= (large ? 8192 : 512) && (!large || blocks * bp.g.nk <= 400000));
+            // the load burst: whole loads, and a kernel exists for the combination
+            REQUIRE(bp.lw == 1 || (bp.lw == 4 && bp.g.Cw % 8 == 0));
+            REQUIRE(bp.depth % bp.lw == 0);
+            REQUIRE((bp.lw == 1 && (bp.depth == 4 || bp.depth == 8 || (bp.depth == 13 && bp.waves == 8))) ||
+                    (bp.lw == 4 && (bp.depth == 4 || bp.depth == 8 || (bp.depth == 16 && bp.waves == 8))));
             REQUIRE(1ll * d.C * d.kh * d.kw < (1ll << 24));
         }
     }
