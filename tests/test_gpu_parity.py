@@ -244,6 +244,9 @@ SMALL_LAYERS = [
     Layer("c64", C=64, H=12, W=13, F=64, kh=3, kw=3, pad=1),
     Layer("c96_f100", C=96, H=9, W=8, F=100, kh=3, kw=3),
     Layer("wide", C=32, H=3, W=40, F=16, kh=3, kw=3, pad=1),
+    # pixels of eight and sixteen words (the small-product kernel's 16-byte activation loads), with padding
+    Layer("c256_pad", C=256, H=5, W=6, F=40, kh=3, kw=3, pad=1),
+    Layer("c512_pad_s2", C=512, H=7, W=7, F=33, kh=3, kw=3, pad=1, stride=2),
 ]
 
 
@@ -304,7 +307,7 @@ def test_fc_with_many_rows():
     gu.check_layer(L, x, weight_rows(rng, F, K, "gauss"))
 
 
-@pytest.mark.parametrize("B,K,F", [(1, 2, 1), (5, 70, 9), (64, 512, 512), (65, 1000, 130), (300, 4096, 48), (130, 9216, 40)])
+@pytest.mark.parametrize("B,K,F", [(1, 2, 1), (5, 70, 9), (64, 512, 512), (65, 1000, 130), (70, 1280, 96), (300, 4096, 48), (130, 9216, 40)])
 def test_small_fc_layers(B, K, F):
     rng = np.random.default_rng(B + K + F)
     L = Layer("fc", C=K, H=1, W=1, F=F, kh=1, kw=1)
