@@ -202,6 +202,7 @@ int dab_estimate_sign_split(const float* W, int32_t F, int32_t n,
  *   thr_val, thr_idx, alpha_is_upper   [F], as returned by the estimator
  *   E_packed   uint32 [kh*kw*Cw][Fp] out, every word written (layout above)
  *   ecnt       uint32 [F][kh*kw] out
+ * Kernels of up to 384 taps (kh*kw; more -> DAB_ERR_UNSUPPORTED).
  */
 int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t kw,
                      const float* thr_val, const int32_t* thr_idx, const uint8_t* alpha_is_upper,
@@ -226,7 +227,7 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
  *             (one flag per filter of the jobs whose unfinished rows go to the sort kernel; 0 for a
  *             few layers with rows of at most 4608 weights, which are finished in their own launch)
  * Errors: per job as in the separate calls (rows above dab_estimate_max_n(), more than 128 taps with
- * packing -> DAB_ERR_UNSUPPORTED); more than 16 jobs -> DAB_ERR_UNSUPPORTED; ws missing or too
+ * packing -> DAB_ERR_UNSUPPORTED: such a layer takes the separate calls); more than 16 jobs -> DAB_ERR_UNSUPPORTED; ws missing or too
  * small -> DAB_ERR_WORKSPACE; ws not 8-byte aligned -> DAB_ERR_ALIGN.
  */
 typedef struct dab_weight_job {

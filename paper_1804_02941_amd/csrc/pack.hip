@@ -71,6 +71,7 @@ __global__ __launch_bounds__(256) void pack_act_nchw_kernel(const float* __restr
 // accumulated in LDS.  The slab holds a whole filter of up to 24K weights, so most layers
 // need one pass.
 constexpr int kWeightSlabFloats = 24 * 1024;   // 96 KB
+constexpr int kWeightMaxTaps = kWeightSlabFloats / 64;      // a slab holds at least 64 channels of every tap
 
 __global__ __launch_bounds__(1024) void pack_weights_kernel(const float* __restrict__ Wt, const float* __restrict__ thr_val,
                                                            const int32_t* __restrict__ thr_idx,
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(1024) void pack_weights_kernel(const float* __restr
                                                            uint32_t* __restrict__ E, uint32_t* __restrict__ ecnt,
                                                            int F, int C, int T, int Cw, int Fp, int slab_c) {
     extern __shared__ __align__(16) float slab[];
-    __shared__ uint32_t cnt[128];            // per-tap counts, T <= 128 taps (checked on the host)
+    __shared__ uint32_t cnt[kWeightMaxTaps]; // per-tap counts (T <= kWeightMaxTaps, checked on the host)
     // Workgroups go round-robin over the eight XCDs, and a column of E is one 4-byte word per
     // row: neighbouring filters share cache lines.  Filters are dealt out so that an XCD owns a
     // contiguous range of them, and the partial lines merge in that XCD's L2 instead of reaching
@@ -288,7 +289,7 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
         misaligned(ecnt, 4))
         return DAB_ERR_ALIGN;
     const int T = kh * kw;
-    if (T > 128 || 1ll * C * T >= (1ll << 31)) return DAB_ERR_UNSUPPORTED;
+    if (T > kWeightMaxTaps || 1ll * C * T >= (1ll << 31)) return DAB_ERR_UNSUPPORTED;
     const int Cw = ceil_div(C, 32);
     const int Fp = 64 * ceil_div(F, 64);
     int slab_c = (kWeightSlabFloats / T) & ~63;             // whole 64-channel groups per slab

@@ -250,6 +250,15 @@ SMALL_LAYERS = [
 ]
 
 
+@pytest.mark.parametrize("pad", [0, 7])
+def test_large_kernel_extent(pad):
+    """A 15 x 15 kernel (225 taps, the extent of Sketch-A-Net's first layer), with and without padding."""
+    L = Layer(f"k15_pad{pad}", C=6, H=33, W=31, F=20, kh=15, kw=15, pad=pad, stride=3)
+    rng = np.random.default_rng(1500 + pad)
+    x = rng.standard_normal((2, L.C, L.H, L.W)).astype(np.float32)
+    gu.check_layer(L, x, weight_rows(rng, L.F, L.n, "mixture"), tau=None, layout="nhwc")
+
+
 @pytest.mark.parametrize("L", SMALL_LAYERS, ids=lambda L: L.name)
 @pytest.mark.parametrize("B", [1, 3])
 def test_small_conv_layers(L, B):
