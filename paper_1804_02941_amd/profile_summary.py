@@ -51,6 +51,23 @@ def kernel_durations(folder):
     return acc
 
 
+def dominant_kernel_by_neighbour(folder, kernel="binconv_direct_kernel<1, 5, false, false>", grid=131072):
+    """Durations (us) of the dominant kernel's launches: those that follow another launch of it (the graphs of
+    ten back-to-back launches bench.py times for `roofline`), and those inside a step (behind the sort kernel)."""
+    with open(_one(folder, "*kernel_trace.csv")) as f:
+        rows = sorted(csv.DictReader(f), key=lambda r: int(r["Start_Timestamp"]))
+    same, in_step, prev = [], [], None
+    for r in rows:
+        if kernel in r["Kernel_Name"] and int(r["Grid_Size_X"]) == grid:
+            d = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+            if prev is not None and kernel in prev["Kernel_Name"]:
+                same.append(d)
+            elif prev is not None and "binarize_sort_kernel" in prev["Kernel_Name"]:
+                in_step.append(d)
+        prev = r
+    return same, in_step
+
+
 def counter_values(folder):
     """({(kernel, grid): [values in KiB]} of the library's kernels, [values of the 256 MiB calibration copies])."""
     acc, copies = collections.OrderedDict(), []
@@ -108,6 +125,14 @@ def main():
              "| kernel | grid | workgroup | launches | average us | min us | max us |", "|---|---|---|---|---|---|---|"]
     for (k, grid, wg), v in dur.items():
         lines.append(f"| `{k}` | {grid} | {wg} | {len(v)} | {sum(v) / len(v):.2f} | {min(v):.2f} | {max(v):.2f} |")
+    same, in_step = dominant_kernel_by_neighbour(args.trace)
+    if same and in_step:
+        lines += ["", f"The dominant kernel, conv2's `binconv_direct_kernel<1, 5, false, false>` (grid 131072), by what ran before it:",
+                  f"behind another launch of itself (the graphs of ten launches that bench.py times for `roofline`): {len(same)} launches,",
+                  f"average {sum(same) / len(same):.2f} us, min {min(same):.2f}; inside a step (behind the sort kernel, caches cold for its",
+                  f"operands): {len(in_step)} launches, average {sum(in_step) / len(in_step):.2f} us, min {min(in_step):.2f}.  Under the profiler",
+                  "every launch is serialised and a few per cent longer than in a plain graph replay (bench.py's HIP events:",
+                  "`roofline.launch_ms` of the same tree)."]
     with open(os.path.join(args.out, "bench_config3_kernel_stats.md"), "w") as f:
         f.write("\n".join(lines) + "\n")
 
