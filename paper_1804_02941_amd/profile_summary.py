@@ -68,6 +68,30 @@ def dominant_kernel_by_neighbour(folder, kernel="binconv_direct_kernel<1, 5, fal
     return same, in_step
 
 
+STEP_KERNELS = ["prepare_rows_kernel", "prepare_rows_kernel", "binarize_sort_kernel", "binconv_direct_kernel", "binconv_direct_kernel",
+                "binconv_direct_kernel", "binconv_direct_kernel", "binconv_block_kernel", "binconv_block_kernel"]
+
+
+def headline_steps(folder, conv2_grid=131072):
+    """The launches of the headline step (config 3, batch 256), found in the trace by their order: per position the
+    kernel (with its template arguments) and its durations, and the spans from the first start to the last end."""
+    with open(_one(folder, "*kernel_trace.csv")) as f:
+        rows = sorted(csv.DictReader(f), key=lambda r: int(r["Start_Timestamp"]))
+    names = [short(r["Kernel_Name"]) for r in rows]
+    per, spans, i, n = [[] for _ in STEP_KERNELS], [], 0, len(STEP_KERNELS)
+    labels = [None] * n
+    while i + n <= len(rows):
+        if all(names[i + k].startswith(STEP_KERNELS[k] + "<") for k in range(n)) and int(rows[i + 3]["Grid_Size_X"]) == conv2_grid:
+            for k in range(n):
+                per[k].append((int(rows[i + k]["End_Timestamp"]) - int(rows[i + k]["Start_Timestamp"])) / 1e3)
+                labels[k] = names[i + k]
+            spans.append((int(rows[i + n - 1]["End_Timestamp"]) - int(rows[i]["Start_Timestamp"])) / 1e3)
+            i += n
+        else:
+            i += 1
+    return labels, per, spans
+
+
 def counter_values(folder):
     """({(kernel, grid): [values in KiB]} of the library's kernels, [values of the 256 MiB calibration copies])."""
     acc, copies = collections.OrderedDict(), []
@@ -133,6 +157,16 @@ def main():
                   f"operands): {len(in_step)} launches, average {sum(in_step) / len(in_step):.2f} us, min {min(in_step):.2f}.  Under the profiler",
                   "every launch is serialised and a few per cent longer than in a plain graph replay (bench.py's HIP events:",
                   "`roofline.launch_ms` of the same tree)."]
+    labels, per, spans = headline_steps(args.trace)
+    if spans:
+        what = ["weight sides of conv2-conv5, fc7 + a share of the packing", "weight side of conv6 + the rest of the packing",
+                "rows handed to the sort (none here)", "product conv2", "product conv3", "product conv4", "product conv5",
+                "product conv6", "product fc7"]
+        lines += ["", f"The headline step kernel by kernel ({len(spans)} steps in the trace; under the profiler a launch starts when the one",
+                  f"before it ends, so the durations add up to the span of a step, {sum(spans) / len(spans):.1f} us on average):", "",
+                  "| launch | kernel | average us |", "|---|---|---|"]
+        for k, v in enumerate(per):
+            lines.append(f"| {what[k]} | `{labels[k]}` | {sum(v) / len(v):.2f} |")
     with open(os.path.join(args.out, "bench_config3_kernel_stats.md"), "w") as f:
         f.write("\n".join(lines) + "\n")
 
