@@ -381,8 +381,11 @@ static int check_weight_job(const dab_weight_job& j) {
 
 // Rows up to 4608 weights can be finished in one launch: the workgroup that cannot finish a row with
 // the buckets sorts it itself.  Flagging such rows for the sort kernel instead frees the LDS of the
-// in-kernel sort, and more workgroups share a compute unit (seven instead of five of the 256-thread
-// kernel, three instead of two of the 512-thread one).  That is done where it pays for the extra launch:
+// in-kernel sort, and more workgroups share a compute unit: seven instead of five of the 256-thread
+// kernel; the rows of 2305 .. 4608 weights then take 256 threads with eighteen elements each and
+// 1024 buckets, six workgroups per compute unit instead of the two of the 512-thread kernel that can
+// sort (4096 rows of 4096 weights: 63 us instead of 85; these kernels are bound by the latency of a
+// row's chain of phases, so rows in flight count).  That is done where it pays for the extra launch:
 // for a class with many rows, and for the short rows whenever the sort kernel is launched anyway.
 struct HandOver {
     bool small, medium;        // rows up to 2304 weights, rows of 2305 .. 4608
@@ -475,7 +478,7 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
                 const long long p1 = done >= total ? pixels : static_cast<long long>(hi * static_cast<double>(pixels));
                 if (p1 > p0) pk[c].job[pk[c].n++] = make_pack_job(packs[i], p0, p1);
             }
-            if (pk[c].n) share_pack_blocks(&pk[c], end[c], c == 0 ? 4 : 8);
+            if (pk[c].n) share_pack_blocks(&pk[c], end[c], (c == 0 || (c == 1 && hand.medium)) ? 4 : 8);   // (wavefronts of the class's workgroups)
         }
     }
 #define DAB_ROWS(C, T, I, NB, CAP, SORT, MINW) \
@@ -484,7 +487,7 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
     if (cls[0].n)
         if (int rc = hand.small ? DAB_ROWS(0, 256, 9, 512, 256, false, 7) : DAB_ROWS(0, 256, 9, 512, 256, true, 5)) return rc;
     if (cls[1].n)
-        if (int rc = hand.medium ? DAB_ROWS(1, 512, 9, 2048, 256, false, 6) : DAB_ROWS(1, 512, 9, 2048, 256, true, 4)) return rc;
+        if (int rc = hand.medium ? DAB_ROWS(1, 256, 18, 1024, 256, false, 6) : DAB_ROWS(1, 512, 9, 2048, 256, true, 4)) return rc;
     if (cls[2].n)
         if (int rc = DAB_ROWS(2, 512, 18, 2048, 512, false, 6)) return rc;
     if (cls[3].n)
