@@ -478,7 +478,8 @@ static int run_weight_jobs(const dab_weight_job* jobs, int n_jobs, void* ws, siz
                 const long long p1 = done >= total ? pixels : static_cast<long long>(hi * static_cast<double>(pixels));
                 if (p1 > p0) pk[c].job[pk[c].n++] = make_pack_job(packs[i], p0, p1);
             }
-            if (pk[c].n) share_pack_blocks(&pk[c], end[c], (c == 0 || (c == 1 && hand.medium)) ? 4 : 8);   // (wavefronts of the class's workgroups)
+            const int class_waves[kClasses] = {4, hand.medium ? 4 : 8, 8, 8};      // (wavefronts of the class's workgroups)
+            if (pk[c].n) share_pack_blocks(&pk[c], end[c], class_waves[c]);
         }
     }
 #define DAB_ROWS(C, T, I, NB, CAP, SORT, MINW) \
