@@ -361,7 +361,7 @@ static int dispatch_estimate(const float* W, int F, int n, float* alpha, float* 
 
 // ---------------------------------------------------------------- host side of the multi-layer call
 constexpr int kSmallMaxN = 256 * 9;                // rows up to here: 256 threads and 512 buckets per row
-constexpr int kShortMaxN = 512 * 9;                // rows up to here: 512 threads and 2048 buckets, sorted in the same kernel if need be
+constexpr int kShortMaxN = 512 * 9;                // rows up to here: 512 threads x 9 and 2048 buckets, sorted in the same kernel if need be (or 256 x 18 and 1024 buckets, handed over)
 constexpr int kMidMaxN = 512 * 18;                 // rows up to here: 18 weights per thread, longer ones 26; both hand rows over to the sort kernel
 
 static int check_weight_job(const dab_weight_job& j) {
