@@ -217,7 +217,10 @@ int dab_pack_weights(const float* W, int32_t F, int32_t C, int32_t kh, int32_t k
  * a layer together; filters of different layers are just as independent, so they share the
  * launches (a workgroup looks up its job), and a filter's mask (Corollary 1) is packed by the
  * workgroup that has just found its split, while the row is still in cache.  Results are, bit
- * for bit, those of the separate calls.
+ * for bit, those of the separate calls, with one exception: for a row in which several splits have
+ * scores that are equal to the last bit or differ only by the rounding of the float64 sums (a
+ * constant row is the extreme case), the two may return different ones of those splits, because
+ * their sort kernels cut such a row into different per-thread pieces.
  *
  *   jobs      host array of n_jobs descriptors (read during the call only); every pointer inside is a
  *             device pointer with the meaning it has in dab_estimate_alpha_beta / dab_pack_weights.
