@@ -430,7 +430,11 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
                                 const float y = fmaf(dcol[j], acc[i][j][q * 4 + t], bcol[j] * sv[t]);
                                 const bool bit = fp0 + j * 32 + p < g.F && y >= tcol[j];
                                 const unsigned long long mask = __ballot(bit);
-                                asm volatile("v_writelane_b32 %0, %1, %2"
+                                // The mask is written by a vector compare.  On this ISA a vector instruction that reads a scalar
+                                // register needs two wait states behind the vector instruction that wrote it; the compiler
+                                // inserts them for its own instructions but does not look into inline assembly (without them the
+                                // lane write took the register's previous content, the compare before the F mask: bits past F set).
+                                asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %2"
                                              : "+v"(wb[j]) : "s"(static_cast<uint32_t>(mask)), "n"(r0));
                                 asm volatile("v_writelane_b32 %0, %1, %2"
                                              : "+v"(wb[j]) : "s"(static_cast<uint32_t>(mask >> 32)), "n"(r0 + 4));

@@ -80,6 +80,19 @@ def test_small_conv_layers_rebinarized(L):
     check_rebinarize(L, x, W, None, None)
 
 
+@pytest.mark.parametrize("C,F", [(160, 230), (64, 70), (256, 129)])
+def test_filter_counts_that_end_inside_a_word_in_the_persistent_kernel(C, F):
+    """Enough pixels for the persistent one-launch kernel and a filter count that is not a multiple of
+    32: the bits past F in every pixel's last word are zero (they once took the unmasked compare)."""
+    L = Layer(f"ragged_f{F}", C=C, H=14, W=10, F=F, kh=3, kw=3, pad=2)
+    rng = np.random.default_rng(C * 1000 + F)
+    x = rng.standard_normal((33, L.C, L.H, L.W)).astype(np.float32)
+    W = weight_rows(rng, L.F, L.n, "mixture")
+    tau_out = (rng.standard_normal(L.F) * 0.5).astype(np.float32)
+    check_rebinarize(L, x, W, None, tau_out)
+    check_rebinarize(L, x, W, None, None)
+
+
 @pytest.mark.parametrize("B,K,F", [(1, 2, 1), (5, 70, 9), (64, 512, 512), (65, 1000, 130), (300, 4096, 48), (130, 9216, 40)])
 def test_small_fc_layers_rebinarized(B, K, F):
     rng = np.random.default_rng(B * K + F)
