@@ -1,0 +1,145 @@
+"""Seeded random sweeps over layer shapes and job mixes (through the C ABI, on the GPU).
+
+The fixed cases of the other files sit on the boundaries somebody thought of; these draw shapes
+across all product kernels (channel counts that are and are not multiples of 32 / 256, padding up
+to the kernel extent, strides, filter counts that end inside a word, fully-connected shapes) and
+mixes of layers for the grouped calls, and check what is unique: integer sums and estimates
+against the oracle, the packed-sign output against packing the fp32 output, the grouped calls
+against the separate ones.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1804_02941_amd import binding as dab
+from paper_1804_02941_amd import workloads as wl
+
+import gpu_util as gu
+from test_gpu_parity import weight_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_shape(rng, big=False):
+    """(B, C, H, W, F, kh, kw, pad, stride) of a layer: many-channel, odd-channel, many-pixel or fully-connected."""
+    kind = int(rng.integers(0, 4))
+    if kind == 0:
+        C = int(rng.choice([256, 512, 768, 1024])); kh = int(rng.choice([1, 2, 3])); kw = int(rng.choice([1, 2, 3]))
+        H = int(rng.integers(kh, 9)); W = int(rng.integers(kw, 9)); F = int(rng.integers(1, 300 if big else 140))
+        B = int(rng.integers(1, 40 if big else 5))
+    elif kind == 1:
+        C = int(rng.integers(1, 300)); kh = int(rng.integers(1, 6)); kw = int(rng.integers(1, 6))
+        H = int(rng.integers(kh, 20 if big else 14)); W = int(rng.integers(kw, 20 if big else 14))
+        F = int(rng.integers(1, 300 if big else 200)); B = int(rng.integers(1, 10 if big else 4))
+    elif kind == 2:
+        C = int(rng.choice([32, 64, 96, 128, 160, 256])); kh = kw = int(rng.choice([1, 3, 5]))
+        H = int(rng.integers(kh + 6, 40 if big else 24)); W = int(rng.integers(kw + 6, 40 if big else 24))
+        F = int(rng.integers(60, 400 if big else 300)); B = int(rng.integers(2, 40 if big else 8))
+    else:
+        C = int(rng.choice([64, 200, 512, 1280, 2048, 4096] + ([9216] if big else []))); kh = kw = 1; H = W = 1
+        F = int(rng.integers(1, 600 if big else 300)); B = int(rng.integers(1, 1200 if big else 200))
+    pad = int(rng.integers(0, max(kh, kw) + 1)) if 1 < kh * kw <= 32 else 0
+    stride = int(rng.integers(1, 4))
+    return B, C, H, W, F, kh, kw, pad, stride
+
+
+def usable(s, max_n=None):
+    B, C, H, W, F, kh, kw, pad, stride = s
+    return H + 2 * pad >= kh and W + 2 * pad >= kw and C * kh * kw >= 2 and (max_n is None or C * kh * kw <= max_n)
+
+
+def test_random_layers_against_the_oracle():
+    rng = np.random.default_rng(20241)
+    done = 0
+    while done < 120:
+        s = draw_shape(rng)
+        if not usable(s, 13312):
+            continue
+        B, C, H, W, F, kh, kw, pad, stride = s
+        L = wl.Layer(f"random{done}", C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
+        x = rng.standard_normal((B, C, H, W)).astype(np.float32)
+        w = weight_rows(rng, F, L.n, str(rng.choice(["gauss", "mixture"])))
+        tau = (rng.standard_normal(C) * 0.3).astype(np.float32) if rng.integers(0, 2) else None
+        try:
+            gu.check_layer(L, x, w, tau=tau, layout="nhwc")
+        except AssertionError as e:
+            raise AssertionError(f"{s}: {e}") from e
+        done += 1
+
+
+def test_random_layers_packed_sign_output_equals_packing_the_fp32_output():
+    rng = np.random.default_rng(20242)
+    torch.manual_seed(20242)
+    dev = "cuda:0"
+    done = 0
+    while done < 300:
+        s = draw_shape(rng, big=True)
+        if not usable(s):
+            continue
+        B, C, H, W, F, kh, kw, pad, stride = s
+        Cw, Fp = (C + 31) // 32, 64 * ((F + 63) // 64)
+        A = torch.randint(-2**31, 2**31 - 1, (B, H, W, Cw), dtype=torch.int32, device=dev)
+        E = torch.randint(-2**31, 2**31 - 1, (kh * kw * Cw, Fp), dtype=torch.int32, device=dev)
+        if C % 32:                                                  # bits past C are zero in packed operands
+            A[..., -1] &= (1 << (C % 32)) - 1
+            E.view(kh * kw, Cw, Fp)[:, -1, :] &= (1 << (C % 32)) - 1
+        E[:, F:] = 0
+        alpha = torch.rand(F, device=dev) + 0.1
+        beta = -torch.rand(F, device=dev) - 0.1
+        tau = torch.randn(F, device=dev) * 3.0 if rng.integers(0, 2) else None
+        d = dab.dab_conv_desc(B, C, H, W, F, kh, kw, pad, pad, stride, stride)
+        Y, s1 = dab.dab_binconv2d(d, A, E, alpha, beta, want_s1=True)
+        bits = dab.dab_binconv2d_bits(d, A, E, alpha, beta, tau)
+        ref = dab.dab_pack_activations(Y, dab.DAB_LAYOUT_NHWC, tau)
+        torch.cuda.synchronize()
+        assert torch.equal(bits.reshape(ref.shape), ref), s
+        assert int(s1.abs().max()) <= C * kh * kw, s
+        done += 1
+
+
+def test_random_mixes_through_prepare_layers_equal_the_separate_calls():
+    rng = np.random.default_rng(20243)
+    kinds = ["gauss", "mixture", "laplace", "dupes", "onesided"]
+    for mix in range(40):
+        wjobs, desc = [], []
+        for _ in range(int(rng.integers(1, 7))):
+            cls = int(rng.integers(0, 5))
+            n = int([rng.integers(2, 2305), rng.integers(2305, 4609), rng.integers(4609, 9217), rng.integers(9217, 13313),
+                     rng.choice([2304, 2305, 4608, 4609, 9216, 9217, 13312, 256, 257])][cls])
+            T = next((t for t in (25, 9, 4, 3, 2) if n % t == 0), 1)
+            kh, kw = {25: (5, 5), 9: (3, 3), 4: (2, 2), 3: (1, 3), 2: (2, 1), 1: (1, 1)}[T]
+            C = n // T
+            many = rng.integers(0, 12) == 0 and n <= 4608           # enough rows to be handed to the sort kernel
+            F = int(rng.integers(1536, 1800)) if many else int(rng.integers(1, 200))
+            kind = str(rng.choice(kinds))
+            W = weight_rows(rng, F, n, kind).reshape(F, C, kh, kw)
+            if rng.integers(0, 4) == 0:
+                W[int(rng.integers(0, F))] = float(rng.standard_normal())                # a constant filter
+            Wt = gu.to_gpu(W)
+            wjobs.append(dict(W=Wt, est=dab.estimate_outputs(F, Wt.device), packed=dab.pack_weights_outputs(F, C, kh, kw, Wt.device)))
+            desc.append((F, C, kh, kw, kind))
+        pitems = []
+        for _ in range(int(rng.integers(1, 6))):
+            C = int(rng.choice([1, 3, 31, 64, 70, 128, 192, 256, 300, 512, 1024]))
+            B, H, Wd = int(rng.integers(1, 40)), int(rng.integers(1, 12)), int(rng.integers(1, 12))
+            X = gu.to_gpu(rng.standard_normal((B, H, Wd, C)).astype(np.float32))
+            tau = gu.to_gpu(rng.standard_normal(C).astype(np.float32) * 0.3) if rng.integers(0, 2) else None
+            pitems.append((X, tau, torch.full((B, H, Wd, dab.words_per_pixel(C)), -1, dtype=torch.int32, device=X.device)))
+        if sum(d[0] for d in desc) < len(pitems):
+            continue                                                # (fewer filters than tensors: the call refuses)
+        dab.dab_prepare_layers(dab.weight_jobs(wjobs), dab.pack_jobs(pitems))
+        torch.cuda.synchronize()
+        for j, dsc in zip(wjobs, desc):
+            F = dsc[0]
+            ref = dab.dab_estimate_alpha_beta(j["W"].reshape(F, -1))
+            E, ecnt = dab.dab_pack_weights(j["W"], ref["thr_val"], ref["thr_idx"], ref["alpha_is_upper"])
+            torch.cuda.synchronize()
+            if all(torch.equal(j["est"][k], ref[k]) for k in ref):
+                assert torch.equal(j["packed"][0], E) and torch.equal(j["packed"][1], ecnt), dsc
+            else:
+                # only rows with splits tied to rounding may differ (a constant filter): then both are the oracle's maximum
+                gu.check_estimate(j["W"].cpu().numpy(), {k: v.cpu().numpy() for k, v in j["est"].items()})
+        for (X, tau, A) in pitems:
+            R = dab.dab_pack_activations(X, dab.DAB_LAYOUT_NHWC, tau)
+            torch.cuda.synchronize()
+            assert torch.equal(A, R.reshape(A.shape)), tuple(X.shape)
