@@ -14,8 +14,11 @@ import torch
 from paper_1804_02941_amd import binding as dab
 from paper_1804_02941_amd import workloads as wl
 
+from oracle import training as otr
+
 import gpu_util as gu
 from test_gpu_parity import weight_rows
+from test_gpu_training import check_bounded
 
 pytestmark = pytest.mark.gpu
 
@@ -143,3 +146,54 @@ def test_random_mixes_through_prepare_layers_equal_the_separate_calls():
             R = dab.dab_pack_activations(X, dab.DAB_LAYOUT_NHWC, tau)
             torch.cuda.synchronize()
             assert torch.equal(A, R.reshape(A.shape)), tuple(X.shape)
+
+
+ROW_LENGTHS = [2, 3, 64, 192, 193, 255, 256, 257, 768, 769, 1280, 1792, 1793, 2304, 2305, 2816, 2817, 3584, 3585, 4095, 4096,
+               4608, 4609, 5632, 7168, 7169, 8192, 8193, 9216, 9217, 11264, 11265, 13312]      # the kernels' class limits
+
+
+def test_random_rows_through_the_estimators():
+    """Rows of every length class and kind (duplicates, one-sided, constant, two-valued) through the plain, the
+    windowed and the allocation-free estimator and the training-side kernels, against the oracle."""
+    rng = np.random.default_rng(20244)
+    for it in range(120):
+        n = int(rng.choice(ROW_LENGTHS)) if rng.integers(0, 3) == 0 else int(rng.integers(2, 13313))
+        F = int(rng.integers(1, 40)) if n > 3000 else int(rng.integers(1, 300))
+        w = weight_rows(rng, F, n, str(rng.choice(["gauss", "mixture", "laplace", "dupes", "onesided"])))
+        if rng.integers(0, 5) == 0:
+            w[int(rng.integers(0, F))] = float(rng.standard_normal())
+        if rng.integers(0, 8) == 0:
+            w[int(rng.integers(0, F))] = np.where(rng.random(n) < 0.5, 0.25, -0.5).astype(np.float32)
+        t = gu.to_gpu(w)
+        which = int(rng.integers(0, 4))
+        if which == 0:
+            got = dab.dab_estimate_alpha_beta(t)
+            torch.cuda.synchronize()
+            gu.check_estimate(w, {k: v.cpu().numpy() for k, v in got.items()})
+        elif which == 1:
+            prev = dab.dab_estimate_alpha_beta(t)
+            w1 = (w + 0.05 * np.float32(np.sqrt(2.0 / n)) * rng.standard_normal((F, n))).astype(np.float32)
+            d = int(rng.choice([0, 1, 2, max(2, n // 50), n, 2 ** 31 - 1]))
+            got = dab.dab_estimate_alpha_beta_bounded(gu.to_gpu(w1), prev["K"], prev["alpha_is_upper"], d)
+            torch.cuda.synchronize()
+            check_bounded(w1, {k: v.cpu().numpy() for k, v in got.items()}, prev["K"].cpu().numpy(),
+                          prev["alpha_is_upper"].cpu().numpy(), d)
+        elif which == 2:
+            W2 = dab.dab_mean_center_clamp(t.reshape(F, n, 1, 1)).reshape(F, n)
+            est = dab.dab_estimate_alpha_beta(W2)
+            Wt = dab.dab_binarized_weights(W2, est["alpha"], est["beta"], est["thr_val"], est["thr_idx"], est["alpha_is_upper"])
+            up = rng.standard_normal((F, n)).astype(np.float32)
+            dW = dab.dab_weight_gradient(W2, est["thr_val"], est["thr_idx"], est["alpha_is_upper"], upstream=gu.to_gpu(up))
+            torch.cuda.synchronize()
+            wc, est_np = W2.cpu().numpy(), {k: v.cpu().numpy() for k, v in est.items()}
+            assert np.allclose(wc, otr.mean_center_clamp(w.reshape(F, n, 1, 1), "filter").reshape(F, n), rtol=1e-5, atol=1e-7)
+            e, _ = gu.check_estimate(wc, est_np)
+            assert np.array_equal(Wt.cpu().numpy(), np.where(e == 1, est_np["alpha"][:, None], est_np["beta"][:, None]).astype(np.float32))
+            ref = otr.weight_gradient(wc, e, up)
+            assert np.allclose(dW.cpu().numpy(), ref, rtol=1e-5, atol=1e-6 * np.abs(ref).max()), (F, n)
+        else:
+            a = dab.dab_estimate_alpha_beta(t)
+            b = dab.dab_estimate_alpha_beta_noalloc(t, dab.estimate_outputs(F, t.device))
+            torch.cuda.synchronize()
+            for k in a:
+                assert torch.equal(a[k], b[k]), (k, F, n)
