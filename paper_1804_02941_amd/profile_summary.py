@@ -145,7 +145,7 @@ def main():
              "<false, false, 2, 4, 4> grid 16384 fc7.  The other rows belong to the measurements beside the headline: the separate",
              "calls of the stage table, the chain that hands bits on (product kernels whose BITS argument is true), the training side, the",
              "weights-only layers (wbin_prepare_kernel, binconv_mfma_kernel<8, 0, 1>), configurations 2, 4 and 5 (config 5's",
-             "weight sides are the launches with grid 2097152), batch 32, and the popcount-rate probe.", "",
+             "weight sides are the binarize_rows_kernel launches with grids 2097152 and 1048576), batch 32, and the popcount-rate probe.", "",
              "| kernel | grid | workgroup | launches | average us | min us | max us |", "|---|---|---|---|---|---|---|"]
     for (k, grid, wg), v in dur.items():
         lines.append(f"| `{k}` | {grid} | {wg} | {len(v)} | {sum(v) / len(v):.2f} | {min(v):.2f} | {max(v):.2f} |")
