@@ -32,6 +32,7 @@
 namespace dab {
 
 constexpr int kDirNTile = 128;              // filters per workgroup
+constexpr int kDirGroupTable = 64;          // >= load groups of a tile (36) + two rounds of lookahead
 constexpr uint32_t kOob = 0x7FFFFFF0u;      // a buffer offset past every tensor: such loads return 0
 
 // bit 4i + d of x -> sign bit of nibble i of dword d, magnitude 1.0: the A fragment of 32 channels.
@@ -145,6 +146,11 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
     extern __shared__ __align__(16) uint4 panel[];                 // [n_ent][4][64 lanes] 16-byte groups; entries from nk on are zero
     __shared__ __align__(16) float sA_lds[8][64];                  // row sums of each wavefront's 64 pixels
     __shared__ __align__(16) float col_lds[3][kDirNTile];                        // beta - alpha, beta, tau of the tile's columns
+    // The load groups of a tile in order: .x byte offset of the group inside the window (kOob past
+    // the last one), .y its tap, and bit 8 where the upper half's word does not exist (the last group
+    // of a tap with an odd number of words).  Read one group ahead by every lane (same address: a
+    // broadcast), in place of a cursor of five scalar registers advanced by selects at every load.
+    __shared__ uint2 gtab[kDirGroupTable];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -196,6 +202,16 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
         }
     }
 
+    if (tid < kDirGroupTable) {
+        uint2 e = make_uint2(kOob, 0u);
+        if (tid < g.NG) {
+            const int tap = tid / g.G, jg = tid - tap * g.G;
+            const int ky = tap / g.kw, kx = tap - ky * g.kw;
+            e.x = static_cast<uint32_t>(((ky * g.W + kx) * g.Cw + jg * LW) * 4);
+            e.y = static_cast<uint32_t>(tap) | ((g.odd && jg == g.G - 1) ? 256u : 0u);
+        }
+        gtab[tid] = e;
+    }
     // scalars of the tile's 128 columns, kept in LDS (not in registers through the reduction loop)
     if (tid < kDirNTile) {
         const int f = min(f0 + tid, g.F - 1);                      // (in filter order; the epilogues index accordingly)
@@ -264,30 +280,24 @@ __global__ __launch_bounds__(512) void binconv_direct_kernel(const DirectGeom g,
             // ---- the reduction.  Load groups run over (tap, word group); group gi covers k-steps
             // gi*LW .. gi*LW + LW-1.  PF groups are in flight; the slot emptied by the previous
             // group is refilled during this one.  Groups past the end load nothing (zeros) and
-            // meet zero entries of the panel.  The cursors are wavefront-uniform and advance by
-            // selects, so a round of PF groups is one basic block.
+            // meet zero entries of the panel.  Where a group lies comes from the table in LDS; the
+            // consume cursor is wavefront-uniform and advances by selects, so a round of PF groups
+            // is one basic block.
             typename WordsOf<LW>::type xq[PF][2];
-            int l_g = 0, l_tap = 0, l_kx = 0, l_jg = 0;
-            uint32_t l_off = 0;                                    // byte offset of the group inside the window
+            int l_g = 0;
+            uint2 nxt = gtab[0];                                   // the entry of group l_g
             auto issue = [&](int slot) {
-                const uint32_t soff = l_g < g.NG ? l_off : kOob;
+                const uint2 e = nxt;
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    uint32_t voff = base[i] + soff;
-                    if (PAD) voff = ((tbits[i] >> (l_tap & 31)) & 1u) ? voff : kOob;
+                    uint32_t voff = base[i] + e.x;
+                    if (PAD) voff = ((tbits[i] >> (e.y & 31u)) & 1u) ? voff : kOob;
                     // an odd number of words per pixel: the upper half's last word does not exist
-                    if (LW == 1) voff = (g.odd && h == 1 && l_jg == g.G - 1) ? kOob : voff;
+                    if (LW == 1) voff = (h == 1 && (e.y & 256u)) ? kOob : voff;
                     load_words<LW>(xq[slot][i], arsrc, voff);
                 }
                 ++l_g;
-                ++l_jg;
-                const bool wrap = l_jg == g.G;                     // on to the next tap
-                l_jg = wrap ? 0 : l_jg;
-                l_tap += wrap ? 1 : 0;
-                l_kx += wrap ? 1 : 0;
-                const bool wrap2 = l_kx == g.kw;                   // on to the next row of the window
-                l_kx = wrap2 ? 0 : l_kx;
-                l_off += wrap2 ? g.step_ky : (wrap ? g.step_kx : static_cast<uint32_t>(LW * 4));
+                nxt = gtab[l_g];
             };
 #pragma unroll
             for (int d = 0; d < PF - 1; ++d) issue(d);
