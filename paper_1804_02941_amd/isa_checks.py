@@ -27,12 +27,12 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 
 
-def compile_to_isa(source: str, out: str) -> None:
+def compile_to_isa(source: str, out: str, extra=()) -> None:
     """hipcc -S of one translation unit of csrc/ for gfx950 (the flags of build.py that shape the code)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fno-gpu-rdc", "-ffp-contract=off",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-S", "--cuda-device-only", os.path.join(CSRC, source), "-o", out]
+           *extra, "-S", "--cuda-device-only", os.path.join(CSRC, source), "-o", out]
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
         raise RuntimeError("hipcc -S failed:\n" + proc.stdout)
@@ -173,6 +173,92 @@ def scalar_read_hazards(lines):
     return bad
 
 
+def reads_before_any_write(lines):
+    """Violations [(instruction index, text, registers)] of one kernel: a vector register read that is not written
+    on every path from the kernel's entry (v0, the work-item id, is set at entry).  A partial write (under any EXEC
+    or DPP mask) counts as a write, so only registers wholly unwritten on some path are reported; a DPP
+    instruction whose row or bank mask is not all ones or that has no bound_ctrl, v_writelane and the
+    multiply-accumulate forms read their destination's old value."""
+    insns, labels = _instructions(lines)
+    n = len(insns)
+    succ = [[] for _ in range(n)]
+    for k, (_, t, _) in enumerate(insns):
+        op = t.split()[0]
+        if op == "s_endpgm":
+            continue
+        if op == "s_branch":
+            succ[k].append(labels[t.split()[1]])
+            continue
+        m = re.match(r"s_cbranch_\w+\s+(\.LBB\d+_\d+)", t)
+        if m:
+            succ[k].append(labels[m.group(1)])
+        if k + 1 < n:
+            succ[k].append(k + 1)
+
+    def reads_writes(t):
+        op = t.split()[0]
+        parts = [p.strip() for p in t[len(op):].split(",")]
+        reads, writes = set(), set()
+        memory = op.startswith(("ds_", "buffer_", "global_", "flat_", "scratch_"))
+        if not (op.startswith("v_") or memory):
+            return reads, writes
+        no_result = ("store" in op or op.startswith("ds_write") or
+                     (op.startswith("ds_") and not op.startswith("ds_read") and "rtn" not in op and "permute" not in op))
+        if op.startswith(("v_cmp", "v_readfirstlane", "v_readlane")):
+            for q in parts[1:]:
+                reads |= _vregs(q)
+        elif no_result:
+            for q in parts:
+                reads |= _vregs(q)
+        else:
+            writes |= _vregs(parts[0])
+            for q in parts[1:]:
+                reads |= _vregs(q)
+            dpp = "_dpp" in op or "row_" in t or "quad_perm" in t
+            keeps_old = dpp and (("row_mask" in t and "row_mask:0xf" not in t) or ("bank_mask" in t and "bank_mask:0xf" not in t)
+                                 or "bound_ctrl" not in t)
+            if keeps_old or op.startswith(("v_writelane", "v_mac", "v_fmac")):
+                reads |= _vregs(parts[0])
+        return reads, writes
+
+    defined = [None] * n
+    defined[0] = frozenset({0})
+    work, seen_bad = [0], {}
+    while work:
+        k = work.pop()
+        r, w = reads_writes(insns[k][1])
+        if r - defined[k]:
+            seen_bad[k] = r
+        out = defined[k] | frozenset(w)
+        for s2 in succ[k]:
+            new = out if defined[s2] is None else defined[s2] & out
+            if new != defined[s2]:
+                defined[s2] = new
+                work.append(s2)
+    return [(k, insns[k][1], sorted(r - defined[k])) for k, r in sorted(seen_bad.items()) if r - defined[k]]
+
+
+def check_estimators_without_the_reserved_register(verbose=True):
+    """The sort kernels as they are allocated without DAB_RESERVE_VGPRS (57-64 registers: the allocation whose
+    results were wrong on the GPU): no register read before any write; returns the number of violations."""
+    total = 0
+    with tempfile.TemporaryDirectory() as tmp:
+        isa = os.path.join(tmp, "estimate.s")
+        compile_to_isa("estimate.hip", isa, ["-DDAB_NO_RESERVE_VGPRS"])
+        for name, lines in kernels(open(isa).read()):
+            if "estimate_kernel" not in name:
+                continue
+            v = reads_before_any_write(lines)
+            total += len(v)
+            if verbose and v:
+                print(name)
+                for item in v[:8]:
+                    print("   ", item)
+    if verbose:
+        print("reads before any write:", total)
+    return total
+
+
 def check_sources(verbose=True):
     """Compiles the two translation units with inline assembly and runs both checks; returns the number of violations."""
     total = 0
@@ -195,4 +281,4 @@ def check_sources(verbose=True):
 
 
 if __name__ == "__main__":
-    sys.exit(1 if check_sources() else 0)
+    sys.exit(1 if check_sources() + check_estimators_without_the_reserved_register() else 0)

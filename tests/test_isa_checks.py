@@ -51,3 +51,26 @@ def test_the_in_flight_check_sees_a_use_before_the_wait():
     assert len(ic.loads_in_flight(lines)) == 1                      # vmcnt(2) leaves both loads pending
     (name, lines), = ic.kernels(IN_FLIGHT.format(n=1))
     assert ic.loads_in_flight(lines) == []                          # the older load has landed
+
+
+def test_the_sort_kernels_at_their_64_register_allocation_read_no_register_before_it_is_written():
+    assert ic.check_estimators_without_the_reserved_register(verbose=True) == 0
+
+
+UNWRITTEN = """
+_ZN3dab4demoEv:
+	v_mov_b32_e32 v1, 0
+	s_cbranch_scc1 .LBB0_2
+	v_mov_b32_e32 v2, 1
+.LBB0_2:
+	v_mov_b32_dpp v1, v0 row_shr:1 row_mask:0xf bank_mask:0xf
+	v_add_u32_e32 v3, v1, v2
+	s_endpgm
+.Lfunc_end0:
+"""
+
+
+def test_the_read_before_write_check_sees_a_register_set_on_one_path_only():
+    (name, lines), = ic.kernels(UNWRITTEN)
+    bad = ic.reads_before_any_write(lines)
+    assert len(bad) == 1 and bad[0][2] == [2]                      # v2 is set only when the branch is not taken
