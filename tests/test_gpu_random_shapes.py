@@ -14,11 +14,13 @@ import torch
 from paper_1804_02941_amd import binding as dab
 from paper_1804_02941_amd import workloads as wl
 
+from oracle import packing as opk
 from oracle import training as otr
 
 import gpu_util as gu
 from test_gpu_parity import weight_rows
 from test_gpu_training import check_bounded
+from test_gpu_fullsize import _structured_masks
 
 pytestmark = pytest.mark.gpu
 
@@ -197,3 +199,57 @@ def test_random_rows_through_the_estimators():
             torch.cuda.synchronize()
             for k in a:
                 assert torch.equal(a[k], b[k]), (k, F, n)
+
+
+def test_random_mid_sized_layers_whole_tensor_against_closed_forms():
+    """Thousands to a hundred thousand pixels (many tiles of the persistent kernel, ragged last tiles), every
+    output of the fp32 and of the packed-sign launch against values built with numpy indexing only: masks
+    that select whole windows, single weights, channel ranges or tap rows make s1 a difference of channel
+    prefix sums, and alpha = 1.5, beta = 0.5 make y = s1 + sA / 2 exact in fp32 (so the signs are fixed too)."""
+    rng = np.random.default_rng(20245)
+    done = 0
+    while done < 30:
+        k = int(rng.choice([1, 3, 5, 7]))
+        kh, kw = k, int(rng.choice([k, max(1, k - 2)]))
+        C = int(rng.choice([32, 48, 64, 70, 96, 128, 160, 256, 300, 512, 1024]))
+        F, B = int(rng.integers(1, 400)), int(rng.choice([1, 3, 8, 32, 64, 128, 256]))
+        H, W = int(rng.integers(kh, 64)), int(rng.integers(kw, 64))
+        pad = int(rng.integers(0, min(kh, kw) + 1)) if 1 < kh * kw <= 32 else 0
+        stride = int(rng.integers(1, 4))
+        L = wl.Layer(f"closed{done}", C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
+        M = B * L.Ho * L.Wo
+        if M * F > 4e7 or B * C * H * W > 6e7 or M < 2000:
+            continue
+        shape = dict(B=B, C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
+        a = (rng.integers(0, 2, size=(B, C, H, W), dtype=np.int8) * 2 - 1)
+        e, spec = _structured_masks(L, rng)
+        A = gu.to_gpu(opk.pack_activations(a).view(np.int32)).reshape(B, H, W, -1)
+        E = gu.to_gpu(opk.pack_weights(e)[0].view(np.int32))
+        alpha = torch.full((F,), 1.5, dtype=torch.float32, device="cuda:0")
+        beta = torch.full((F,), 0.5, dtype=torch.float32, device="cuda:0")
+        tau_np = (rng.integers(-6, 7, size=F) * 0.5).astype(np.float32)
+        d = dab.dab_conv_desc(B, C, H, W, F, kh, kw, pad, pad, stride, stride)
+        Y = dab.dab_binconv2d(d, A, E, alpha, beta)
+        bits = dab.dab_binconv2d_bits(d, A, E, alpha, beta, gu.to_gpu(tau_np))
+        torch.cuda.synchronize()
+        cp = np.zeros((B, C + 1, H + 2 * pad, W + 2 * pad), dtype=np.int32)          # channel prefix sums, zero border
+        np.cumsum(a, axis=1, dtype=np.int32, out=cp[:, 1:, pad:pad + H, pad:pad + W])
+
+        def window_sum(plane, taps):
+            out = np.zeros((B, L.Ho, L.Wo), dtype=np.int32)
+            for (i, j) in taps:
+                out += plane[:, i:i + stride * (L.Ho - 1) + 1:stride, j:j + stride * (L.Wo - 1) + 1:stride]
+            return out
+
+        sA = window_sum(cp[:, C], [(i, j) for i in range(kh) for j in range(kw)])
+        want, cache = np.empty((B, L.Ho, L.Wo, F), np.float32), {}
+        for f, (c0, c1, taps) in enumerate(spec):
+            key = (c0, c1, tuple(taps))
+            if key not in cache:
+                cache[key] = window_sum(cp[:, c1] - cp[:, c0], taps)
+            want[..., f] = cache[key].astype(np.float32) + 0.5 * sA.astype(np.float32)
+        assert np.array_equal(Y.cpu().numpy().reshape(want.shape), want), shape
+        signs = np.where(want >= tau_np, 1, -1).astype(np.int8)
+        want_bits = opk.pack_activations(np.transpose(signs, (0, 3, 1, 2)))
+        assert np.array_equal(gu.u32(bits).reshape(want_bits.shape), want_bits), shape
+        done += 1
