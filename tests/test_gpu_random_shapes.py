@@ -201,11 +201,47 @@ def test_random_rows_through_the_estimators():
                 assert torch.equal(a[k], b[k]), (k, F, n)
 
 
+def closed_form_check(rng, B, C, H, W, F, kh, kw, pad, stride):
+    """Every output of the fp32 and of the packed-sign launch of one layer against values built with numpy indexing
+    only: masks that select whole windows, single weights, channel ranges or tap rows make s1 a difference of
+    channel prefix sums, and alpha = 1.5, beta = 0.5 make y = s1 + sA / 2 exact in fp32 (so the signs are fixed too)."""
+    L = wl.Layer("closed", C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
+    shape = dict(B=B, C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
+    a = (rng.integers(0, 2, size=(B, C, H, W), dtype=np.int8) * 2 - 1)
+    e, spec = _structured_masks(L, rng)
+    A = gu.to_gpu(opk.pack_activations(a).view(np.int32)).reshape(B, H, W, -1)
+    E = gu.to_gpu(opk.pack_weights(e)[0].view(np.int32))
+    alpha = torch.full((F,), 1.5, dtype=torch.float32, device="cuda:0")
+    beta = torch.full((F,), 0.5, dtype=torch.float32, device="cuda:0")
+    tau_np = (rng.integers(-6, 7, size=F) * 0.5).astype(np.float32)
+    d = dab.dab_conv_desc(B, C, H, W, F, kh, kw, pad, pad, stride, stride)
+    Y = dab.dab_binconv2d(d, A, E, alpha, beta)
+    bits = dab.dab_binconv2d_bits(d, A, E, alpha, beta, gu.to_gpu(tau_np))
+    torch.cuda.synchronize()
+    cp = np.zeros((B, C + 1, H + 2 * pad, W + 2 * pad), dtype=np.int32)              # channel prefix sums, zero border
+    np.cumsum(a, axis=1, dtype=np.int32, out=cp[:, 1:, pad:pad + H, pad:pad + W])
+
+    def window_sum(plane, taps):
+        out = np.zeros((B, L.Ho, L.Wo), dtype=np.int32)
+        for (i, j) in taps:
+            out += plane[:, i:i + stride * (L.Ho - 1) + 1:stride, j:j + stride * (L.Wo - 1) + 1:stride]
+        return out
+
+    sA = window_sum(cp[:, C], [(i, j) for i in range(kh) for j in range(kw)])
+    want, cache = np.empty((B, L.Ho, L.Wo, F), np.float32), {}
+    for f, (c0, c1, taps) in enumerate(spec):
+        key = (c0, c1, tuple(taps))
+        if key not in cache:
+            cache[key] = window_sum(cp[:, c1] - cp[:, c0], taps)
+        want[..., f] = cache[key].astype(np.float32) + 0.5 * sA.astype(np.float32)
+    assert np.array_equal(Y.cpu().numpy().reshape(want.shape), want), shape
+    signs = np.where(want >= tau_np, 1, -1).astype(np.int8)
+    want_bits = opk.pack_activations(np.transpose(signs, (0, 3, 1, 2)))
+    assert np.array_equal(gu.u32(bits).reshape(want_bits.shape), want_bits), shape
+
+
 def test_random_mid_sized_layers_whole_tensor_against_closed_forms():
-    """Thousands to a hundred thousand pixels (many tiles of the persistent kernel, ragged last tiles), every
-    output of the fp32 and of the packed-sign launch against values built with numpy indexing only: masks
-    that select whole windows, single weights, channel ranges or tap rows make s1 a difference of channel
-    prefix sums, and alpha = 1.5, beta = 0.5 make y = s1 + sA / 2 exact in fp32 (so the signs are fixed too)."""
+    """Thousands to a hundred thousand pixels: many tiles of the persistent kernel, ragged last tiles."""
     rng = np.random.default_rng(20245)
     done = 0
     while done < 30:
@@ -216,40 +252,39 @@ def test_random_mid_sized_layers_whole_tensor_against_closed_forms():
         H, W = int(rng.integers(kh, 64)), int(rng.integers(kw, 64))
         pad = int(rng.integers(0, min(kh, kw) + 1)) if 1 < kh * kw <= 32 else 0
         stride = int(rng.integers(1, 4))
-        L = wl.Layer(f"closed{done}", C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
+        L = wl.Layer("probe", C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
         M = B * L.Ho * L.Wo
         if M * F > 4e7 or B * C * H * W > 6e7 or M < 2000:
             continue
-        shape = dict(B=B, C=C, H=H, W=W, F=F, kh=kh, kw=kw, pad=pad, stride=stride)
-        a = (rng.integers(0, 2, size=(B, C, H, W), dtype=np.int8) * 2 - 1)
-        e, spec = _structured_masks(L, rng)
-        A = gu.to_gpu(opk.pack_activations(a).view(np.int32)).reshape(B, H, W, -1)
-        E = gu.to_gpu(opk.pack_weights(e)[0].view(np.int32))
-        alpha = torch.full((F,), 1.5, dtype=torch.float32, device="cuda:0")
-        beta = torch.full((F,), 0.5, dtype=torch.float32, device="cuda:0")
-        tau_np = (rng.integers(-6, 7, size=F) * 0.5).astype(np.float32)
-        d = dab.dab_conv_desc(B, C, H, W, F, kh, kw, pad, pad, stride, stride)
-        Y = dab.dab_binconv2d(d, A, E, alpha, beta)
-        bits = dab.dab_binconv2d_bits(d, A, E, alpha, beta, gu.to_gpu(tau_np))
-        torch.cuda.synchronize()
-        cp = np.zeros((B, C + 1, H + 2 * pad, W + 2 * pad), dtype=np.int32)          # channel prefix sums, zero border
-        np.cumsum(a, axis=1, dtype=np.int32, out=cp[:, 1:, pad:pad + H, pad:pad + W])
-
-        def window_sum(plane, taps):
-            out = np.zeros((B, L.Ho, L.Wo), dtype=np.int32)
-            for (i, j) in taps:
-                out += plane[:, i:i + stride * (L.Ho - 1) + 1:stride, j:j + stride * (L.Wo - 1) + 1:stride]
-            return out
-
-        sA = window_sum(cp[:, C], [(i, j) for i in range(kh) for j in range(kw)])
-        want, cache = np.empty((B, L.Ho, L.Wo, F), np.float32), {}
-        for f, (c0, c1, taps) in enumerate(spec):
-            key = (c0, c1, tuple(taps))
-            if key not in cache:
-                cache[key] = window_sum(cp[:, c1] - cp[:, c0], taps)
-            want[..., f] = cache[key].astype(np.float32) + 0.5 * sA.astype(np.float32)
-        assert np.array_equal(Y.cpu().numpy().reshape(want.shape), want), shape
-        signs = np.where(want >= tau_np, 1, -1).astype(np.int8)
-        want_bits = opk.pack_activations(np.transpose(signs, (0, 3, 1, 2)))
-        assert np.array_equal(gu.u32(bits).reshape(want_bits.shape), want_bits), shape
+        closed_form_check(rng, B, C, H, W, F, kh, kw, pad, stride)
         done += 1
+
+
+def limit_shapes():
+    """Shapes on both sides of the limits that decide which kernel runs and how it is tiled."""
+    cases = []
+    for C in (224, 256, 288, 320):                                  # reductions around the persistent kernel's 36 k-steps
+        cases.append((8, C, 20, 20, 130, 3, 3, 1, 1))
+    for (kh, kw) in ((4, 8), (3, 11), (5, 7), (6, 6)):              # padded windows around 32 taps
+        cases.append((4, 64, 24, 24, 70, kh, kw, 2, 1))
+    for M in (16352, 16384, 16416):                                 # 511, 512, 513 blocks of 32 x 32
+        cases.append((M // 16, 512, 4, 4, 32, 1, 1, 0, 1))
+    for B in (63, 64, 65, 127, 128, 129, 255, 256, 257):            # block counts around the small-product limits, long reductions
+        cases.append((B, 2304, 1, 1, 1000, 1, 1, 0, 1))
+    for B in (500, 1024, 2048):
+        cases.append((B, 4096, 1, 1, 1030, 1, 1, 0, 1))
+    for (H, W) in ((16, 16), (16, 17), (23, 22), (32, 32)):         # pixel counts around whole tiles of 64 / 256 / 512
+        for B in (1, 2, 31, 32, 33):
+            cases.append((B, 64, H, W, 128, 3, 3, 1, 1))
+    for F in (1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257):   # filter counts around words and 128-filter tiles
+        cases.append((16, 96, 18, 18, F, 3, 3, 1, 1))
+    for pad in (0, 1, 2, 3):                                        # padding up to the kernel extent, strides
+        for stride in (1, 2, 3):
+            cases.append((16, 128, 21, 19, 100, 3, 3, pad, stride))
+    return cases
+
+
+def test_shapes_at_the_kernels_limits_whole_tensor():
+    rng = np.random.default_rng(20246)
+    for case in limit_shapes():
+        closed_form_check(rng, *case)
